@@ -1,0 +1,174 @@
+/*
+ * moe.h - C ABI of the MI355X (gfx950) MoE expert-layer library.
+ *
+ * One top-k Mixture-of-Experts block, forward and backward, as the paper describes it
+ * (arxiv 2504.03871, Section 2.1): a gate scores every expert for each token, the token goes to its
+ * top-k experts, the expert outputs are weighted by the scores and summed.  "Dispatch" groups token
+ * rows by expert, "combine" brings the expert outputs back (Section 2.1, expert parallelism).  Every
+ * call can be restricted to one GPU's share of each expert's tokens, which is how the asymmetric
+ * expert assignment of Section 4.2 appears at this level: a half-open range [lo_e, hi_e) over the
+ * kept-token list of expert e.
+ *
+ * Conventions for every entry point
+ *   - Returns MOE_OK (0) or a negative MOE_ERR_* code.  Arguments are validated before anything is
+ *     launched; on an argument error nothing has been enqueued and no output is touched.
+ *   - `cfg` is a host pointer.  Every other pointer is a DEVICE pointer owned by the caller and must
+ *     be 16-byte aligned; the library allocates nothing, frees nothing and keeps no state between
+ *     calls (except the last HIP error code, per host thread).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is enqueued on
+ *     it; no call synchronises with the host and none reads device memory from the host.
+ *   - Activations (x, x_perm, y_perm, saved, d_out, dy_perm, dx_perm, out, dx) and expert weights
+ *     (W1, W1b, W2) have the storage type cfg->dtype: fp32, or bf16 (round-to-nearest-even) with
+ *     fp32 accumulation.  Router tensors (Wr, bias, logits, topk_w, d_topk_w, d_logits, dWr) and
+ *     expert weight gradients (dW1, dW1b, dW2) are always fp32.  Index tensors are int32.
+ *   - All matrices are dense row-major: x[T][d_model], W1[E][d_model][d_ff], W2[E][d_ff][d_model],
+ *     Wr[d_model][E], topk_*[T][k], permuted buffers [T*k][...].
+ *   - Assignment a = t*k + j is slot j of token t.  Expert e's list holds its assignments in ascending
+ *     token order; the first kept[e] = min(counts[e], capacity) of them own rows
+ *     offsets[e] .. offsets[e]+kept[e]-1 of the permuted buffers; later ones are dropped
+ *     (row_of = -1) and contribute nothing.
+ *   - slice_lo / slice_hi: device int32[E], positions in expert e's kept list that THIS GPU
+ *     computes.  Both NULL = everything.  On the device they are clamped to [0, kept[e]] and an
+ *     inverted range is empty.  Rows of permuted buffers outside the shares are never read for a
+ *     result and never written.
+ *   - Shapes: 1 <= k <= min(E, MOE_MAX_K), E <= MOE_MAX_E, T >= 0 (T = 0 is a no-op),
+ *     T*k <= 2^30.  bf16: d_model and d_ff multiples of 64; fp32: multiples of 4.
+ *   - Calls that use the same workspace or output buffers must not overlap in time.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_API __attribute__((visibility("default")))
+
+#define MOE_MAX_E 256
+#define MOE_MAX_K 8
+
+enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
+enum { MOE_ACT_GELU = 0, MOE_ACT_SWIGLU = 1 };
+
+enum {
+  MOE_OK = 0,
+  MOE_ERR_NULL = -1,      /* a required pointer is NULL */
+  MOE_ERR_BAD_SHAPE = -2, /* T, d_model, d_ff, E, k out of the supported range or misaligned sizes */
+  MOE_ERR_BAD_DTYPE = -3, /* dtype or act not one of the enumerators */
+  MOE_ERR_BAD_SLICE = -4, /* exactly one of slice_lo / slice_hi is NULL */
+  MOE_ERR_ALIGN = -5,     /* a device pointer is not 16-byte aligned */
+  MOE_ERR_HIP = -6        /* a launch failed; see moe_last_hip_error() */
+};
+
+typedef struct moe_cfg {
+  int32_t T;        /* tokens */
+  int32_t d_model;  /* embedding width d */
+  int32_t d_ff;     /* expert hidden width f */
+  int32_t E;        /* experts */
+  int32_t k;        /* experts per token */
+  int32_t dtype;    /* MOE_DTYPE_* : storage type of activations and expert weights */
+  int32_t act;      /* MOE_ACT_GELU: gelu_erf(x W1) W2 ; MOE_ACT_SWIGLU: (silu(x W1) * (x W1b)) W2 */
+  int32_t capacity; /* rows kept per expert; <= 0 = unlimited */
+} moe_cfg;
+
+/* Static text for a return code (never NULL). */
+MOE_API const char* moe_error_string(int code);
+/* hipError_t value of the last failed HIP call made by this host thread (0 if none). */
+MOE_API int moe_last_hip_error(void);
+
+/* Bytes of device workspace `ws` sufficient for every call below with this cfg. */
+MOE_API int moe_workspace_bytes(const moe_cfg* cfg, size_t* bytes);
+/* Bytes of the `saved` buffer of moe_expert_ffn_fwd: (2 for GELU, 3 for SwiGLU) * T*k * d_ff elements. */
+MOE_API int moe_saved_bytes(const moe_cfg* cfg, size_t* bytes);
+
+/*
+ * Gate (Section 2.1: confidence score per expert, top-k).  logits = x Wr (+ bias), fp32 accumulate,
+ * written to logits_out[T][E].  If logits_in is non-NULL the matrix product is skipped and those
+ * logits are used instead (x, Wr may then be NULL).  Selection is made on the fp32 logits as stored:
+ * descending value, equal values by ascending expert id; slot 0 is the best.
+ * topk_w[t][j] = exp(l_j - l_0) / sum_i exp(l_i - l_0) over the k selected logits.
+ * bias[E] may be NULL.  logits_out may be NULL only when logits_in is given.
+ */
+MOE_API int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* bias,
+              const float* logits_in, float* logits_out, int32_t* topk_idx, float* topk_w,
+              void* stream);
+
+/*
+ * Dispatch (Section 2.1: token embeddings go to their experts; locally a stable group-by-expert).
+ * Writes counts[E] (routed), kept[E], offsets[E+1] (exclusive scan of kept), row_of[T*k]
+ * (row of each assignment or -1), src_of[T*k] (assignment of each row, -1 from offsets[E] on) and
+ * gathers x_perm[row] = x[src_of[row] / k] for the rows inside this GPU's shares.
+ * x_perm may be NULL: only the index arrays are produced.
+ */
+MOE_API int moe_dispatch(const moe_cfg* cfg, const void* x, const int32_t* topk_idx,
+                 const int32_t* slice_lo, const int32_t* slice_hi,
+                 int32_t* counts, int32_t* kept, int32_t* offsets, int32_t* row_of, int32_t* src_of,
+                 void* x_perm, void* ws, void* stream);
+
+/*
+ * Expert FFN forward on the in-share rows (Section 2.1: experts are FFNs made of GEMMs).
+ * GELU:   A = x_perm W1[e], H = gelu_erf(A), y_perm = H W2[e];          saved = [A | H]
+ * SwiGLU: G = x_perm W1[e], U = x_perm W1b[e], H = silu(G) * U, y_perm = H W2[e];  saved = [G | U | H]
+ * Each saved plane is [T*k][d_ff] in the storage type.  W1b must be NULL for GELU.
+ */
+MOE_API int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b,
+                       const void* W2, const int32_t* offsets, const int32_t* kept,
+                       const int32_t* slice_lo, const int32_t* slice_hi,
+                       void* saved, void* y_perm, void* ws, void* stream);
+
+/*
+ * Combine (Section 2.1: outputs weighted by the scores and summed).
+ * out[t] = sum over slots j = 0..k-1, in that order, of topk_w[t][j] * y_perm[row_of[t*k+j]],
+ * taking only slots that are kept and inside this GPU's shares; fp32 accumulation.
+ * topk_w == NULL means unit weights (the un-permute of the input gradient).  accumulate != 0 adds
+ * to `out` instead of overwriting it.
+ */
+MOE_API int moe_combine(const moe_cfg* cfg, const void* y_perm, const float* topk_w, const int32_t* topk_idx,
+                const int32_t* row_of, const int32_t* offsets, const int32_t* kept,
+                const int32_t* slice_lo, const int32_t* slice_hi,
+                void* out, int32_t accumulate, void* stream);
+
+/*
+ * Combine backward (Section 5: the gradient of the block output feeds two branches).
+ * For every in-share slot: dy_perm[row] = topk_w[a] * d_out[t] and d_topk_w[a] = <d_out[t], y_perm[row]>;
+ * every other slot gets d_topk_w[a] = 0.
+ */
+MOE_API int moe_combine_bwd(const moe_cfg* cfg, const void* d_out, const void* y_perm, const float* topk_w,
+                    const int32_t* topk_idx, const int32_t* row_of, const int32_t* offsets,
+                    const int32_t* kept, const int32_t* slice_lo, const int32_t* slice_hi,
+                    void* dy_perm, float* d_topk_w, void* stream);
+
+/*
+ * Expert FFN backward on the in-share rows.
+ * dH = dy_perm W2[e]^T;  dW2[e] = H^T dy_perm;
+ * GELU:   dA = dH * gelu'(A);  dW1[e] = x_perm^T dA;  dx_perm = dA W1[e]^T
+ * SwiGLU: dU = dH * silu(G), dG = dH * U * silu'(G);  dW1[e] = x_perm^T dG, dW1b[e] = x_perm^T dU;
+ *         dx_perm = dG W1[e]^T + dU W1b[e]^T
+ * Weight gradients sum over the in-share rows of the expert only; accumulate != 0 adds them to
+ * dW1/dW1b/dW2 instead of overwriting (an expert with an empty share then leaves its gradient as is,
+ * otherwise it is zero-filled).
+ */
+MOE_API int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_perm, const void* saved,
+                       const void* W1, const void* W1b, const void* W2,
+                       const int32_t* offsets, const int32_t* kept,
+                       const int32_t* slice_lo, const int32_t* slice_hi,
+                       void* dx_perm, float* dW1, float* dW1b, float* dW2, int32_t accumulate,
+                       void* ws, void* stream);
+
+/*
+ * Gate backward (Section 5: the branch through the confidence scores to the gate weights and to
+ * the block input, accumulated with the gradient that comes back through the experts).
+ * g = sum_j w_j dw_j;  d_logits[t][e_j] = w_j (dw_j - g), 0 for unselected experts;
+ * dWr = x^T d_logits (overwritten);  dx += d_logits Wr^T (dx may be NULL to skip that part).
+ */
+MOE_API int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx,
+                  const float* topk_w, const float* d_topk_w,
+                  float* d_logits, float* dWr, void* dx, void* ws, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

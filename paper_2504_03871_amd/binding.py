@@ -1,0 +1,152 @@
+"""ctypes binding of the C-ABI MoE library (include/moe.h): argument marshalling only.
+
+Each function has the name and the argument order of its C entry point, takes torch tensors (or
+None for optional pointers) and enqueues on torch's current HIP stream.  No arithmetic of the
+layer happens in Python, and there is no fallback: if the library has not been built, or a call
+returns an error code, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
+
+DTYPE_F32, DTYPE_BF16 = 0, 1
+ACT_GELU, ACT_SWIGLU = 0, 1
+MAX_E, MAX_K = 256, 8
+
+SYMBOLS = ("moe_error_string", "moe_last_hip_error", "moe_workspace_bytes", "moe_saved_bytes", "moe_route",
+           "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
+           "moe_route_bwd")
+
+
+class MoeCfg(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d_model", "d_ff", "E", "k", "dtype", "act", "capacity")]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, fn, code, text, hip):
+        super().__init__(f"{fn} failed: {code} ({text})" + (f", hipError {hip}" if code == -6 else ""))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built (run __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_03871_amd.build`")
+        l = ctypes.CDLL(LIB_PATH)
+        l.moe_error_string.restype = ctypes.c_char_p
+        l.moe_error_string.argtypes = [ctypes.c_int]
+        l.moe_last_hip_error.restype = ctypes.c_int
+        p, i32 = ctypes.c_void_p, ctypes.c_int32
+        cfgp = ctypes.POINTER(MoeCfg)
+        sig = {
+            "moe_workspace_bytes": [cfgp, ctypes.POINTER(ctypes.c_size_t)],
+            "moe_saved_bytes": [cfgp, ctypes.POINTER(ctypes.c_size_t)],
+            "moe_route": [cfgp] + [p] * 8,
+            "moe_dispatch": [cfgp] + [p] * 12,
+            "moe_expert_ffn_fwd": [cfgp] + [p] * 12,
+            "moe_combine": [cfgp] + [p] * 9 + [i32, p],
+            "moe_combine_bwd": [cfgp] + [p] * 12,
+            "moe_expert_ffn_bwd": [cfgp] + [p] * 14 + [i32, p, p],
+            "moe_route_bwd": [cfgp] + [p] * 10,
+        }
+        for name, args in sig.items():
+            fn = getattr(l, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = args
+        _lib = l
+    return _lib
+
+
+def make_cfg(T, d_model, d_ff, E, k, dtype=DTYPE_BF16, act=ACT_GELU, capacity=0) -> MoeCfg:
+    return MoeCfg(int(T), int(d_model), int(d_ff), int(E), int(k), int(dtype), int(act), int(capacity))
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(name, rc):
+    if rc != 0:
+        l = lib()
+        raise MoeError(name, rc, l.moe_error_string(rc).decode(), l.moe_last_hip_error())
+
+
+def moe_workspace_bytes(cfg) -> int:
+    n = ctypes.c_size_t(0)
+    _check("moe_workspace_bytes", lib().moe_workspace_bytes(ctypes.byref(cfg), ctypes.byref(n)))
+    return n.value
+
+
+def moe_saved_bytes(cfg) -> int:
+    n = ctypes.c_size_t(0)
+    _check("moe_saved_bytes", lib().moe_saved_bytes(ctypes.byref(cfg), ctypes.byref(n)))
+    return n.value
+
+
+def moe_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, stream=None):
+    _check("moe_route", lib().moe_route(ctypes.byref(cfg), _ptr(x), _ptr(Wr), _ptr(bias), _ptr(logits_in),
+                                        _ptr(logits_out), _ptr(topk_idx), _ptr(topk_w), _stream() if stream is None else stream))
+
+
+def moe_dispatch(cfg, x, topk_idx, slice_lo, slice_hi, counts, kept, offsets, row_of, src_of, x_perm, ws,
+                 stream=None):
+    _check("moe_dispatch", lib().moe_dispatch(ctypes.byref(cfg), _ptr(x), _ptr(topk_idx), _ptr(slice_lo),
+                                              _ptr(slice_hi), _ptr(counts), _ptr(kept), _ptr(offsets), _ptr(row_of),
+                                              _ptr(src_of), _ptr(x_perm), _ptr(ws), _stream() if stream is None else stream))
+
+
+def moe_expert_ffn_fwd(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, saved, y_perm, ws, stream=None):
+    _check("moe_expert_ffn_fwd", lib().moe_expert_ffn_fwd(ctypes.byref(cfg), _ptr(x_perm), _ptr(W1), _ptr(W1b),
+                                                          _ptr(W2), _ptr(offsets), _ptr(kept), _ptr(slice_lo),
+                                                          _ptr(slice_hi), _ptr(saved), _ptr(y_perm), _ptr(ws),
+                                                          _stream() if stream is None else stream))
+
+
+def moe_combine(cfg, y_perm, topk_w, topk_idx, row_of, offsets, kept, slice_lo, slice_hi, out, accumulate=0,
+                stream=None):
+    _check("moe_combine", lib().moe_combine(ctypes.byref(cfg), _ptr(y_perm), _ptr(topk_w), _ptr(topk_idx),
+                                            _ptr(row_of), _ptr(offsets), _ptr(kept), _ptr(slice_lo), _ptr(slice_hi),
+                                            _ptr(out), int(accumulate), _stream() if stream is None else stream))
+
+
+def moe_combine_bwd(cfg, d_out, y_perm, topk_w, topk_idx, row_of, offsets, kept, slice_lo, slice_hi, dy_perm,
+                    d_topk_w, stream=None):
+    _check("moe_combine_bwd", lib().moe_combine_bwd(ctypes.byref(cfg), _ptr(d_out), _ptr(y_perm), _ptr(topk_w),
+                                                    _ptr(topk_idx), _ptr(row_of), _ptr(offsets), _ptr(kept),
+                                                    _ptr(slice_lo), _ptr(slice_hi), _ptr(dy_perm), _ptr(d_topk_w),
+                                                    _stream() if stream is None else stream))
+
+
+def moe_expert_ffn_bwd(cfg, dy_perm, x_perm, saved, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, dx_perm, dW1,
+                       dW1b, dW2, accumulate, ws, stream=None):
+    _check("moe_expert_ffn_bwd", lib().moe_expert_ffn_bwd(ctypes.byref(cfg), _ptr(dy_perm), _ptr(x_perm), _ptr(saved),
+                                                          _ptr(W1), _ptr(W1b), _ptr(W2), _ptr(offsets), _ptr(kept),
+                                                          _ptr(slice_lo), _ptr(slice_hi), _ptr(dx_perm), _ptr(dW1),
+                                                          _ptr(dW1b), _ptr(dW2), int(accumulate), _ptr(ws),
+                                                          _stream() if stream is None else stream))
+
+
+def moe_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, ws, stream=None):
+    _check("moe_route_bwd", lib().moe_route_bwd(ctypes.byref(cfg), _ptr(x), _ptr(Wr), _ptr(topk_idx), _ptr(topk_w),
+                                                _ptr(d_topk_w), _ptr(d_logits), _ptr(dWr), _ptr(dx), _ptr(ws),
+                                                _stream() if stream is None else stream))

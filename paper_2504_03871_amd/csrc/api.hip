@@ -1,0 +1,261 @@
+// C ABI of the MoE library: argument validation, workspace layout, kernel sequencing.
+#include "common.h"
+#include "gemm.h"
+
+namespace moe {
+
+static thread_local int g_last_hip_error = 0;
+int set_hip_error(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return MOE_ERR_HIP;
+}
+
+int check_cfg(const moe_cfg* c) {
+  if (c == nullptr) return MOE_ERR_NULL;
+  if (c->dtype != MOE_DTYPE_F32 && c->dtype != MOE_DTYPE_BF16) return MOE_ERR_BAD_DTYPE;
+  if (c->act != MOE_ACT_GELU && c->act != MOE_ACT_SWIGLU) return MOE_ERR_BAD_DTYPE;
+  if (c->T < 0 || c->d_model <= 0 || c->d_ff <= 0) return MOE_ERR_BAD_SHAPE;
+  if (c->E < 1 || c->E > MOE_MAX_E) return MOE_ERR_BAD_SHAPE;
+  if (c->k < 1 || c->k > MOE_MAX_K || c->k > c->E) return MOE_ERR_BAD_SHAPE;
+  const int mult = (c->dtype == MOE_DTYPE_BF16) ? 64 : 4;
+  if (c->d_model % mult != 0 || c->d_ff % mult != 0) return MOE_ERR_BAD_SHAPE;
+  if ((long long)c->T * c->k > (1ll << 30)) return MOE_ERR_BAD_SHAPE;
+  return MOE_OK;
+}
+
+WsLayout ws_layout(const moe_cfg* c) {
+  WsLayout w;
+  const size_t A = (size_t)c->T * c->k;
+  size_t off = 0;
+  w.dispatch_blk_cnt = off;
+  off += align_up(((A + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK) * (size_t)c->E * 4, 256);
+  w.tile_map = off;
+  off += align_up(16 + (size_t)max_row_tiles((int)A, c->E, TILE_ROWS_MIN) * sizeof(RowTile), 256);
+  w.route_partials = off;
+  off += align_up(((size_t)(c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS) * c->d_model * c->E * 4, 256);
+  w.ffn_bwd_dact = off;
+  off += align_up((c->act == MOE_ACT_SWIGLU ? 2 : 1) * A * c->d_ff * elt_size(c), 256);
+  w.total = off;
+  return w;
+}
+
+// defined in the kernel files
+int launch_route(const moe_cfg*, const void*, const float*, const float*, const float*, float*, int32_t*, float*, hipStream_t);
+int launch_route_bwd(const moe_cfg*, const void*, const float*, const int32_t*, const float*, const float*, float*,
+                     float*, void*, float*, hipStream_t);
+int launch_dispatch(const moe_cfg*, const void*, const int32_t*, const int32_t*, const int32_t*, int32_t*, int32_t*,
+                    int32_t*, int32_t*, int32_t*, void*, int32_t*, hipStream_t);
+int launch_combine(const moe_cfg*, const void*, const float*, const int32_t*, const int32_t*, const int32_t*,
+                   const int32_t*, const int32_t*, const int32_t*, void*, int, hipStream_t);
+int launch_combine_bwd(const moe_cfg*, const void*, const void*, const float*, const int32_t*, const int32_t*,
+                       const int32_t*, const int32_t*, const int32_t*, const int32_t*, void*, float*, hipStream_t);
+
+__global__ void fill_zero_kernel(float* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+static int check_slices(const int32_t* lo, const int32_t* hi) {
+  return ((lo == nullptr) != (hi == nullptr)) ? MOE_ERR_BAD_SLICE : MOE_OK;
+}
+
+static int launch_gemm(const moe_cfg* c, int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles,
+                       hipStream_t s) {
+  return c->dtype == MOE_DTYPE_BF16 ? launch_gemm_bf16(mode, epi, dual, chain, g, max_tiles, s)
+                                    : launch_gemm_f32(mode, epi, dual, chain, g, max_tiles, s);
+}
+static int tile_rows_for(const moe_cfg* c) { return c->dtype == MOE_DTYPE_BF16 ? gemm_bf16_tile_rows() : 64; }
+
+}  // namespace moe
+
+using namespace moe;
+
+#define REQUIRE(p) do { if ((p) == nullptr) return MOE_ERR_NULL; } while (0)
+#define ALIGNED(p) do { if (misaligned(p)) return MOE_ERR_ALIGN; } while (0)
+#define CHECK(expr) do { int rc_ = (expr); if (rc_ != MOE_OK) return rc_; } while (0)
+
+extern "C" {
+
+const char* moe_error_string(int code) {
+  switch (code) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_NULL: return "a required pointer is NULL";
+    case MOE_ERR_BAD_SHAPE: return "unsupported shape (T, d_model, d_ff, E or k)";
+    case MOE_ERR_BAD_DTYPE: return "unknown dtype or activation";
+    case MOE_ERR_BAD_SLICE: return "slice_lo and slice_hi must both be given or both be NULL";
+    case MOE_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case MOE_ERR_HIP: return "HIP launch failed (see moe_last_hip_error)";
+    default: return "unknown error code";
+  }
+}
+
+int moe_last_hip_error(void) { return g_last_hip_error; }
+
+int moe_workspace_bytes(const moe_cfg* cfg, size_t* bytes) {
+  CHECK(check_cfg(cfg));
+  REQUIRE(bytes);
+  *bytes = ws_layout(cfg).total;
+  return MOE_OK;
+}
+
+int moe_saved_bytes(const moe_cfg* cfg, size_t* bytes) {
+  CHECK(check_cfg(cfg));
+  REQUIRE(bytes);
+  *bytes = (size_t)(cfg->act == MOE_ACT_SWIGLU ? 3 : 2) * cfg->T * cfg->k * cfg->d_ff * elt_size(cfg);
+  return MOE_OK;
+}
+
+int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* bias, const float* logits_in,
+              float* logits_out, int32_t* topk_idx, float* topk_w, void* stream) {
+  CHECK(check_cfg(cfg));
+  if (logits_in == nullptr) { REQUIRE(x); REQUIRE(Wr); REQUIRE(logits_out); }
+  REQUIRE(topk_idx);
+  REQUIRE(topk_w);
+  ALIGNED(x); ALIGNED(Wr); ALIGNED(bias); ALIGNED(logits_in); ALIGNED(logits_out); ALIGNED(topk_idx); ALIGNED(topk_w);
+  if (cfg->T == 0) return MOE_OK;
+  return launch_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, (hipStream_t)stream);
+}
+
+int moe_dispatch(const moe_cfg* cfg, const void* x, const int32_t* topk_idx, const int32_t* slice_lo,
+                 const int32_t* slice_hi, int32_t* counts, int32_t* kept, int32_t* offsets, int32_t* row_of,
+                 int32_t* src_of, void* x_perm, void* ws, void* stream) {
+  CHECK(check_cfg(cfg));
+  CHECK(check_slices(slice_lo, slice_hi));
+  REQUIRE(topk_idx); REQUIRE(counts); REQUIRE(kept); REQUIRE(offsets); REQUIRE(row_of); REQUIRE(src_of); REQUIRE(ws);
+  if (x_perm != nullptr) REQUIRE(x);
+  ALIGNED(x); ALIGNED(topk_idx); ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(counts); ALIGNED(kept);
+  ALIGNED(offsets); ALIGNED(row_of); ALIGNED(src_of); ALIGNED(x_perm); ALIGNED(ws);
+  const WsLayout w = ws_layout(cfg);
+  int32_t* blk_cnt = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + w.dispatch_blk_cnt);
+  // T == 0 still has to produce zero counts and offsets: the kernels handle an empty assignment list
+  return launch_dispatch(cfg, x, topk_idx, slice_lo, slice_hi, counts, kept, offsets, row_of, src_of, x_perm, blk_cnt,
+                         (hipStream_t)stream);
+}
+
+int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b, const void* W2,
+                       const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo, const int32_t* slice_hi,
+                       void* saved, void* y_perm, void* ws, void* stream) {
+  CHECK(check_cfg(cfg));
+  CHECK(check_slices(slice_lo, slice_hi));
+  REQUIRE(x_perm); REQUIRE(W1); REQUIRE(W2); REQUIRE(offsets); REQUIRE(kept); REQUIRE(saved); REQUIRE(y_perm); REQUIRE(ws);
+  const bool swiglu = cfg->act == MOE_ACT_SWIGLU;
+  if (swiglu) REQUIRE(W1b);
+  if (!swiglu && W1b != nullptr) return MOE_ERR_BAD_DTYPE;
+  ALIGNED(x_perm); ALIGNED(W1); ALIGNED(W1b); ALIGNED(W2); ALIGNED(offsets); ALIGNED(kept); ALIGNED(slice_lo);
+  ALIGNED(slice_hi); ALIGNED(saved); ALIGNED(y_perm); ALIGNED(ws);
+  if (cfg->T == 0) return MOE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const WsLayout w = ws_layout(cfg);
+  const int A = cfg->T * cfg->k, d = cfg->d_model, f = cfg->d_ff;
+  const int tr = tile_rows_for(cfg), max_tiles = max_row_tiles(A, cfg->E, tr);
+  TileMap map = tile_map_at(static_cast<char*>(ws) + w.tile_map);
+  CHECK(launch_tile_map(offsets, kept, slice_lo, slice_hi, cfg->E, tr, map, s));
+  const size_t plane = (size_t)A * f * elt_size(cfg);
+  char* sv = static_cast<char*>(saved);
+  GemmArgs g = {};
+  g.tiles = map.tiles; g.ntiles = map.header;
+  g.offsets = offsets; g.kept = kept; g.lo = slice_lo; g.hi = slice_hi; g.E = cfg->E;
+  // hidden = act(x_perm W1)
+  g.A = x_perm; g.B = W1; g.B2 = W1b; g.N = f; g.K = d;
+  g.C = sv; g.C2 = sv + plane; g.C3 = sv + 2 * plane;
+  CHECK(launch_gemm(cfg, MODE_NN, swiglu ? EPI_SWIGLU_FWD : EPI_GELU_FWD, swiglu, false, g, max_tiles, s));
+  // y = hidden W2
+  g.A = swiglu ? sv + 2 * plane : sv + plane; g.B = W2; g.B2 = nullptr; g.N = d; g.K = f;
+  g.C = y_perm; g.C2 = g.C3 = nullptr;
+  return launch_gemm(cfg, MODE_NN, EPI_STORE, false, false, g, max_tiles, s);
+}
+
+int moe_combine(const moe_cfg* cfg, const void* y_perm, const float* topk_w, const int32_t* topk_idx,
+                const int32_t* row_of, const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo,
+                const int32_t* slice_hi, void* out, int32_t accumulate, void* stream) {
+  CHECK(check_cfg(cfg));
+  CHECK(check_slices(slice_lo, slice_hi));
+  REQUIRE(y_perm); REQUIRE(topk_idx); REQUIRE(row_of); REQUIRE(offsets); REQUIRE(kept); REQUIRE(out);
+  ALIGNED(y_perm); ALIGNED(topk_w); ALIGNED(topk_idx); ALIGNED(row_of); ALIGNED(offsets); ALIGNED(kept);
+  ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(out);
+  if (cfg->T == 0) return MOE_OK;
+  return launch_combine(cfg, y_perm, topk_w, topk_idx, row_of, offsets, kept, slice_lo, slice_hi, out, accumulate,
+                        (hipStream_t)stream);
+}
+
+int moe_combine_bwd(const moe_cfg* cfg, const void* d_out, const void* y_perm, const float* topk_w,
+                    const int32_t* topk_idx, const int32_t* row_of, const int32_t* offsets, const int32_t* kept,
+                    const int32_t* slice_lo, const int32_t* slice_hi, void* dy_perm, float* d_topk_w, void* stream) {
+  CHECK(check_cfg(cfg));
+  CHECK(check_slices(slice_lo, slice_hi));
+  REQUIRE(d_out); REQUIRE(y_perm); REQUIRE(topk_w); REQUIRE(topk_idx); REQUIRE(row_of); REQUIRE(offsets);
+  REQUIRE(kept); REQUIRE(dy_perm); REQUIRE(d_topk_w);
+  ALIGNED(d_out); ALIGNED(y_perm); ALIGNED(topk_w); ALIGNED(topk_idx); ALIGNED(row_of); ALIGNED(offsets);
+  ALIGNED(kept); ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(dy_perm); ALIGNED(d_topk_w);
+  if (cfg->T == 0) return MOE_OK;
+  return launch_combine_bwd(cfg, d_out, y_perm, topk_w, topk_idx, row_of, offsets, kept, slice_lo, slice_hi, dy_perm,
+                            d_topk_w, (hipStream_t)stream);
+}
+
+int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_perm, const void* saved, const void* W1,
+                       const void* W1b, const void* W2, const int32_t* offsets, const int32_t* kept,
+                       const int32_t* slice_lo, const int32_t* slice_hi, void* dx_perm, float* dW1, float* dW1b,
+                       float* dW2, int32_t accumulate, void* ws, void* stream) {
+  CHECK(check_cfg(cfg));
+  CHECK(check_slices(slice_lo, slice_hi));
+  REQUIRE(dy_perm); REQUIRE(x_perm); REQUIRE(saved); REQUIRE(W1); REQUIRE(W2); REQUIRE(offsets); REQUIRE(kept);
+  REQUIRE(dx_perm); REQUIRE(dW1); REQUIRE(dW2); REQUIRE(ws);
+  const bool swiglu = cfg->act == MOE_ACT_SWIGLU;
+  if (swiglu) { REQUIRE(W1b); REQUIRE(dW1b); }
+  if (!swiglu && (W1b != nullptr || dW1b != nullptr)) return MOE_ERR_BAD_DTYPE;
+  ALIGNED(dy_perm); ALIGNED(x_perm); ALIGNED(saved); ALIGNED(W1); ALIGNED(W1b); ALIGNED(W2); ALIGNED(offsets);
+  ALIGNED(kept); ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(dx_perm); ALIGNED(dW1); ALIGNED(dW1b); ALIGNED(dW2);
+  ALIGNED(ws);
+  if (cfg->T == 0) return MOE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const WsLayout w = ws_layout(cfg);
+  const int A = cfg->T * cfg->k, d = cfg->d_model, f = cfg->d_ff;
+  const int tr = tile_rows_for(cfg), max_tiles = max_row_tiles(A, cfg->E, tr);
+  TileMap map = tile_map_at(static_cast<char*>(ws) + w.tile_map);
+  CHECK(launch_tile_map(offsets, kept, slice_lo, slice_hi, cfg->E, tr, map, s));
+  const size_t plane = (size_t)A * f * elt_size(cfg);
+  const char* sv = static_cast<const char*>(saved);
+  char* dact = static_cast<char*>(ws) + w.ffn_bwd_dact;
+  const void* hidden = swiglu ? sv + 2 * plane : sv + plane;
+  GemmArgs g = {};
+  g.tiles = map.tiles; g.ntiles = map.header;
+  g.offsets = offsets; g.kept = kept; g.lo = slice_lo; g.hi = slice_hi; g.E = cfg->E;
+  g.accumulate = accumulate;
+  // dH = dy W2^T, fused with the activation derivative -> dA (GELU) or dG, dU (SwiGLU)
+  g.A = dy_perm; g.B = W2; g.N = f; g.K = d;
+  g.C = dact; g.C2 = dact + plane; g.S1 = sv; g.S2 = sv + plane;
+  CHECK(launch_gemm(cfg, MODE_NT, swiglu ? EPI_SWIGLU_BWD : EPI_GELU_BWD, false, false, g, max_tiles, s));
+  // dW2[e] = H^T dy
+  g.A = hidden; g.B = dy_perm; g.M = f; g.N = d; g.K = 0; g.C = dW2; g.C2 = nullptr; g.S1 = g.S2 = nullptr;
+  CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+  // dW1[e] = x_perm^T dA   (SwiGLU: dW1 from dG, dW1b from dU)
+  g.A = x_perm; g.B = dact; g.M = d; g.N = f; g.C = dW1;
+  CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+  if (swiglu) {
+    g.B = dact + plane; g.C = dW1b;
+    CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+  }
+  // dx_perm = dA W1^T   (SwiGLU: dG W1^T + dU W1b^T)
+  g.A = dact; g.A2 = dact + plane; g.B = W1; g.B2 = W1b; g.M = 0; g.N = d; g.K = f; g.C = dx_perm;
+  return launch_gemm(cfg, MODE_NT, EPI_STORE, false, swiglu, g, max_tiles, s);
+}
+
+int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx, const float* topk_w,
+                  const float* d_topk_w, float* d_logits, float* dWr, void* dx, void* ws, void* stream) {
+  CHECK(check_cfg(cfg));
+  REQUIRE(x); REQUIRE(Wr); REQUIRE(topk_idx); REQUIRE(topk_w); REQUIRE(d_topk_w); REQUIRE(d_logits); REQUIRE(dWr);
+  REQUIRE(ws);
+  ALIGNED(x); ALIGNED(Wr); ALIGNED(topk_idx); ALIGNED(topk_w); ALIGNED(d_topk_w); ALIGNED(d_logits); ALIGNED(dWr);
+  ALIGNED(dx); ALIGNED(ws);
+  hipStream_t s = (hipStream_t)stream;
+  if (cfg->T == 0) {
+    const int n = cfg->d_model * cfg->E;
+    fill_zero_kernel<<<(n + 255) / 256, 256, 0, s>>>(dWr, n);   // a kernel, not a memset: safe under graph capture
+    return launch_status();
+  }
+  const WsLayout w = ws_layout(cfg);
+  float* partials = reinterpret_cast<float*>(static_cast<char*>(ws) + w.route_partials);
+  return launch_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, partials, s);
+}
+
+}  // extern "C"

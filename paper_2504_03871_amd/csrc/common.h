@@ -1,0 +1,107 @@
+// Shared host/device helpers of the MoE library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/moe.h"
+
+namespace moe {
+
+constexpr int WAVE = 64;
+
+// ---------------------------------------------------------------- host side
+int set_hip_error(hipError_t e);          // records e for moe_last_hip_error(), returns MOE_ERR_HIP
+int check_cfg(const moe_cfg* c);          // MOE_OK or an argument error
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline int launch_status() {
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? MOE_OK : set_hip_error(e);
+}
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t elt_size(const moe_cfg* c) { return c->dtype == MOE_DTYPE_BF16 ? 2 : 4; }
+
+// Workspace layout (bytes from the start of `ws`), one region per user; see api.hip.
+struct WsLayout {
+  size_t dispatch_blk_cnt;  // int32 [nblk][E]
+  size_t tile_map;          // int32 header + int4 entries (grouped GEMM row tiles)
+  size_t route_partials;    // fp32 [nchunk][d][E]
+  size_t ffn_bwd_dact;      // storage type [planes][T*k][f]: dA (GELU) or dG | dU (SwiGLU)
+  size_t total;
+};
+WsLayout ws_layout(const moe_cfg* c);
+
+constexpr int DISPATCH_CHUNK = 1024;   // assignments ranked by one block
+constexpr int ROUTE_BWD_TOKENS = 128;  // tokens per block of the gate-backward kernel
+constexpr int TILE_ROWS_MIN = 64;      // smallest row-tile height any grouped GEMM uses (sizes the tile map)
+
+// ---------------------------------------------------------------- device side
+#ifdef __HIPCC__
+typedef __bf16 bf16;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  bf16 h = (bf16)f;  // v_cvt_pk_bf16_f32: round to nearest even
+  return (uint32_t)(*reinterpret_cast<unsigned short*>(&h));
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// 16-byte vector of activations: 4 fp32 or 8 bf16.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  float4 raw;
+  __device__ __forceinline__ void load(const float* p) { raw = *reinterpret_cast<const float4*>(p); }
+  __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = raw; }
+  __device__ __forceinline__ void unpack(float* f) const { f[0] = raw.x; f[1] = raw.y; f[2] = raw.z; f[3] = raw.w; }
+  __device__ __forceinline__ void pack(const float* f) { raw = make_float4(f[0], f[1], f[2], f[3]); }
+};
+template <> struct Vec16<bf16> {
+  static constexpr int N = 8;
+  uint4 raw;
+  __device__ __forceinline__ void load(const bf16* p) { raw = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void store(bf16* p) const { *reinterpret_cast<uint4*>(p) = raw; }
+  __device__ __forceinline__ void unpack(float* f) const {
+    const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[2 * i] = __uint_as_float(u[i] << 16); f[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u); }
+  }
+  __device__ __forceinline__ void pack(const float* f) {
+    raw = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+  }
+};
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
+
+// This GPU's share [l, h) of expert e's kept list: clamped to [0, kept], inverted = empty.
+__device__ __forceinline__ void share_of(const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
+                                         int m, int e, int& l, int& h) {
+  l = 0;
+  h = m;
+  if (lo != nullptr) {
+    l = min(max(lo[e], 0), m);
+    h = min(max(hi[e], 0), m);
+    if (h < l) h = l;
+  }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, WAVE);
+  return v;
+}
+
+// exact-erf GELU pieces, SiLU pieces (fp32)
+__device__ __forceinline__ float gelu_f(float a) { return 0.5f * a * erfcf(-a * 0.70710678118654752440f); }
+__device__ __forceinline__ float gelu_grad_f(float a) {
+  return 0.5f * erfcf(-a * 0.70710678118654752440f) + a * 0.39894228040143267794f * __expf(-0.5f * a * a);
+}
+__device__ __forceinline__ float sigmoid_f(float g) { return 1.0f / (1.0f + __expf(-g)); }
+#endif  // __HIPCC__
+
+}  // namespace moe

@@ -1,0 +1,167 @@
+// Dispatch: stable group-by-expert of the T*k assignments and the row gather.
+//
+// The paper's dispatch all-to-all sends each token embedding to the GPU that holds the target
+// expert (Section 2.1); on one GPU this is a permutation.  Order inside an expert is ascending
+// token index, so the result is unique and the capacity cut ("first C of the list") is the
+// stable rank itself.  Everything here is integer work and deterministic: per-block histograms,
+// a scan over blocks, and an in-block stable rank built from wave ballots.
+#include "common.h"
+
+namespace moe {
+
+constexpr int DP_THREADS = 256;
+constexpr int DP_WAVES = DP_THREADS / WAVE;
+constexpr int DP_ROUNDS = DISPATCH_CHUNK / DP_THREADS;   // 4
+constexpr int DP_SUB = DP_ROUNDS * DP_WAVES;             // 16 sub-chunks of 64 assignments, ascending
+
+__global__ __launch_bounds__(DP_THREADS) void dispatch_hist_kernel(const int32_t* __restrict__ topk_idx, int A, int E,
+                                                                  int32_t* __restrict__ blk_cnt) {
+  __shared__ int s_cnt[MOE_MAX_E];
+  for (int e = threadIdx.x; e < E; e += DP_THREADS) s_cnt[e] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * DISPATCH_CHUNK;
+#pragma unroll
+  for (int r = 0; r < DP_ROUNDS; ++r) {
+    const int a = base + r * DP_THREADS + threadIdx.x;
+    if (a < A) atomicAdd(&s_cnt[topk_idx[a]], 1);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += DP_THREADS) blk_cnt[(size_t)blockIdx.x * E + e] = s_cnt[e];
+}
+
+__global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
+    const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ blk_cnt, int A, int E, int capacity, int nblk,
+    int32_t* __restrict__ counts, int32_t* __restrict__ kept, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ row_of, int32_t* __restrict__ src_of) {
+  __shared__ int s_before[MOE_MAX_E];            // assignments of expert e in earlier blocks
+  __shared__ int s_kept[MOE_MAX_E];
+  __shared__ int s_off[MOE_MAX_E + 1];
+  __shared__ int s_sub[DP_SUB][MOE_MAX_E];       // per sub-chunk counts, then exclusive offsets
+  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+
+  // scan over blocks (each block redoes it: nblk*E is tiny) and over experts
+  for (int e = tid; e < MOE_MAX_E; e += DP_THREADS) {
+    int before = 0, total = 0;
+    if (e < E) {
+      for (int b = 0; b < nblk; ++b) {
+        const int c = blk_cnt[(size_t)b * E + e];
+        before += (b < (int)blockIdx.x) ? c : 0;
+        total += c;
+      }
+    }
+    const int m = (capacity > 0) ? min(total, capacity) : total;
+    s_before[e] = before;
+    s_kept[e] = m;
+    if (blockIdx.x == 0 && e < E) { counts[e] = total; kept[e] = m; }
+    for (int sc = 0; sc < DP_SUB; ++sc) s_sub[sc][e] = 0;
+  }
+  __syncthreads();
+  if (tid == 0) {   // E <= 256: a serial scan costs less than a barrier-heavy parallel one
+    int run = 0;
+    for (int e = 0; e < E; ++e) { s_off[e] = run; run += s_kept[e]; }
+    s_off[E] = run;
+  }
+  __syncthreads();
+  if (blockIdx.x == 0)
+    for (int e = tid; e <= E; e += DP_THREADS) offsets[e] = s_off[e];
+
+  const int base = blockIdx.x * DISPATCH_CHUNK;
+  int my_e[DP_ROUNDS], my_rank[DP_ROUNDS];
+#pragma unroll
+  for (int r = 0; r < DP_ROUNDS; ++r) {
+    const int a = base + r * DP_THREADS + tid;
+    const bool valid = a < A;
+    const int e = valid ? topk_idx[a] : -1;
+    my_e[r] = e;
+    // rank among the lanes of this wave with the same expert; one pass per distinct expert present
+    unsigned long long todo = __ballot(valid);
+    int rank = 0;
+    while (todo) {
+      const int leader = __ffsll((long long)todo) - 1;
+      const int e0 = __shfl(e, leader, WAVE);
+      const unsigned long long same = __ballot(valid && e == e0);
+      if (valid && e == e0) {
+        rank = __popcll(same & ((1ull << lane) - 1ull));
+        if (rank == 0) s_sub[r * DP_WAVES + wave][e0] = __popcll(same);   // one writer per (sub-chunk, expert)
+      }
+      todo &= ~same;
+    }
+    my_rank[r] = rank;
+  }
+  __syncthreads();
+  for (int e = tid; e < E; e += DP_THREADS) {
+    int run = s_before[e];
+    for (int sc = 0; sc < DP_SUB; ++sc) { const int c = s_sub[sc][e]; s_sub[sc][e] = run; run += c; }
+  }
+  __syncthreads();
+  const int R = s_off[E];
+#pragma unroll
+  for (int r = 0; r < DP_ROUNDS; ++r) {
+    const int a = base + r * DP_THREADS + tid;
+    if (a >= A) continue;
+    const int e = my_e[r];
+    const int rank = s_sub[r * DP_WAVES + wave][e] + my_rank[r];
+    int row = -1;
+    if (rank < s_kept[e]) { row = s_off[e] + rank; src_of[row] = a; }
+    row_of[a] = row;
+    if (a >= R) src_of[a] = -1;   // rows past the end of the kept lists
+  }
+}
+
+// x_perm[row] = x[src_of[row] / k] for the rows inside this GPU's shares.  One wave per row.
+template <typename T>
+__global__ __launch_bounds__(256) void dispatch_gather_kernel(
+    const T* __restrict__ x, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ src_of,
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept, const int32_t* __restrict__ lo,
+    const int32_t* __restrict__ hi, T* __restrict__ x_perm, int A, int d, int E, int k) {
+  constexpr int VN = Vec16<T>::N;
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int wave_global = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+  const int nwaves = gridDim.x * blockDim.x / WAVE;
+  const int R = offsets[E];
+  for (int row = wave_global; row < R; row += nwaves) {
+    const int a = src_of[row];
+    const int e = topk_idx[a];
+    int l, h;
+    share_of(lo, hi, kept[e], e, l, h);
+    const int pos = row - offsets[e];
+    if (pos < l || pos >= h) continue;
+    const T* src = x + (size_t)(a / k) * d;
+    T* dst = x_perm + (size_t)row * d;
+    for (int c = lane * VN; c < d; c += 4 * WAVE * VN) {
+      Vec16<T> v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c + u * WAVE * VN < d) v[u].load(src + c + u * WAVE * VN);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c + u * WAVE * VN < d) v[u].store(dst + c + u * WAVE * VN);
+    }
+  }
+}
+
+int launch_dispatch(const moe_cfg* c, const void* x, const int32_t* idx, const int32_t* lo, const int32_t* hi,
+                    int32_t* counts, int32_t* kept, int32_t* offsets, int32_t* row_of, int32_t* src_of, void* x_perm,
+                    int32_t* blk_cnt, hipStream_t s) {
+  const int A = c->T * c->k;
+  const int nblk = (A + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK;
+  int rc = MOE_OK;
+  if (nblk > 0) {
+    dispatch_hist_kernel<<<nblk, DP_THREADS, 0, s>>>(idx, A, c->E, blk_cnt);
+    rc = launch_status();
+    if (rc != MOE_OK) return rc;
+  }
+  // with no assignments one block still writes the (all-zero) counts, kept and offsets
+  dispatch_rank_kernel<<<nblk > 0 ? nblk : 1, DP_THREADS, 0, s>>>(idx, blk_cnt, A, c->E, c->capacity, nblk, counts, kept, offsets, row_of, src_of);
+  rc = launch_status();
+  if (rc != MOE_OK || x_perm == nullptr || A == 0) return rc;
+  const int waves_per_block = 256 / WAVE;
+  const int grid = min((A + waves_per_block - 1) / waves_per_block, 256 * 32);
+  if (c->dtype == MOE_DTYPE_BF16)
+    dispatch_gather_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)x, idx, src_of, offsets, kept, lo, hi, (bf16*)x_perm, A, c->d_model, c->E, c->k);
+  else
+    dispatch_gather_kernel<float><<<grid, 256, 0, s>>>((const float*)x, idx, src_of, offsets, kept, lo, hi, (float*)x_perm, A, c->d_model, c->E, c->k);
+  return launch_status();
+}
+
+}  // namespace moe

@@ -1,0 +1,108 @@
+// Grouped (per-expert, ragged) GEMM plumbing shared by the fp32 and the bf16 MFMA kernels.
+//
+// The expert FFN of the paper is "mainly GEMMs" (Section 2.1) and its cost must follow the number
+// of token rows an expert receives, not the number of experts (Section 4.2, the remark on
+// T_E^Exp).  So every GEMM here walks a device-resident list of row tiles built from
+// offsets / kept / shares: no padding of experts to a common size and no host read-back of counts.
+#pragma once
+#include "common.h"
+
+namespace moe {
+
+// One tile of consecutive permuted rows belonging to one expert.
+struct RowTile {
+  int32_t e;      // expert
+  int32_t row0;   // first row (absolute index into the permuted buffers)
+  int32_t nrows;  // valid rows in this tile (1..tile height)
+  int32_t pad;
+};
+
+// Tile map in the workspace: header[0] = number of tiles, then the tiles.
+struct TileMap {
+  int32_t* header;
+  RowTile* tiles;
+};
+inline TileMap tile_map_at(void* ws_region) {
+  TileMap m;
+  m.header = reinterpret_cast<int32_t*>(ws_region);
+  m.tiles = reinterpret_cast<RowTile*>(reinterpret_cast<char*>(ws_region) + 16);
+  return m;
+}
+inline int max_row_tiles(int A, int E, int tile_rows) { return (A + tile_rows - 1) / tile_rows + E; }
+
+enum GemmMode {
+  MODE_NN = 0,  // C[rows, N] = A[rows, K] * B_e[K, N]          (forward GEMMs)
+  MODE_NT = 1,  // C[rows, N] = A[rows, K] * B_e[N, K]^T        (dH, dX)
+  MODE_TN = 2   // C_e[M, N] (+)= A[rows_e, M]^T * B[rows_e, N]  (weight gradients)
+};
+
+enum Epilogue {
+  EPI_STORE = 0,       // C = acc
+  EPI_GELU_FWD = 1,    // C = acc (pre-activation), C2 = gelu(acc)
+  EPI_SWIGLU_FWD = 2,  // dual accumulators g,u: C = g, C2 = u, C3 = silu(g)*u
+  EPI_GELU_BWD = 3,    // C = acc * gelu'(S1)
+  EPI_SWIGLU_BWD = 4,  // C = dG = acc * S2 * silu'(S1), C2 = dU = acc * silu(S1)   (S1 = G, S2 = U)
+  EPI_DW = 5           // fp32 C_e = acc (+ C_e)
+};
+
+struct GemmArgs {
+  const void* A;
+  const void* A2;   // second activation operand (SwiGLU dX: dU)
+  const void* B;
+  const void* B2;   // second weight operand (SwiGLU: W1b)
+  void* C;
+  void* C2;
+  void* C3;
+  const void* S1;
+  const void* S2;
+  const RowTile* tiles;
+  const int32_t* ntiles;
+  const int32_t* offsets;
+  const int32_t* kept;
+  const int32_t* lo;
+  const int32_t* hi;
+  int M, N, K;   // NN/NT: N and K fixed (M unused); TN: M and N fixed (K is the expert's row count)
+  int E;
+  int accumulate;
+};
+
+int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, int E,
+                    int tile_rows, TileMap map, hipStream_t s);
+
+// fp32 storage, fp32 FMA (any shape that passes check_cfg)
+int launch_gemm_f32(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s);
+// bf16 storage, MFMA with fp32 accumulation
+int launch_gemm_bf16(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s);
+int gemm_bf16_tile_rows();
+
+#ifdef __HIPCC__
+// Element-wise epilogues, shared by both kernels.  `row` is the absolute permuted row, `col` the
+// output column, `ldc` the row pitch of the output(s).
+template <typename T, int EPI>
+__device__ __forceinline__ void epilogue(const GemmArgs& g, size_t idx, float acc, float acc2) {
+  if constexpr (EPI == EPI_STORE) {
+    reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc);
+  } else if constexpr (EPI == EPI_GELU_FWD) {
+    reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc);
+    reinterpret_cast<T*>(g.C2)[idx] = from_f32<T>(gelu_f(acc));
+  } else if constexpr (EPI == EPI_SWIGLU_FWD) {
+    reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc);
+    reinterpret_cast<T*>(g.C2)[idx] = from_f32<T>(acc2);
+    reinterpret_cast<T*>(g.C3)[idx] = from_f32<T>(acc * sigmoid_f(acc) * acc2);
+  } else if constexpr (EPI == EPI_GELU_BWD) {
+    const float a = to_f32(reinterpret_cast<const T*>(g.S1)[idx]);
+    reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc * gelu_grad_f(a));
+  } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+    const float gg = to_f32(reinterpret_cast<const T*>(g.S1)[idx]);
+    const float uu = to_f32(reinterpret_cast<const T*>(g.S2)[idx]);
+    const float sg = sigmoid_f(gg);
+    reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc * uu * sg * (1.f + gg * (1.f - sg)));
+    reinterpret_cast<T*>(g.C2)[idx] = from_f32<T>(acc * gg * sg);
+  } else {
+    float* c = reinterpret_cast<float*>(g.C);
+    c[idx] = g.accumulate ? c[idx] + acc : acc;
+  }
+}
+#endif
+
+}  // namespace moe

@@ -1,0 +1,165 @@
+// Row-tile map builder and the fp32 grouped GEMM (fp32 storage, fp32 FMA accumulation).
+//
+// The fp32 path exists for the small full-precision configuration, whose tolerance (1e-5) rules out
+// reduced-precision matrix instructions; it is a plain LDS-tiled kernel, not a tuned one.
+#include "gemm.h"
+
+namespace moe {
+
+__global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept,
+                                                       const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
+                                                       int E, int tile_rows, int32_t* __restrict__ header,
+                                                       RowTile* __restrict__ tiles) {
+  __shared__ int s_n[MOE_MAX_E], s_start[MOE_MAX_E + 1];
+  const int e = threadIdx.x;
+  int l = 0, h = 0;
+  if (e < E) share_of(lo, hi, kept[e], e, l, h);
+  s_n[e] = (h - l + tile_rows - 1) / tile_rows;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int i = 0; i < E; ++i) { s_start[i] = run; run += s_n[i]; }
+    s_start[E] = run;
+    header[0] = run;
+  }
+  __syncthreads();
+  if (e < E) {
+    const int base = offsets[e] + l;
+    for (int i = 0; i < s_n[e]; ++i) {
+      RowTile t;
+      t.e = e;
+      t.row0 = base + i * tile_rows;
+      t.nrows = min(tile_rows, h - l - i * tile_rows);
+      t.pad = 0;
+      tiles[s_start[e] + i] = t;
+    }
+  }
+}
+
+int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, int E,
+                    int tile_rows, TileMap map, hipStream_t s) {
+  tile_map_kernel<<<1, 256, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles);
+  return launch_status();
+}
+
+constexpr int SB = 64;   // tile edge
+constexpr int SK = 16;   // k step
+
+// NN/NT: grid = (ceil(N/SB), max row tiles).  TN: grid = (ceil(N/SB), ceil(M/SB), E).
+template <int MODE, int EPI, bool DUAL, bool CHAIN>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
+  __shared__ float As[SK][SB + 4];
+  __shared__ float Bs[SK][SB + 4];
+  __shared__ float Bs2[DUAL ? SK : 1][SB + 4];
+  const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+  const int n0 = blockIdx.x * SB;
+  int e, row0, mvalid, klen, m0 = 0;
+  if constexpr (MODE == MODE_TN) {
+    e = blockIdx.z;
+    m0 = blockIdx.y * SB;
+    int l, h;
+    share_of(g.lo, g.hi, g.kept[e], e, l, h);
+    row0 = g.offsets[e] + l;
+    klen = h - l;
+    mvalid = min(SB, g.M - m0);
+    if (klen == 0 && g.accumulate) return;
+  } else {
+    if ((int)blockIdx.y >= g.ntiles[0]) return;
+    const RowTile t = g.tiles[blockIdx.y];
+    e = t.e;
+    row0 = t.row0;
+    mvalid = t.nrows;
+    klen = g.K;
+  }
+  const int nvalid = min(SB, g.N - n0);
+  float acc[4][4] = {}, acc2[DUAL ? 4 : 1][4] = {};
+  for (int pass = 0; pass < (CHAIN ? 2 : 1); ++pass) {
+    const float* A = reinterpret_cast<const float*>(pass == 0 ? g.A : g.A2);
+    const float* B = reinterpret_cast<const float*>(pass == 0 ? g.B : g.B2);
+    const float* B2 = reinterpret_cast<const float*>(g.B2);
+    for (int k0 = 0; k0 < klen; k0 += SK) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int id = tid + 256 * i;
+        {  // A element (m, kk)
+          int m, kk;
+          if constexpr (MODE == MODE_TN) { m = id % SB; kk = id / SB; } else { m = id / SK; kk = id % SK; }
+          float v = 0.f;
+          if (m < mvalid && k0 + kk < klen) {
+            if constexpr (MODE == MODE_TN) v = A[(size_t)(row0 + k0 + kk) * g.M + m0 + m];
+            else v = A[(size_t)(row0 + m) * g.K + k0 + kk];
+          }
+          As[kk][m] = v;
+        }
+        {  // B element (kk, n)
+          int n, kk;
+          if constexpr (MODE == MODE_NT) { n = id / SK; kk = id % SK; } else { n = id % SB; kk = id / SB; }
+          float v = 0.f, v2 = 0.f;
+          if (n < nvalid && k0 + kk < klen) {
+            size_t off;
+            if constexpr (MODE == MODE_TN) off = (size_t)(row0 + k0 + kk) * g.N + n0 + n;
+            else if constexpr (MODE == MODE_NN) off = ((size_t)e * g.K + k0 + kk) * g.N + n0 + n;
+            else off = ((size_t)e * g.N + n0 + n) * g.K + k0 + kk;
+            v = B[off];
+            if constexpr (DUAL) v2 = B2[off];
+          }
+          Bs[kk][n] = v;
+          if constexpr (DUAL) Bs2[kk][n] = v2;
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < SK; ++kk) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        if constexpr (DUAL) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc2[i][j] = fmaf(a[i], Bs2[kk][tx * 4 + j], acc2[i][j]);
+        }
+      }
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = ty * 4 + i, n = tx * 4 + j;
+      if (m < mvalid && n < nvalid) {
+        size_t idx;
+        if constexpr (MODE == MODE_TN) idx = ((size_t)e * g.M + m0 + m) * g.N + n0 + n;
+        else idx = (size_t)(row0 + m) * g.N + n0 + n;
+        epilogue<float, EPI>(g, idx, acc[i][j], DUAL ? acc2[DUAL ? i : 0][j] : 0.f);
+      }
+    }
+}
+
+template <int MODE, int EPI, bool DUAL, bool CHAIN>
+static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
+  dim3 grid;
+  if (MODE == MODE_TN) grid = dim3((g.N + SB - 1) / SB, (g.M + SB - 1) / SB, g.E);
+  else grid = dim3((g.N + SB - 1) / SB, max_tiles, 1);
+  gemm_f32_kernel<MODE, EPI, DUAL, CHAIN><<<grid, 256, 0, s>>>(g);
+  return launch_status();
+}
+
+int launch_gemm_f32(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s) {
+  if (mode == MODE_NN && epi == EPI_GELU_FWD) return launch_one<MODE_NN, EPI_GELU_FWD, false, false>(g, max_tiles, s);
+  if (mode == MODE_NN && epi == EPI_SWIGLU_FWD && dual) return launch_one<MODE_NN, EPI_SWIGLU_FWD, true, false>(g, max_tiles, s);
+  if (mode == MODE_NN && epi == EPI_STORE) return launch_one<MODE_NN, EPI_STORE, false, false>(g, max_tiles, s);
+  if (mode == MODE_NT && epi == EPI_GELU_BWD) return launch_one<MODE_NT, EPI_GELU_BWD, false, false>(g, max_tiles, s);
+  if (mode == MODE_NT && epi == EPI_SWIGLU_BWD) return launch_one<MODE_NT, EPI_SWIGLU_BWD, false, false>(g, max_tiles, s);
+  if (mode == MODE_NT && epi == EPI_STORE && !chain) return launch_one<MODE_NT, EPI_STORE, false, false>(g, max_tiles, s);
+  if (mode == MODE_NT && epi == EPI_STORE && chain) return launch_one<MODE_NT, EPI_STORE, false, true>(g, max_tiles, s);
+  if (mode == MODE_TN && epi == EPI_DW) return launch_one<MODE_TN, EPI_DW, false, false>(g, max_tiles, s);
+  return MOE_ERR_BAD_DTYPE;
+}
+
+}  // namespace moe

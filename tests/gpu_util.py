@@ -1,0 +1,84 @@
+"""Helpers for the GPU parity tests: upload a workload, run the HIP path, run the oracle, compare."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import moe_oracle as O
+from paper_2504_03871_amd import synth as S
+
+TOL = {S.DT_F32: 1e-5, S.DT_BF16: 2e-2}
+SENTINEL = 12345.0   # exactly representable in bf16? 12345 = 0x4640E400 -> no; use a power-of-two mix below
+SENTINEL = 12288.0   # 1.5 * 2^13, exact in bf16 and fp32
+
+
+def to_dev(arr_f32, bits, device, bf16):
+    import torch
+    if bf16:
+        return torch.from_numpy(bits.view(np.int16).copy()).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr_f32, dtype=np.float32)).to(device)
+
+
+def make_layer(w: S.Workload, inp: dict, device="cuda:0"):
+    from paper_2504_03871_amd.layer import MoELayer
+    import torch
+    L = MoELayer(w.T, w.d, w.f, w.E, w.k, dtype=w.dtype, act=w.act, capacity=w.capacity, device=device)
+    bf = w.dtype == S.DT_BF16
+    for name, attr in (("x", "x"), ("W1", "W1"), ("W2", "W2"), ("d_out", "d_out"), ("W1b", "W1b")):
+        if name in inp:
+            getattr(L, attr).copy_(to_dev(inp[name], inp.get(name + "_bits"), device, bf))
+    L.Wr.copy_(torch.from_numpy(inp["Wr"]).to(device))
+    if inp.get("bias") is not None:
+        L.bias = torch.from_numpy(inp["bias"]).to(device)
+    return L
+
+
+def fill_sentinels(L):
+    """Every output buffer starts at a sentinel so that untouched rows can be recognised."""
+    for name in ("x_perm", "y_perm", "out", "dy_perm", "dx_perm", "dx", "dW1", "dW2", "dW1b", "d_logits", "dWr",
+                 "d_topk_w", "logits", "topk_w"):
+        t = getattr(L, name)
+        if t is not None:
+            t.fill_(SENTINEL)
+    for i in range(3 if L.act == 1 else 2):
+        L.saved_plane(i).fill_(SENTINEL)
+    for name in ("topk_idx", "counts", "kept", "offsets", "row_of", "src_of"):
+        getattr(L, name).fill_(-7)
+
+
+def host(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy().astype(np.float64)
+    a = t.cpu().numpy()
+    return a.astype(np.float64) if a.dtype == np.float32 else a
+
+
+def rel_err(got, ref):
+    """(relative L2 error, max abs error / max abs ref) over the finite entries of ref."""
+    m = np.isfinite(ref)
+    g, r = got[m], ref[m]
+    den = np.linalg.norm(r)
+    mx = np.abs(r).max() if r.size else 0.0
+    l2 = np.linalg.norm(g - r) / den if den > 0 else np.linalg.norm(g - r)
+    ma = np.abs(g - r).max() / mx if mx > 0 else (np.abs(g - r).max() if r.size else 0.0)
+    return l2, ma
+
+
+def assert_close(name, got, ref, tol):
+    assert got.shape == ref.shape, f"{name}: shape {got.shape} vs {ref.shape}"
+    assert np.isfinite(got[np.isfinite(ref)]).all(), f"{name}: non-finite values"
+    l2, ma = rel_err(got, ref)
+    assert l2 <= tol and ma <= tol, f"{name}: rel L2 {l2:.3e}, max-abs/max {ma:.3e} > {tol:g}"
+    return l2, ma
+
+
+def run_oracle(w: S.Workload, inp: dict, gpu_logits=None, lo=None, hi=None, slice_fn=None):
+    return O.moe_layer(inp["x"], inp["Wr"], inp.get("bias"), inp["W1"], inp.get("W1b"), inp["W2"], inp["d_out"],
+                       w.k, w.act, capacity=w.capacity, lo=lo, hi=hi, logits=gpu_logits, slice_fn=slice_fn)
+
+
+def untouched_rows(t, live_mask):
+    """True if every row not in live_mask still holds the sentinel."""
+    a = host(t)
+    dead = ~live_mask
+    return bool((a[dead] == SENTINEL).all())

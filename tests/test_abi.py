@@ -1,0 +1,91 @@
+"""Host-side checks of the C ABI: the library loads, exports every declared symbol, and rejects bad
+arguments before launching anything (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2504_03871_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert set(names) == set(B.SYMBOLS), (names, B.SYMBOLS)
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_error_strings():
+    lib = B.lib()
+    assert lib.moe_error_string(0) == b"ok"
+    for code in range(-6, 0):
+        assert len(lib.moe_error_string(code)) > 3
+    assert b"unknown" in lib.moe_error_string(-99)
+    assert lib.moe_last_hip_error() == 0
+
+
+def test_cfg_validation():
+    ok = dict(T=8, d_model=64, d_ff=128, E=4, k=2, dtype=B.DTYPE_BF16, act=B.ACT_GELU)
+    assert B.moe_workspace_bytes(B.make_cfg(**ok)) > 0
+    assert B.moe_saved_bytes(B.make_cfg(**ok)) == 2 * 16 * 128 * 2
+    assert B.moe_saved_bytes(B.make_cfg(**{**ok, "act": B.ACT_SWIGLU, "dtype": B.DTYPE_F32})) == 3 * 16 * 128 * 4
+    bad = [dict(k=5), dict(k=0), dict(E=0), dict(E=257), dict(k=9, E=16), dict(d_model=72), dict(d_ff=100),
+           dict(T=-1), dict(d_model=0)]
+    for b in bad:
+        with pytest.raises(B.MoeError) as ei:
+            B.moe_workspace_bytes(B.make_cfg(**{**ok, **b}))
+        assert ei.value.code == -2, b
+    for b in (dict(dtype=2), dict(act=7)):
+        with pytest.raises(B.MoeError) as ei:
+            B.moe_workspace_bytes(B.make_cfg(**{**ok, **b}))
+        assert ei.value.code == -3
+    # fp32 accepts multiples of 4
+    assert B.moe_workspace_bytes(B.make_cfg(**{**ok, "dtype": B.DTYPE_F32, "d_model": 68, "d_ff": 100})) > 0
+
+
+def test_pointer_validation_happens_before_any_launch():
+    """Fake (never dereferenced) device addresses: every call must fail in validation."""
+    cfg = B.make_cfg(8, 64, 128, 4, 2)
+    P, Q = 0x10000, 0x10008       # aligned / misaligned fake addresses
+    s = ctypes.c_void_p(0)
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_route(cfg, None, P, None, None, P, P, P, stream=s)
+    assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_route(cfg, P, P, None, None, P, Q, P, stream=s)
+    assert ei.value.code == -5
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_dispatch(cfg, P, P, P, None, P, P, P, P, P, P, P, stream=s)      # only one slice bound
+    assert ei.value.code == -4
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_dispatch(cfg, None, P, None, None, P, P, P, P, P, P, P, stream=s)  # x_perm without x
+    assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_expert_ffn_fwd(cfg, P, P, P, P, P, P, None, None, P, P, P, stream=s)   # W1b given for GELU
+    assert ei.value.code == -3
+    sw = B.make_cfg(8, 64, 128, 4, 2, act=B.ACT_SWIGLU)
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_expert_ffn_fwd(sw, P, P, None, P, P, P, None, None, P, P, P, stream=s)  # SwiGLU without W1b
+    assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_combine(cfg, P, P, P, P, P, P, None, None, None, 0, stream=s)
+    assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_combine_bwd(cfg, P, P, None, P, P, P, P, None, None, P, P, stream=s)
+    assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_expert_ffn_bwd(cfg, P, P, P, P, None, P, P, P, None, None, P, P, None, None, 0, P, stream=s)
+    assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_route_bwd(cfg, P, P, P, P, P, P, P, Q, P, stream=s)
+    assert ei.value.code == -5
