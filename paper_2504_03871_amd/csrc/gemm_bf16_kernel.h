@@ -1,0 +1,479 @@
+// bf16 grouped GEMM kernel for the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+//
+// Work decomposition: block tile BM x BN, WGM x WGN waves, each wave owns (BM/WGM) x (BN/WGN) as a
+// grid of 32x32 MFMA tiles; K advances BKT elements per stage.
+//
+// Pipeline: a ring of three LDS stages.  Global loads for stage kt+3 are issued at the top of
+// iteration kt into one of two register sets and written to LDS one iteration later, so a load has
+// two iterations of MFMA work to land.  Stage kt+1 is complete and visible a full iteration before
+// it is needed, which lets each wave fetch the first fragments of the next stage before the
+// block barrier: the barrier only guards buffer reuse and is off the MFMA critical path.
+//
+// Operands: one whose K index is contiguous in memory is kept as [rows][BKT] in LDS and read with
+// 16-byte LDS reads; one whose K index is strided is kept exactly as it lies in memory, [BKT][cols],
+// and read with the transposing 8-byte LDS read of gfx950, so nothing is ever transposed in global
+// memory and the same kernel serves x W (NN), dy W^T (NT) and x^T dy (TN).
+//
+// Epilogue (NN/NT): accumulators go through a per-wave LDS slab to turn the MFMA register layout
+// into rows, so that every output (and every saved tensor the backward epilogues read) moves as
+// 8-byte pieces that fill whole 128-byte lines.
+//
+// MFMA 32x32x16 register layout (checked on the hardware): lane l supplies row/column l%32 and the
+// eight K values (l/32)*8..+7 of the step; accumulator register v of lane l is row
+// (v/4)*8 + (l/32)*4 + v%4, column l%32 of the 32x32 tile.
+#pragma once
+#include "gemm.h"
+
+namespace moe {
+
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int NUM_XCD = 8;
+constexpr int NBUF = 3;   // LDS stages in the ring
+
+// ---- LDS layouts -------------------------------------------------------------------------------
+// K-contiguous tile: [rows][BKT] bf16.  The 16-byte chunks of a row are XOR-swizzled with the index
+// of the 256-byte LDS line the row lies in, so 16 lanes reading the same chunk of 16 consecutive
+// rows hit 16 distinct 16-byte bank groups (the LDS serves 64 banks x 4 bytes per clock).
+template <int BKT>
+__device__ __forceinline__ int kc_off(int row, int chunk) {
+  constexpr int CPR = BKT / 8, RP = 256 / (BKT * 2);
+  return row * (BKT * 2) + ((chunk ^ ((row / RP) & (CPR - 1))) << 4);
+}
+// K-strided tile: [BKT][W] bf16; the 64-byte granules of a K row are XOR-swizzled with k%4, so the four
+// K rows that one transposing read touches fall into different bank groups.
+template <int W>
+__device__ __forceinline__ int ks_off(int krow, int col_byte) {
+  return krow * (W * 2) + ((((col_byte >> 6) ^ (krow & 3)) << 6) | (col_byte & 63));
+}
+
+template <int BKT>
+__device__ __forceinline__ bf16x8 lds_read_kc(const char* tile, int row, int chunk) {
+  return *reinterpret_cast<const bf16x8*>(tile + kc_off<BKT>(row, chunk));
+}
+// Eight K values of K step `kstep` for column col_base + l%32 from a K-strided tile.  The
+// transposing read works on blocks of 16 lanes: lane s of a block reads 8 bytes at (K row s/4,
+// columns 4*(s%4)..+3) and receives the four K rows of column s.
+template <int W>
+__device__ __forceinline__ bf16x8 lds_read_ks(const char* tile, int kstep, int col_base, int lane) {
+  const int b = lane >> 4, s = lane & 15;
+  const int krow = kstep * 16 + (b >> 1) * 8 + (s >> 2);
+  const int colb = (col_base + (b & 1) * 16 + (s & 3) * 4) * 2;
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + ks_off<W>(krow, colb)));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + ks_off<W>(krow + 4, colb)));
+  union { struct { s16x4 a, b; } p; bf16x8 v; } u;
+  u.p.a = lo;
+  u.p.b = hi;
+  return u.v;
+}
+
+// Same, from a precomputed per-lane address: the second half lies four K rows further on.
+template <int W>
+__device__ __forceinline__ bf16x8 lds_read_ks2(const char* p) {
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * W * 2));
+  union { struct { s16x4 a, b; } q; bf16x8 v; } u;
+  u.q.a = lo;
+  u.q.b = hi;
+  return u.v;
+}
+
+// ---- global -> register -> LDS staging of one stage --------------------------------------------
+// Global loads are raw buffer loads: the descriptor's byte count is set to the part of the operand
+// this tile may read, and the hardware returns zero for anything past it.  That gives the ragged
+// edges (rows past an expert's share, K rows past the share in the weight-gradient GEMM, columns past
+// the matrix) for free, with no predicates, no branches and one 32-bit offset register per load.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, size_t bytes) {
+  const unsigned n = bytes > 0xffffffffull ? 0xffffffffu : (unsigned)bytes;
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+}
+
+// One operand tile of one stage.  KC: [ROWS][BKT], thread chunk id -> (row id/CPR, chunk id%CPR).
+// KS: [BKT][ROWS] (ROWS = tile width), chunk id -> (K row id/(ROWS/8), chunk id%(ROWS/8)).
+template <bool KC, int ROWS, int NT, int BKT>
+struct Stage {
+  static constexpr int CPR = KC ? BKT / 8 : ROWS / 8;
+  static constexpr int CH = ROWS * BKT / 8 / NT;
+  static_assert(CH >= 1, "tile too small for this many threads");
+  u32x4 r[CH];
+  // byte offset of chunk i of this thread inside the operand (pitch in bytes), and inside the LDS tile
+  static __device__ __forceinline__ unsigned goff(int i, int tid, unsigned pitch) {
+    const int id = tid + NT * i;
+    return (unsigned)(id / CPR) * pitch + (unsigned)(id % CPR) * 16u;
+  }
+  static __device__ __forceinline__ int loff(int i, int tid) {
+    const int id = tid + NT * i;
+    if constexpr (KC) return kc_off<BKT>(id / CPR, id % CPR);
+    else return ks_off<ROWS>(id / CPR, (id % CPR) * 16);
+  }
+  __device__ __forceinline__ void load(rsrc_t rs, const unsigned (&voff)[CH], unsigned adv) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff[i] + adv, 0, 0);
+  }
+  __device__ __forceinline__ void store(char* tile, const int (&lo)[CH]) const {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) *reinterpret_cast<u32x4*>(tile + lo[i]) = r[i];
+  }
+};
+
+// Block -> tile.  Workgroups are handed to the eight XCDs round-robin; each XCD gets one contiguous
+// range of the (grouped) tile order so that tiles running together on an XCD share operand panels in
+// its L2.  Inside the order, GROUP row tiles are walked column by column.
+__device__ __forceinline__ bool block_to_tile(int n_real, int ntn, int& rt, int& nt) {
+  constexpr int GROUP = 4;
+  const int per = (n_real + NUM_XCD - 1) / NUM_XCD;
+  const int i = blockIdx.x / NUM_XCD;
+  if (i >= per) return false;
+  const int logical = (blockIdx.x % NUM_XCD) * per + i;
+  if (logical >= n_real) return false;
+  const int nrt = n_real / ntn;
+  const int per_group = GROUP * ntn;
+  const int grp = logical / per_group, in = logical % per_group;
+  const int first = grp * GROUP, gsz = min(GROUP, nrt - first);
+  rt = first + in % gsz;
+  nt = in / gsz;
+  return true;
+}
+
+// ---- fast activation pieces for bf16 outputs ----------------------------------------------------
+// Phi(a) from the rational erf approximation 7.1.26 of Abramowitz & Stegun (|error| < 1.5e-7, far
+// below bf16 resolution); `expo` receives exp(-a^2/2), which gelu' needs as well.
+__device__ __forceinline__ float phi_fast(float a, float& expo) {
+  const float x = fabsf(a) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  expo = __builtin_amdgcn_exp2f(a * a * -0.72134752044448170368f);   // exp(-a^2/2)
+  const float q = 0.5f * p * t * expo;
+  return a >= 0.f ? 1.0f - q : q;
+}
+__device__ __forceinline__ float sigmoid_fast(float g) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.44269504088896340736f));
+}
+
+// Row-layout epilogue on four consecutive columns starting at flat index idx (bf16 tensors).
+template <int EPI>
+__device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f32x4& a, const f32x4& a2) {
+  auto st = [](void* base, size_t i, float v0, float v1, float v2, float v3) {
+    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16*>(base) + i) = u32x2{pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
+  };
+  auto ld = [](const void* base, size_t i, float* f) {
+    const u32x2 r = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(base) + i);
+    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+  };
+  if constexpr (EPI == EPI_STORE) {
+    st(g.C, idx, a[0], a[1], a[2], a[3]);
+  } else if constexpr (EPI == EPI_GELU_FWD) {
+    st(g.C, idx, a[0], a[1], a[2], a[3]);
+    float h[4], ex;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) h[i] = a[i] * phi_fast(a[i], ex);
+    st(g.C2, idx, h[0], h[1], h[2], h[3]);
+  } else if constexpr (EPI == EPI_SWIGLU_FWD) {
+    st(g.C, idx, a[0], a[1], a[2], a[3]);
+    st(g.C2, idx, a2[0], a2[1], a2[2], a2[3]);
+    float h[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) h[i] = a[i] * sigmoid_fast(a[i]) * a2[i];
+    st(g.C3, idx, h[0], h[1], h[2], h[3]);
+  } else if constexpr (EPI == EPI_GELU_BWD) {
+    float s[4], o[4];
+    ld(g.S1, idx, s);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float ex;
+      const float ph = phi_fast(s[i], ex);
+      o[i] = a[i] * fmaf(s[i] * 0.39894228040143267794f, ex, ph);
+    }
+    st(g.C, idx, o[0], o[1], o[2], o[3]);
+  } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+    float gg[4], uu[4], dg[4], du[4];
+    ld(g.S1, idx, gg);
+    ld(g.S2, idx, uu);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float sg = sigmoid_fast(gg[i]);
+      dg[i] = a[i] * uu[i] * sg * fmaf(gg[i], 1.f - sg, 1.f);
+      du[i] = a[i] * gg[i] * sg;
+    }
+    st(g.C, idx, dg[0], dg[1], dg[2], dg[3]);
+    st(g.C2, idx, du[0], du[1], du[2], du[3]);
+  }
+}
+
+template <int BM, int BN, int BKT, bool DUAL>
+constexpr int gemm_bf16_stage_bytes() { return BM * BKT * 2 + BN * BKT * 2 * (DUAL ? 2 : 1); }
+template <int BM, int BN, int BKT, bool DUAL, int WGM, int WGN>
+constexpr int gemm_bf16_lds_bytes() {
+  constexpr int ring = NBUF * gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
+  constexpr int slab = WGM * WGN * 32 * (BN / WGN + 8) * 4;   // epilogue: one 32-row fp32 slab per wave
+  return ring > slab ? ring : slab;
+}
+
+template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmArgs g) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM / 32, WTN = BN / WGN / 32;
+  constexpr int KS = BKT / 16;               // MFMA K steps per stage (even)
+  constexpr bool A_KC = (MODE != MODE_TN);   // A stored with K contiguous
+  constexpr bool B_KC = (MODE == MODE_NT);
+  constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2;
+  constexpr int STAGE = gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
+  static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of K steps per stage");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  int e, row0, mvalid, klen, m0 = 0, n0;
+  {
+    const int ntn = (g.N + BN - 1) / BN;
+    int rt, nt;
+    if constexpr (MODE == MODE_TN) {
+      const int ntm = (g.M + BM - 1) / BM;
+      if (!block_to_tile(g.E * ntm * ntn, ntn, rt, nt)) return;
+      e = rt / ntm;
+      m0 = (rt % ntm) * BM;
+      int l, h;
+      share_of(g.lo, g.hi, g.kept[e], e, l, h);
+      row0 = g.offsets[e] + l;
+      klen = h - l;
+      mvalid = min(BM, g.M - m0);
+      if (klen == 0 && g.accumulate) return;
+    } else {
+      if (!block_to_tile(g.ntiles[0] * ntn, ntn, rt, nt)) return;
+      const RowTile t = g.tiles[rt];
+      e = t.e;
+      row0 = t.row0;
+      mvalid = t.nrows;
+      klen = g.K;
+    }
+    n0 = nt * BN;
+  }
+  const int nvalid = min(BN, g.N - n0);
+
+  f32x16 acc[WTM][WTN], acc2[DUAL ? WTM : 1][DUAL ? WTN : 1];
+#pragma unroll
+  for (int i = 0; i < WTM; ++i)
+#pragma unroll
+    for (int j = 0; j < WTN; ++j) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      if constexpr (DUAL) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc2[i][j][v] = 0.f;
+      }
+    }
+
+  const int KT = (klen + BKT - 1) / BKT;
+  typedef Stage<A_KC, BM, NT, BKT> StA;
+  typedef Stage<B_KC, BN, NT, BKT> StB;
+
+  // per-lane LDS offsets (constant for the whole kernel)
+  int a_lo[StA::CH], b_lo[StB::CH];
+#pragma unroll
+  for (int i = 0; i < StA::CH; ++i) a_lo[i] = StA::loff(i, tid);
+#pragma unroll
+  for (int i = 0; i < StB::CH; ++i) b_lo[i] = StB::loff(i, tid) + A_BYTES;
+  // fragment read offsets inside a stage.  K-contiguous: one per K step (the row term and the 32-row
+  // stride are the same for every MFMA tile); K-strided: one per MFMA tile (K steps are a constant apart).
+  int a_fr[A_KC ? KS : WTM], b_fr[B_KC ? KS : WTN];
+  if constexpr (A_KC) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) a_fr[ks] = kc_off<BKT>(wm * WTM * 32 + (lane & 31), ks * 2 + (lane >> 5));
+  } else {
+#pragma unroll
+    for (int i = 0; i < WTM; ++i)
+      a_fr[i] = ks_off<BM>(((lane >> 5) & 1) * 8 + ((lane & 15) >> 2),
+                           ((wm * WTM + i) * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2);
+  }
+  if constexpr (B_KC) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      b_fr[ks] = A_BYTES + kc_off<BKT>(wn * WTN * 32 + (lane & 31), ks * 2 + (lane >> 5));
+  } else {
+#pragma unroll
+    for (int j = 0; j < WTN; ++j)
+      b_fr[j] = A_BYTES + ks_off<BN>(((lane >> 5) & 1) * 8 + ((lane & 15) >> 2),
+                                     ((wn * WTN + j) * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2);
+  }
+
+#pragma unroll 1
+  for (int pass = 0; pass < (CHAIN ? 2 : 1); ++pass) {
+    // buffer descriptors of this tile's operands, pitches and the advance per K stage (bytes)
+    const bf16* A = reinterpret_cast<const bf16*>(pass == 0 ? g.A : g.A2);
+    const bf16* B = reinterpret_cast<const bf16*>(pass == 0 ? g.B : g.B2);
+    const bf16* B2 = reinterpret_cast<const bf16*>(g.B2);
+    rsrc_t ra, rb, rb2;
+    unsigned pa, pb, astep, bstep;
+    if constexpr (MODE == MODE_TN) {
+      // A = [rows][M] from (row0, m0), B = [rows][N] from (row0, n0); rows past the share read as zero
+      ra = make_rsrc(A + (size_t)row0 * g.M + m0, ((size_t)klen * g.M - m0) * 2);
+      rb = make_rsrc(B + (size_t)row0 * g.N + n0, ((size_t)klen * g.N - n0) * 2);
+      rb2 = rb;
+      pa = g.M * 2; pb = g.N * 2; astep = BKT * pa; bstep = BKT * pb;
+    } else if constexpr (MODE == MODE_NN) {
+      // A = [rows][K] rows row0..row0+mvalid; B = W_e [K][N] from column n0
+      ra = make_rsrc(A + (size_t)row0 * g.K, (size_t)mvalid * g.K * 2);
+      rb = make_rsrc(B + (size_t)e * g.K * g.N + n0, ((size_t)g.K * g.N - n0) * 2);
+      rb2 = make_rsrc(B2 + (size_t)e * g.K * g.N + n0, ((size_t)g.K * g.N - n0) * 2);
+      pa = g.K * 2; pb = g.N * 2; astep = BKT * 2; bstep = BKT * pb;
+    } else {
+      // A as above; B = W_e [N][K] rows n0..N
+      ra = make_rsrc(A + (size_t)row0 * g.K, (size_t)mvalid * g.K * 2);
+      rb = make_rsrc(B + ((size_t)e * g.N + n0) * g.K, (size_t)(g.N - n0) * g.K * 2);
+      rb2 = rb;
+      pa = g.K * 2; pb = g.K * 2; astep = BKT * 2; bstep = BKT * 2;
+    }
+    unsigned a_vo[StA::CH], b_vo[StB::CH];
+#pragma unroll
+    for (int i = 0; i < StA::CH; ++i) a_vo[i] = StA::goff(i, tid, pa);
+#pragma unroll
+    for (int i = 0; i < StB::CH; ++i) b_vo[i] = StB::goff(i, tid, pb);
+
+    StA sa0, sa1;
+    StB sb0, sb1, sc0, sc1;   // sc*: second weight tile of the SwiGLU forward
+    bf16x8 af[2][WTM], bfr[2][WTN], bfr2[2][DUAL ? WTN : 1];
+
+#define MOE_LOAD(n_, kt_)                                                             \
+  do {                                                                                \
+    sa##n_.load(ra, a_vo, (unsigned)(kt_) * astep);                                   \
+    sb##n_.load(rb, b_vo, (unsigned)(kt_) * bstep);                                   \
+    if constexpr (DUAL) sc##n_.load(rb2, b_vo, (unsigned)(kt_) * bstep);              \
+  } while (0)
+#define MOE_STORE(n_, buf_)                                                           \
+  do {                                                                                \
+    char* st__ = smem + (buf_);                                                       \
+    sa##n_.store(st__, a_lo);                                                         \
+    sb##n_.store(st__, b_lo);                                                         \
+    if constexpr (DUAL) sc##n_.store(st__ + B_BYTES, b_lo);                           \
+  } while (0)
+#define MOE_FRAGS(slot_, buf_, ks_)                                                                         \
+  do {                                                                                                      \
+    const char* st__ = smem + (buf_);                                                                       \
+    _Pragma("unroll") for (int i = 0; i < WTM; ++i) {                                                       \
+      if constexpr (A_KC) af[slot_][i] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + i * 32 * BKT * 2); \
+      else af[slot_][i] = lds_read_ks2<BM>(st__ + a_fr[i] + (ks_) * 16 * BM * 2);                           \
+    }                                                                                                       \
+    _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                       \
+      if constexpr (B_KC) bfr[slot_][j] = *reinterpret_cast<const bf16x8*>(st__ + b_fr[ks_] + j * 32 * BKT * 2); \
+      else bfr[slot_][j] = lds_read_ks2<BN>(st__ + b_fr[j] + (ks_) * 16 * BN * 2);                          \
+      if constexpr (DUAL) bfr2[slot_][j] = lds_read_ks2<BN>(st__ + B_BYTES + b_fr[j] + (ks_) * 16 * BN * 2); \
+    }                                                                                                       \
+  } while (0)
+// one iteration: loads for stage kt+3 into set LD_, multiply stage kt, write stage kt+2 from set ST_.
+// The three conditions are literal `true` in the steady-state loop, so that it has no branches and
+// the hardware wait counters stay exact; the last iterations use the run-time conditions.
+// cur / nxt / wr are the ring offsets of stages kt, kt+1, kt+2.
+#define MOE_ITER(kt_, LD_, ST_, DO_LOAD_, DO_STORE_, DO_NEXT_)                                              \
+  do {                                                                                                      \
+    if (DO_LOAD_) MOE_LOAD(LD_, (kt_) + 3);                                                                 \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                     \
+      if (ks + 1 < KS) MOE_FRAGS((ks + 1) & 1, cur, ks + 1);                                                \
+      else if (DO_NEXT_) MOE_FRAGS((ks + 1) & 1, nxt, 0);                                                   \
+      _Pragma("unroll") for (int i = 0; i < WTM; ++i)                                                       \
+        _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                   \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0); \
+          if constexpr (DUAL)                                                                               \
+            acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr2[ks & 1][j], acc2[i][j], 0, 0, 0); \
+        }                                                                                                   \
+    }                                                                                                       \
+    if (DO_STORE_) MOE_STORE(ST_, wr);                                                                      \
+    __syncthreads();                                                                                        \
+    { const int t__ = cur; cur = nxt; nxt = wr; wr = t__; }                                                 \
+  } while (0)
+
+    if (KT > 0) {
+      MOE_LOAD(0, 0);
+      if (KT > 1) MOE_LOAD(1, 1);
+      __syncthreads();   // every wave has finished reading the previous pass's LDS stages
+      MOE_STORE(0, 0);
+      if (KT > 1) MOE_STORE(1, STAGE);
+      if (KT > 2) MOE_LOAD(1, 2);
+      __syncthreads();
+      int cur = 0, nxt = STAGE, wr = 2 * STAGE;
+      MOE_FRAGS(0, cur, 0);
+      int kt = 0;
+#pragma unroll 1
+      for (; kt + 4 < KT; kt += 2) {
+        MOE_ITER(kt, 0, 1, true, true, true);
+        MOE_ITER(kt + 1, 1, 0, true, true, true);
+      }
+#pragma unroll 1
+      for (; kt < KT; kt += 2) {
+        MOE_ITER(kt, 0, 1, kt + 3 < KT, kt + 2 < KT, kt + 1 < KT);
+        if (kt + 1 < KT) MOE_ITER(kt + 1, 1, 0, kt + 4 < KT, kt + 3 < KT, kt + 2 < KT);
+      }
+    }
+#undef MOE_LOAD
+#undef MOE_STORE
+#undef MOE_FRAGS
+#undef MOE_ITER
+  }
+
+  if constexpr (MODE == MODE_TN) {
+    // fp32 weight gradients: 32 lanes x 4 bytes are a full line per row already
+#pragma unroll
+    for (int i = 0; i < WTM; ++i)
+#pragma unroll
+      for (int j = 0; j < WTN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = (wm * WTM + i) * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          const int n = (wn * WTN + j) * 32 + (lane & 31);
+          if (m < mvalid && n < nvalid)
+            epilogue<bf16, EPI>(g, ((size_t)e * g.M + m0 + m) * g.N + n0 + n, acc[i][j][v], 0.f);
+        }
+  } else {
+    // per-wave slab [32][WTN*32 + 8] fp32 (the ring is free: the loop ended with a block barrier)
+    constexpr int C = WTN * 32, P = C + 8, LPR = C / 4, RPP = 64 / LPR, PASSES = 32 / RPP;
+    float* slab = reinterpret_cast<float*>(smem) + wave * (32 * P);
+    const int rr = lane / LPR, c4 = lane % LPR;
+#pragma unroll
+    for (int i = 0; i < WTM; ++i) {
+      f32x4 va[PASSES], vb[DUAL ? PASSES : 1];
+#pragma unroll
+      for (int half = 0; half < (DUAL ? 2 : 1); ++half) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < WTN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int r = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+            slab[r * P + j * 32 + (lane & 31)] = (half == 0) ? acc[i][j][v] : acc2[DUAL ? i : 0][DUAL ? j : 0][v];
+          }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+          const f32x4 t = *reinterpret_cast<const f32x4*>(slab + (p * RPP + rr) * P + c4 * 4);
+          if (half == 0) va[p] = t; else vb[DUAL ? p : 0] = t;
+        }
+      }
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int m = (wm * WTM + i) * 32 + p * RPP + rr;
+        const int n = wn * C + c4 * 4;
+        if (m < mvalid && n < nvalid)
+          epilogue4<EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0]);
+      }
+    }
+  }
+}
+
+// Grid size that lets every XCD reach its whole range of tiles (see block_to_tile).
+inline unsigned gemm_bf16_grid(long long tiles) { return (unsigned)((tiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD + NUM_XCD); }
+
+}  // namespace moe
