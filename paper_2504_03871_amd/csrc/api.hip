@@ -33,6 +33,8 @@ WsLayout ws_layout(const moe_cfg* c) {
   off += align_up(16 + (size_t)max_row_tiles((int)A, c->E, TILE_ROWS_MIN) * sizeof(RowTile), 256);
   w.route_partials = off;
   off += align_up(((size_t)(c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS) * c->d_model * c->E * 4, 256);
+  w.route_wrt = off;
+  off += align_up((size_t)c->d_model * c->E * 4, 256);
   w.ffn_bwd_dact = off;
   off += align_up((c->act == MOE_ACT_SWIGLU ? 2 : 1) * A * c->d_ff * elt_size(c), 256);
   w.total = off;
@@ -42,7 +44,7 @@ WsLayout ws_layout(const moe_cfg* c) {
 // defined in the kernel files
 int launch_route(const moe_cfg*, const void*, const float*, const float*, const float*, float*, int32_t*, float*, hipStream_t);
 int launch_route_bwd(const moe_cfg*, const void*, const float*, const int32_t*, const float*, const float*, float*,
-                     float*, void*, float*, hipStream_t);
+                     float*, void*, float*, float*, hipStream_t);
 int launch_dispatch(const moe_cfg*, const void*, const int32_t*, const int32_t*, const int32_t*, int32_t*, int32_t*,
                     int32_t*, int32_t*, int32_t*, void*, int32_t*, hipStream_t);
 int launch_combine(const moe_cfg*, const void*, const float*, const int32_t*, const int32_t*, const int32_t*,
@@ -255,7 +257,8 @@ int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int3
   }
   const WsLayout w = ws_layout(cfg);
   float* partials = reinterpret_cast<float*>(static_cast<char*>(ws) + w.route_partials);
-  return launch_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, partials, s);
+  float* wrt = reinterpret_cast<float*>(static_cast<char*>(ws) + w.route_wrt);
+  return launch_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, partials, wrt, s);
 }
 
 }  // extern "C"

@@ -133,73 +133,118 @@ __global__ __launch_bounds__(RT_WAVES* WAVE) void route_kernel(
 }
 
 // ---------------------------------------------------------------- backward
-// Block = one token chunk x one column block.  Thread owns VEC adjacent columns i of x / dx / Wr.
-// LDS: s_wr[e][col] = Wr[col][e] (for dx) and s_acc[e][col] (dWr partial of this token chunk).
+// Three small kernels.
+//  1. WrT[e][i] = Wr[i][e], so that the input-gradient kernel reads contiguous weights.
+//  2. One wave per token: dsel_j = w_j (dw_j - sum_i w_i dw_i); writes the token's d_logits row and
+//     adds sum_j dsel_j WrT[e_j][:] to dx[t][:].
+//  3. dWr = x^T d_logits in its sparse form (k non-zeros per token): a block owns a tile of columns
+//     and a chunk of tokens, every wave keeps a private [E][columns] accumulator in LDS for a quarter
+//     of the chunk, the waves are summed in a fixed order and the per-chunk partials are reduced by a
+//     last kernel in chunk order, so the result is bit-reproducible.
+__global__ void wr_transpose_kernel(const float* __restrict__ Wr, float* __restrict__ WrT, int d, int E) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < d * E) WrT[(size_t)(i % E) * d + i / E] = Wr[i];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void route_bwd_dx_kernel(
+    const float* __restrict__ WrT, const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
+    const float* __restrict__ d_topk_w, float* __restrict__ d_logits, T* __restrict__ dx, int Tn, int d, int E, int k) {
+  constexpr int VN = Vec16<T>::N;
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int t = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+  if (t >= Tn) return;
+  float ds[MOE_MAX_K];
+  int ej[MOE_MAX_K];
+  float gsum = 0.f;
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_K; ++j)
+    if (j < k) gsum = fmaf(topk_w[(size_t)t * k + j], d_topk_w[(size_t)t * k + j], gsum);
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_K; ++j) {
+    ds[j] = 0.f;
+    ej[j] = 0;
+    if (j < k) {
+      ds[j] = topk_w[(size_t)t * k + j] * (d_topk_w[(size_t)t * k + j] - gsum);
+      ej[j] = topk_idx[(size_t)t * k + j];
+    }
+  }
+  for (int e = lane; e < E; e += WAVE) {
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j) v = (j < k && ej[j] == e) ? ds[j] : v;
+    d_logits[(size_t)t * E + e] = v;
+  }
+  if (dx == nullptr) return;
+  for (int c = lane * VN; c < d; c += WAVE * VN) {
+    Vec16<T> v;
+    v.load(dx + (size_t)t * d + c);
+    float acc[VN];
+    v.unpack(acc);
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j)
+      if (j < k) {
+        const float* wr = WrT + (size_t)ej[j] * d + c;
+#pragma unroll
+        for (int i = 0; i < VN; i += 4) {
+          const float4 w4 = *reinterpret_cast<const float4*>(wr + i);
+          acc[i] = fmaf(ds[j], w4.x, acc[i]);
+          acc[i + 1] = fmaf(ds[j], w4.y, acc[i + 1]);
+          acc[i + 2] = fmaf(ds[j], w4.z, acc[i + 2]);
+          acc[i + 3] = fmaf(ds[j], w4.w, acc[i + 3]);
+        }
+      }
+    v.pack(acc);
+    v.store(dx + (size_t)t * d + c);
+  }
+}
+
+constexpr int RB_MAX_WAVES = 4;  // waves per block of the dWr kernel (fewer when E is large: LDS)
+constexpr int RB_BATCH = 8;      // tokens whose x values a thread keeps in flight
+
+// Block = nw waves; thread owns VEC adjacent columns; wave w handles tokens w, w+nw, ... of the chunk.
 template <typename T, int VEC>
-__global__ void route_bwd_kernel(const T* __restrict__ x, const float* __restrict__ Wr,
-                                 const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
-                                 const float* __restrict__ d_topk_w, float* __restrict__ d_logits,
-                                 float* __restrict__ partials, T* __restrict__ dx, int Tn, int d, int E, int k,
-                                 int cols) {
+__global__ __launch_bounds__(RB_MAX_WAVES* WAVE) void route_bwd_dwr_kernel(
+    const T* __restrict__ x, const int32_t* __restrict__ topk_idx, const float* __restrict__ d_logits,
+    float* __restrict__ partials, int Tn, int d, int E, int k) {
   extern __shared__ float smem[];
-  float* s_wr = smem;                       // [E][cols]
-  float* s_acc = smem + (size_t)E * cols;   // [E][cols]
-  float* s_ds = s_acc + (size_t)E * cols;   // [ROUTE_BWD_TOKENS][k] dsel
-  int* s_e = reinterpret_cast<int*>(s_ds + ROUTE_BWD_TOKENS * MOE_MAX_K);  // [ROUTE_BWD_TOKENS][k]
-  const int c0 = blockIdx.x * cols;
+  constexpr int COLS = WAVE * VEC;
+  const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE, nw = blockDim.x / WAVE;
+  float* acc = smem + (size_t)wave * E * COLS;   // [E][COLS], private to the wave
+  const int c0 = blockIdx.x * COLS + lane * VEC;
   const int t0 = blockIdx.y * ROUTE_BWD_TOKENS;
   const int nt = min(ROUTE_BWD_TOKENS, Tn - t0);
-  const int ncol = min(cols, d - c0);
-
-  for (int i = threadIdx.x; i < E * cols; i += blockDim.x) {
-    const int e = i / cols, c = i % cols;
-    s_wr[i] = (c < ncol) ? Wr[(size_t)(c0 + c) * E + e] : 0.f;
-    s_acc[i] = 0.f;
-  }
-  for (int i = threadIdx.x; i < nt; i += blockDim.x) {
-    const size_t a0 = (size_t)(t0 + i) * k;
-    float g = 0.f;
-    for (int j = 0; j < k; ++j) g += topk_w[a0 + j] * d_topk_w[a0 + j];
-    for (int j = 0; j < k; ++j) {
-      s_ds[i * MOE_MAX_K + j] = topk_w[a0 + j] * (d_topk_w[a0 + j] - g);
-      s_e[i * MOE_MAX_K + j] = topk_idx[a0 + j];
+  for (int i = lane; i < E * COLS; i += WAVE) acc[i] = 0.f;
+  const bool live = c0 < d;   // d is a multiple of VEC
+  for (int tb = wave; tb < nt; tb += nw * RB_BATCH) {
+    float xv[RB_BATCH][VEC];
+#pragma unroll
+    for (int u = 0; u < RB_BATCH; ++u) {
+      const int t = tb + u * nw;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) xv[u][v] = (live && t < nt) ? to_f32(x[(size_t)(t0 + t) * d + c0 + v]) : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < RB_BATCH; ++u) {
+      const int t = tb + u * nw;
+      if (t < nt) {
+        for (int j = 0; j < k; ++j) {
+          const int e = topk_idx[(size_t)(t0 + t) * k + j];        // wave-uniform
+          const float ds = d_logits[(size_t)(t0 + t) * E + e];
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) acc[e * COLS + lane * VEC + v] = fmaf(ds, xv[u][v], acc[e * COLS + lane * VEC + v]);
+        }
+      }
     }
   }
   __syncthreads();
-  if (blockIdx.x == 0 && d_logits != nullptr) {
-    for (int i = threadIdx.x; i < nt * E; i += blockDim.x) {
-      const int t = i / E, e = i % E;
-      float v = 0.f;
-      for (int j = 0; j < k; ++j) v = (s_e[t * MOE_MAX_K + j] == e) ? s_ds[t * MOE_MAX_K + j] : v;
-      d_logits[(size_t)t0 * E + i] = v;
-    }
-  }
-  const int c = threadIdx.x * VEC;
-  if (c < ncol) {
-    for (int t = 0; t < nt; ++t) {
-      const size_t off = (size_t)(t0 + t) * d + c0 + c;
-      float xv[VEC], gv[VEC];
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) { xv[v] = to_f32(x[off + v]); gv[v] = 0.f; }
-      for (int j = 0; j < k; ++j) {
-        const int e = s_e[t * MOE_MAX_K + j];
-        const float ds = s_ds[t * MOE_MAX_K + j];
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-          gv[v] = fmaf(ds, s_wr[e * cols + c + v], gv[v]);
-          s_acc[e * cols + c + v] = fmaf(ds, xv[v], s_acc[e * cols + c + v]);
-        }
-      }
-      if (dx != nullptr) {
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) dx[off + v] = from_f32<T>(to_f32(dx[off + v]) + gv[v]);
-      }
-    }
-    // partials[chunk][col][e]
-    for (int e = 0; e < E; ++e)
-#pragma unroll
-      for (int v = 0; v < VEC; ++v)
-        partials[((size_t)blockIdx.y * d + c0 + c + v) * E + e] = s_acc[e * cols + c + v];
+  // sum the waves in wave order and write partials[chunk][col][e]
+  for (int i = threadIdx.x; i < E * COLS; i += blockDim.x) {
+    const int e = i / COLS, c = i % COLS;
+    float s = 0.f;
+    for (int w = 0; w < nw; ++w) s += smem[(size_t)w * E * COLS + i];
+    const int col = blockIdx.x * COLS + c;
+    if (col < d) partials[((size_t)blockIdx.y * d + col) * E + e] = s;
   }
 }
 
@@ -222,35 +267,41 @@ int launch_route(const moe_cfg* c, const void* x, const float* Wr, const float* 
   return launch_status();
 }
 
-int route_bwd_cols(int E) {
-  // 2*E*cols fp32 of LDS, at most 128 KiB; a power of two between 64 and 512
-  int cols = 512;
-  while (cols > 64 && (size_t)2 * E * cols * 4 > 128 * 1024) cols >>= 1;
-  return cols;
+template <typename T, int VEC>
+static int launch_dwr(const moe_cfg* c, const void* x, const int32_t* idx, const float* d_logits, float* partials,
+                      int chunks, hipStream_t s) {
+  int nw = RB_MAX_WAVES;
+  while (nw > 1 && (size_t)nw * c->E * WAVE * VEC * 4 > 128 * 1024) nw >>= 1;
+  const size_t lds = (size_t)nw * c->E * WAVE * VEC * 4;
+  auto kern = route_bwd_dwr_kernel<T, VEC>;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return set_hip_error(e);
+  const dim3 grid((c->d_model + WAVE * VEC - 1) / (WAVE * VEC), chunks);
+  kern<<<grid, nw * WAVE, lds, s>>>((const T*)x, idx, d_logits, partials, c->T, c->d_model, c->E, c->k);
+  return launch_status();
 }
 
 int launch_route_bwd(const moe_cfg* c, const void* x, const float* Wr, const int32_t* idx, const float* w,
-                     const float* dw, float* d_logits, float* dWr, void* dx, float* partials, hipStream_t s) {
-  const int cols = route_bwd_cols(c->E);
-  const int chunks = (c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS;
-  const dim3 grid((c->d_model + cols - 1) / cols, chunks);
-  const size_t lds = (size_t)2 * c->E * cols * 4 + ROUTE_BWD_TOKENS * MOE_MAX_K * 8;
-  constexpr int VEC = 2;
-  const int threads = cols / VEC;
-  if (c->dtype == MOE_DTYPE_BF16) {
-    auto kern = route_bwd_kernel<bf16, VEC>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return set_hip_error(e);
-    kern<<<grid, threads, lds, s>>>((const bf16*)x, Wr, idx, w, dw, d_logits, partials, (bf16*)dx, c->T, c->d_model, c->E, c->k, cols);
-  } else {
-    auto kern = route_bwd_kernel<float, VEC>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return set_hip_error(e);
-    kern<<<grid, threads, lds, s>>>((const float*)x, Wr, idx, w, dw, d_logits, partials, (float*)dx, c->T, c->d_model, c->E, c->k, cols);
-  }
-  int rc = launch_status();
-  if (rc != MOE_OK) return rc;
+                     const float* dw, float* d_logits, float* dWr, void* dx, float* partials, float* WrT,
+                     hipStream_t s) {
   const int n = c->d_model * c->E;
+  const int chunks = (c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS;
+  const bool bf = c->dtype == MOE_DTYPE_BF16;
+  int rc;
+  if (dx != nullptr) {
+    wr_transpose_kernel<<<(n + 255) / 256, 256, 0, s>>>(Wr, WrT, c->d_model, c->E);
+    if ((rc = launch_status()) != MOE_OK) return rc;
+  }
+  const int grid = (c->T + 3) / 4;
+  if (bf) route_bwd_dx_kernel<bf16><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (bf16*)dx, c->T, c->d_model, c->E, c->k);
+  else route_bwd_dx_kernel<float><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (float*)dx, c->T, c->d_model, c->E, c->k);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  // columns per thread: as many as 128 KiB of LDS allow for 4 waves x E experts (d is a multiple of 4)
+  const int vec = (c->E <= 32) ? 4 : (c->E <= 64 ? 2 : 1);
+  if (vec == 4) rc = bf ? launch_dwr<bf16, 4>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 4>(c, x, idx, d_logits, partials, chunks, s);
+  else if (vec == 2) rc = bf ? launch_dwr<bf16, 2>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 2>(c, x, idx, d_logits, partials, chunks, s);
+  else rc = bf ? launch_dwr<bf16, 1>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 1>(c, x, idx, d_logits, partials, chunks, s);
+  if (rc != MOE_OK) return rc;
   route_bwd_reduce_kernel<<<(n + 255) / 256, 256, 0, s>>>(partials, dWr, n, chunks);
   return launch_status();
 }
