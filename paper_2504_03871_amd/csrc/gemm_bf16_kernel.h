@@ -33,6 +33,12 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
+#ifndef MOE_DBG_NOLOAD   // timing experiments only (the harness defines these); always 0 in the library
+#define MOE_DBG_NOLOAD 0
+#define MOE_DBG_NOFRAG 0
+#define MOE_DBG_NOSTORE 0
+#define MOE_DBG_NOSYNC 0
+#endif
 constexpr int NUM_XCD = 8;
 constexpr int NBUF = 3;   // LDS stages in the ring
 
@@ -124,20 +130,26 @@ struct Stage {
   }
 };
 
-// Block -> tile.  Workgroups are handed to the eight XCDs round-robin; each XCD gets one contiguous
-// range of the (grouped) tile order so that tiles running together on an XCD share operand panels in
-// its L2.  Inside the order, GROUP row tiles are walked column by column.
-__device__ __forceinline__ bool block_to_tile(int n_real, int ntn, int& rt, int& nt) {
+// Block -> tile.  Tiles are numbered (row tile, column tile) with the full row tiles first.  The
+// full region is walked in groups of GROUP row tiles, column by column, and cut into one contiguous
+// range per XCD (workgroups go to the eight XCDs round-robin), so tiles that run together on an XCD
+// share operand panels in its L2.  The partly filled row tiles follow in dispatch order: they are the
+// last blocks to start and fill the chip's final round.
+__device__ __forceinline__ bool block_to_tile(int n_rt, int n_full_rt, int ntn, int& rt, int& nt) {
   constexpr int GROUP = 4;
-  const int per = (n_real + NUM_XCD - 1) / NUM_XCD;
-  const int i = blockIdx.x / NUM_XCD;
-  if (i >= per) return false;
-  const int logical = (blockIdx.x % NUM_XCD) * per + i;
-  if (logical >= n_real) return false;
-  const int nrt = n_real / ntn;
+  const int n_full = n_full_rt * ntn, n_all = n_rt * ntn;
+  const int b = blockIdx.x;
+  if (b >= n_all) return false;
+  if (b >= n_full) {                          // partial row tiles, largest first, in dispatch order
+    rt = n_full_rt + (b - n_full) / ntn;
+    nt = (b - n_full) % ntn;
+    return true;
+  }
+  const int per = n_full / NUM_XCD;           // full tiles per XCD; the few left over keep their own index
+  const int logical = (b < per * NUM_XCD) ? (b % NUM_XCD) * per + b / NUM_XCD : b;
   const int per_group = GROUP * ntn;
   const int grp = logical / per_group, in = logical % per_group;
-  const int first = grp * GROUP, gsz = min(GROUP, nrt - first);
+  const int first = grp * GROUP, gsz = min(GROUP, n_full_rt - first);
   rt = first + in % gsz;
   nt = in / gsz;
   return true;
@@ -222,7 +234,7 @@ constexpr int gemm_bf16_lds_bytes() {
 }
 
 template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmArgs g) {
+__global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 128) ? 2 : 1) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM / 32, WTN = BN / WGN / 32;
   constexpr int KS = BKT / 16;               // MFMA K steps per stage (even)
@@ -242,7 +254,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmArgs g) {
     int rt, nt;
     if constexpr (MODE == MODE_TN) {
       const int ntm = (g.M + BM - 1) / BM;
-      if (!block_to_tile(g.E * ntm * ntn, ntn, rt, nt)) return;
+      if (!block_to_tile(g.E * ntm, g.E * ntm, ntn, rt, nt)) return;
       e = rt / ntm;
       m0 = (rt % ntm) * BM;
       int l, h;
@@ -252,7 +264,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmArgs g) {
       mvalid = min(BM, g.M - m0);
       if (klen == 0 && g.accumulate) return;
     } else {
-      if (!block_to_tile(g.ntiles[0] * ntn, ntn, rt, nt)) return;
+      if (!block_to_tile(g.ntiles[0], g.ntiles[1], ntn, rt, nt)) return;
       const RowTile t = g.tiles[rt];
       e = t.e;
       row0 = t.row0;
@@ -277,6 +289,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmArgs g) {
     }
 
   const int KT = (klen + BKT - 1) / BKT;
+  // MFMA row bands of this wave that contain valid rows
+  const int ni = (MODE == MODE_TN) ? WTM : min(max((mvalid - wm * WTM * 32 + 31) / 32, 0), WTM);
   typedef Stage<A_KC, BM, NT, BKT> StA;
   typedef Stage<B_KC, BN, NT, BKT> StB;
 
@@ -359,10 +373,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmArgs g) {
     sb##n_.store(st__, b_lo);                                                         \
     if constexpr (DUAL) sc##n_.store(st__ + B_BYTES, b_lo);                           \
   } while (0)
-#define MOE_FRAGS(slot_, buf_, ks_)                                                                         \
+#define MOE_FRAGS(slot_, buf_, ks_, NI_)                                                                    \
   do {                                                                                                      \
     const char* st__ = smem + (buf_);                                                                       \
-    _Pragma("unroll") for (int i = 0; i < WTM; ++i) {                                                       \
+    _Pragma("unroll") for (int i = 0; i < WTM; ++i) if (i < (NI_)) {                                        \
       if constexpr (A_KC) af[slot_][i] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + i * 32 * BKT * 2); \
       else af[slot_][i] = lds_read_ks2<BM>(st__ + a_fr[i] + (ks_) * 16 * BM * 2);                           \
     }                                                                                                       \
@@ -376,21 +390,22 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmArgs g) {
 // The three conditions are literal `true` in the steady-state loop, so that it has no branches and
 // the hardware wait counters stay exact; the last iterations use the run-time conditions.
 // cur / nxt / wr are the ring offsets of stages kt, kt+1, kt+2.
-#define MOE_ITER(kt_, LD_, ST_, DO_LOAD_, DO_STORE_, DO_NEXT_)                                              \
+#define MOE_ITER(kt_, LD_, ST_, DO_LOAD_, DO_STORE_, DO_NEXT_, NI_)                                         \
   do {                                                                                                      \
-    if (DO_LOAD_) MOE_LOAD(LD_, (kt_) + 3);                                                                 \
+    if (DO_LOAD_ && !MOE_DBG_NOLOAD) MOE_LOAD(LD_, (kt_) + 3);                                              \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                     \
-      if (ks + 1 < KS) MOE_FRAGS((ks + 1) & 1, cur, ks + 1);                                                \
-      else if (DO_NEXT_) MOE_FRAGS((ks + 1) & 1, nxt, 0);                                                   \
-      _Pragma("unroll") for (int i = 0; i < WTM; ++i)                                                       \
+      if (MOE_DBG_NOFRAG) {}                                                                                \
+      else if (ks + 1 < KS) MOE_FRAGS((ks + 1) & 1, cur, ks + 1, NI_);                                      \
+      else if (DO_NEXT_) MOE_FRAGS((ks + 1) & 1, nxt, 0, NI_);                                              \
+      _Pragma("unroll") for (int i = 0; i < WTM; ++i) if (i < (NI_))                                        \
         _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                   \
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0); \
           if constexpr (DUAL)                                                                               \
             acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr2[ks & 1][j], acc2[i][j], 0, 0, 0); \
         }                                                                                                   \
     }                                                                                                       \
-    if (DO_STORE_) MOE_STORE(ST_, wr);                                                                      \
-    __syncthreads();                                                                                        \
+    if (DO_STORE_ && !MOE_DBG_NOSTORE) MOE_STORE(ST_, wr);                                                  \
+    if (!MOE_DBG_NOSYNC) __syncthreads();                                                                   \
     { const int t__ = cur; cur = nxt; nxt = wr; wr = t__; }                                                 \
   } while (0)
 
@@ -403,18 +418,24 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmArgs g) {
       if (KT > 2) MOE_LOAD(1, 2);
       __syncthreads();
       int cur = 0, nxt = STAGE, wr = 2 * STAGE;
-      MOE_FRAGS(0, cur, 0);
-      int kt = 0;
-#pragma unroll 1
-      for (; kt + 4 < KT; kt += 2) {
-        MOE_ITER(kt, 0, 1, true, true, true);
-        MOE_ITER(kt + 1, 1, 0, true, true, true);
-      }
-#pragma unroll 1
-      for (; kt < KT; kt += 2) {
-        MOE_ITER(kt, 0, 1, kt + 3 < KT, kt + 2 < KT, kt + 1 < KT);
-        if (kt + 1 < KT) MOE_ITER(kt + 1, 1, 0, kt + 4 < KT, kt + 3 < KT, kt + 2 < KT);
-      }
+      // A partly filled row tile multiplies only the 32-row MFMA bands that hold valid rows (ni of
+      // them in this wave); the loads, LDS traffic and barriers stay the same for every wave.
+#define MOE_MAINLOOP(NI_)                                                                       \
+  do {                                                                                          \
+    MOE_FRAGS(0, cur, 0, NI_);                                                                  \
+    int kt = 0;                                                                                 \
+    _Pragma("unroll 1") for (; kt + 4 < KT; kt += 2) {                                          \
+      MOE_ITER(kt, 0, 1, true, true, true, NI_);                                                \
+      MOE_ITER(kt + 1, 1, 0, true, true, true, NI_);                                            \
+    }                                                                                           \
+    _Pragma("unroll 1") for (; kt < KT; kt += 2) {                                              \
+      MOE_ITER(kt, 0, 1, kt + 3 < KT, kt + 2 < KT, kt + 1 < KT, NI_);                           \
+      if (kt + 1 < KT) MOE_ITER(kt + 1, 1, 0, kt + 4 < KT, kt + 3 < KT, kt + 2 < KT, NI_);      \
+    }                                                                                           \
+  } while (0)
+      if (ni == WTM) MOE_MAINLOOP(WTM);
+      else MOE_MAINLOOP(ni);
+#undef MOE_MAINLOOP
     }
 #undef MOE_LOAD
 #undef MOE_STORE
@@ -473,7 +494,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmArgs g) {
   }
 }
 
-// Grid size that lets every XCD reach its whole range of tiles (see block_to_tile).
-inline unsigned gemm_bf16_grid(long long tiles) { return (unsigned)((tiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD + NUM_XCD); }
+inline unsigned gemm_bf16_grid(long long tiles) { return (unsigned)(tiles > 0 ? tiles : 1); }
 
 }  // namespace moe

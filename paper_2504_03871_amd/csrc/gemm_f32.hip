@@ -6,32 +6,50 @@
 
 namespace moe {
 
+// Tile order: every full tile (tile_rows valid rows) first, in expert order, then the experts' last,
+// partly filled tiles by descending row count.  Blocks are dispatched in tile order, so the short
+// tiles fill the chip's last round instead of each costing a full round.
+// header[0] = number of tiles, header[1] = number of full tiles.
 __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept,
                                                        const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
                                                        int E, int tile_rows, int32_t* __restrict__ header,
                                                        RowTile* __restrict__ tiles) {
-  __shared__ int s_n[MOE_MAX_E], s_start[MOE_MAX_E + 1];
+  __shared__ int s_full[MOE_MAX_E], s_rem[MOE_MAX_E], s_start[MOE_MAX_E + 1];
+  __shared__ int s_nfull, s_npart;
   const int e = threadIdx.x;
   int l = 0, h = 0;
   if (e < E) share_of(lo, hi, kept[e], e, l, h);
-  s_n[e] = (h - l + tile_rows - 1) / tile_rows;
+  s_full[e] = (h - l) / tile_rows;
+  s_rem[e] = (h - l) % tile_rows;
   __syncthreads();
   if (threadIdx.x == 0) {
-    int run = 0;
-    for (int i = 0; i < E; ++i) { s_start[i] = run; run += s_n[i]; }
-    s_start[E] = run;
-    header[0] = run;
+    int run = 0, parts = 0;
+    for (int i = 0; i < E; ++i) { s_start[i] = run; run += s_full[i]; parts += (s_rem[i] > 0); }
+    s_nfull = run;
+    s_npart = parts;
+    header[0] = run + parts;
+    header[1] = run;
   }
   __syncthreads();
   if (e < E) {
     const int base = offsets[e] + l;
-    for (int i = 0; i < s_n[e]; ++i) {
+    for (int i = 0; i < s_full[e]; ++i) {
       RowTile t;
       t.e = e;
       t.row0 = base + i * tile_rows;
-      t.nrows = min(tile_rows, h - l - i * tile_rows);
+      t.nrows = tile_rows;
       t.pad = 0;
       tiles[s_start[e] + i] = t;
+    }
+    if (s_rem[e] > 0) {
+      int rank = 0;   // position among the partial tiles: more rows first, ties by expert id
+      for (int o = 0; o < E; ++o) rank += (s_rem[o] > s_rem[e]) || (s_rem[o] == s_rem[e] && o < e);
+      RowTile t;
+      t.e = e;
+      t.row0 = base + s_full[e] * tile_rows;
+      t.nrows = s_rem[e];
+      t.pad = 0;
+      tiles[s_nfull + rank] = t;
     }
   }
 }
