@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -94,10 +96,46 @@ def main():
         L.step()
     torch.cuda.synchronize()
 
+    # ---- HIP events around individual kernels (the library brackets the launches it is armed for)
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    per_step = {"combine": 2}     # launches per step (combine also serves the input-gradient un-permute)
+
+    def make_events(n):
+        arr = (ctypes.c_void_p * n)()
+        for i in range(n):
+            h = ctypes.c_void_p()
+            assert hip.hipEventCreate(ctypes.byref(h)) == 0
+            arr[i] = h
+        return arr
+
+    def arm(names):
+        armed = {}
+        for name in names:
+            n = args.steps * per_step.get(name, 1)
+            st, sp = make_events(n), make_events(n)
+            B.moe_profile_kernel(B.PROF[name], st, sp, n)
+            armed[name] = (st, sp, n)
+        return armed
+
+    def read(armed):
+        out = {}
+        for name, (st, sp, n) in armed.items():
+            B.moe_profile_kernel(B.PROF[name], None, None, 0)
+            tot = 0.0
+            for i in range(n):
+                f = ctypes.c_float()
+                assert hip.hipEventElapsedTime(ctypes.byref(f), st[i], sp[i]) == 0
+                tot += f.value
+            out[name] = tot / n
+        return out
+
     calls = (L.route, L.dispatch, L.ffn_fwd, L.combine, L.combine_bwd, L.ffn_bwd, L.dispatch_bwd, L.route_bwd)
+    # detail pass (untimed): every kernel bracketed, plus per-call events; also finds the dominant kernel
+    armed = arm(list(B.PROF))
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
     for s in range(args.steps):
         e = ev[s]
         e[0].record()
@@ -105,32 +143,73 @@ def main():
             fn()
             e[i + 1].record()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = read(armed)
     stage_ms = {n: float(np.mean([ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)]))
                 for i, n in enumerate(STAGES)}
+    gemm_names = ("gemm1_fwd", "gemm2_fwd", "dh_bwd", "dw2_bwd", "dw1_bwd", "dx_bwd")
+    dom = max(gemm_names, key=lambda n: kern_ms[n])
 
-    # ---- roofline of the dominant kernel group: the grouped expert GEMMs
-    per = 18 if w.act == S.ACT_SWIGLU else 12
-    flops = per * S_rows * w.d * w.f
-    gemm_ms = stage_ms["ffn_fwd"] + stage_ms["ffn_bwd"]
+    # timed region: exactly K steps, only the dominant kernel carries its event pair
+    armed = arm([dom])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        L.step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms = read(armed)[dom]
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # ---- per-kernel algorithmic work (per launch) and the roofline of the dominant kernel
+    swi = w.act == S.ACT_SWIGLU
+    per = 18 if swi else 12
+    unit = 2 * S_rows * w.d * w.f
+    flops = {"gemm1_fwd": unit * (2 if swi else 1), "gemm2_fwd": unit, "dh_bwd": unit, "dw2_bwd": unit,
+             "dw1_bwd": unit * (2 if swi else 1), "dx_bwd": unit * (2 if swi else 1)}
+    es = 2 if bf else 4
+    sb = stage_bytes(w, S_rows, es)
+    kbytes = {"gather": w.T * w.d * es + S_rows * w.d * es + w.T * w.k * 8, "combine": sb["combine"],
+              "combine_bwd": sb["combine_bwd"], "route": sb["route"]}
     peak = PEAK_BF16_TFLOPS if bf else PEAK_F32_TFLOPS
-    achieved = flops / (gemm_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "grouped expert GEMMs (ffn_fwd + ffn_bwd calls)", "achieved": round(achieved, 2),
-                "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
-                "flops_per_step": flops, "ms": round(gemm_ms, 4)}
-    sb = stage_bytes(w, S_rows, 2 if bf else 4)
+    kernels = {}
+    for name, ms in kern_ms.items():
+        d = {"us": round(ms * 1e3, 2)}
+        if name in flops:
+            tf = flops[name] / (ms * 1e-3) / 1e12
+            d.update(flops=flops[name], TFLOPs=round(tf, 1), frac_mfma=round(tf / peak, 4))
+        else:
+            gb = kbytes[name] / (ms * 1e-3) / 1e9
+            d.update(bytes=kbytes[name], GBps=round(gb, 1), frac_hbm=round(gb / PEAK_HBM_GBS, 4))
+        kernels[name] = d
+    kernels[dom].update(us_timed_region=round(dom_ms * 1e3, 2))
+    dom_tf = flops[dom] / (dom_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        tj = json.load(open(tpath))
+        traffic = tj.get(w.name, {}).get(dom)
+    roofline = {"bound": "mfma", "kernel": f"gemm_bf16_kernel ({dom})" if bf else f"gemm_f32_kernel ({dom})",
+                "achieved": round(dom_tf, 1), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(dom_tf / peak, 4), "traffic": traffic, "flops_per_launch": flops[dom],
+                "us_per_launch": round(dom_ms * 1e3, 2),
+                "all_gemms": {"flops_per_step": per * S_rows * w.d * w.f,
+                              "us_per_step": round(sum(kern_ms[n] for n in flops) * 1e3, 1),
+                              "TFLOPs": round(per * S_rows * w.d * w.f / sum(kern_ms[n] for n in flops) / 1e9, 1),
+                              "frac": round(per * S_rows * w.d * w.f / sum(kern_ms[n] for n in flops) / 1e9 / peak, 4)}}
     stages = {}
     for n in STAGES:
         d = {"ms": round(stage_ms[n], 4)}
         if n in sb:
             gbs = sb[n] / (stage_ms[n] * 1e-3) / 1e9
             d.update(bytes=sb[n], GBps=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4))
-        else:
-            fl = (per // 3 if n == "ffn_fwd" else per - per // 3) * S_rows * w.d * w.f
-            d.update(flops=fl, TFLOPs=round(fl / (stage_ms[n] * 1e-3) / 1e12, 2),
-                     frac_mfma=round(fl / (stage_ms[n] * 1e-3) / 1e12 / peak, 4))
         stages[n] = d
+
+    if args.copy_probe:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     # ---- CPU baseline: the oracle as it stands, on the host cores
     cpu = None
@@ -168,6 +247,7 @@ def main():
                                f"{'SwiGLU' if w.act == S.ACT_SWIGLU else 'GELU'} rows_computed={S_rows}"},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "kernels": kernels,
         "stages": stages,
     }
     print(json.dumps(out))

@@ -168,6 +168,27 @@ MOE_API int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, co
                   const float* topk_w, const float* d_topk_w,
                   float* d_logits, float* dWr, void* dx, void* ws, void* stream);
 
+/*
+ * Benchmark aid, not a step of the layer: while armed, every launch of kernel `which` made by this
+ * host thread is bracketed by hipEventRecord(start_events[i]) / hipEventRecord(stop_events[i]) on the
+ * launch's stream, i = launch count modulo n.  The arrays hold n hipEvent_t handles created by the
+ * caller (host memory, must stay valid while armed).  n = 0 disarms.  Do not arm under graph capture.
+ */
+enum {
+  MOE_PROF_GEMM1_FWD = 0,   /* x_perm W1 (+ activation) */
+  MOE_PROF_GEMM2_FWD = 1,   /* H W2 */
+  MOE_PROF_DH_BWD = 2,      /* dy W2^T (+ activation derivative) */
+  MOE_PROF_DW2_BWD = 3,     /* H^T dy */
+  MOE_PROF_DW1_BWD = 4,     /* x_perm^T dA (SwiGLU: both weight gradients) */
+  MOE_PROF_DX_BWD = 5,      /* dA W1^T */
+  MOE_PROF_GATHER = 6,      /* row gather of moe_dispatch */
+  MOE_PROF_COMBINE = 7,     /* moe_combine kernel */
+  MOE_PROF_COMBINE_BWD = 8, /* moe_combine_bwd kernel */
+  MOE_PROF_ROUTE = 9,       /* moe_route kernel */
+  MOE_PROF_COUNT = 10
+};
+MOE_API int moe_profile_kernel(int which, void** start_events, void** stop_events, int n);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,10 @@ MAX_E, MAX_K = 256, 8
 
 SYMBOLS = ("moe_error_string", "moe_last_hip_error", "moe_workspace_bytes", "moe_saved_bytes", "moe_route",
            "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
-           "moe_route_bwd")
+           "moe_route_bwd", "moe_profile_kernel")
+
+PROF = {"gemm1_fwd": 0, "gemm2_fwd": 1, "dh_bwd": 2, "dw2_bwd": 3, "dw1_bwd": 4, "dx_bwd": 5, "gather": 6,
+        "combine": 7, "combine_bwd": 8, "route": 9}
 
 
 class MoeCfg(ctypes.Structure):
@@ -57,6 +60,8 @@ def lib():
             "moe_combine_bwd": [cfgp] + [p] * 12,
             "moe_expert_ffn_bwd": [cfgp] + [p] * 14 + [i32, p, p],
             "moe_route_bwd": [cfgp] + [p] * 10,
+            "moe_profile_kernel": [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
+                                   ctypes.c_int],
         }
         for name, args in sig.items():
             fn = getattr(l, name)
@@ -150,3 +155,8 @@ def moe_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, ws,
     _check("moe_route_bwd", lib().moe_route_bwd(ctypes.byref(cfg), _ptr(x), _ptr(Wr), _ptr(topk_idx), _ptr(topk_w),
                                                 _ptr(d_topk_w), _ptr(d_logits), _ptr(dWr), _ptr(dx), _ptr(ws),
                                                 _stream() if stream is None else stream))
+
+
+def moe_profile_kernel(which, start_events, stop_events, n):
+    """Arm (n > 0) or disarm (n = 0) HIP-event brackets around kernel `which`; arrays of hipEvent_t handles."""
+    _check("moe_profile_kernel", lib().moe_profile_kernel(int(which), start_events, stop_events, int(n)))

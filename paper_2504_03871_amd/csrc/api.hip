@@ -1,6 +1,7 @@
 // C ABI of the MoE library: argument validation, workspace layout, kernel sequencing.
 #include "common.h"
 #include "gemm.h"
+#include "prof.h"
 
 namespace moe {
 
@@ -8,6 +9,11 @@ static thread_local int g_last_hip_error = 0;
 int set_hip_error(hipError_t e) {
   g_last_hip_error = (int)e;
   return MOE_ERR_HIP;
+}
+
+ProfSlot& prof_slot(int which) {
+  static thread_local ProfSlot slots[MOE_PROF_COUNT];
+  return slots[which];
 }
 
 int check_cfg(const moe_cfg* c) {
@@ -93,6 +99,17 @@ const char* moe_error_string(int code) {
 
 int moe_last_hip_error(void) { return g_last_hip_error; }
 
+int moe_profile_kernel(int which, void** start_events, void** stop_events, int n) {
+  if (which < 0 || which >= MOE_PROF_COUNT || n < 0) return MOE_ERR_BAD_SHAPE;
+  if (n > 0 && (start_events == nullptr || stop_events == nullptr)) return MOE_ERR_NULL;
+  ProfSlot& p = prof_slot(which);
+  p.start = start_events;
+  p.stop = stop_events;
+  p.n = n;
+  p.count = 0;
+  return MOE_OK;
+}
+
 int moe_workspace_bytes(const moe_cfg* cfg, size_t* bytes) {
   CHECK(check_cfg(cfg));
   REQUIRE(bytes);
@@ -115,6 +132,7 @@ int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* b
   REQUIRE(topk_w);
   ALIGNED(x); ALIGNED(Wr); ALIGNED(bias); ALIGNED(logits_in); ALIGNED(logits_out); ALIGNED(topk_idx); ALIGNED(topk_w);
   if (cfg->T == 0) return MOE_OK;
+  ProfScope ps(MOE_PROF_ROUTE, (hipStream_t)stream);
   return launch_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, (hipStream_t)stream);
 }
 
@@ -160,10 +178,14 @@ int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, c
   // hidden = act(x_perm W1)
   g.A = x_perm; g.B = W1; g.B2 = W1b; g.N = f; g.K = d;
   g.C = sv; g.C2 = sv + plane; g.C3 = sv + 2 * plane;
-  CHECK(launch_gemm(cfg, MODE_NN, swiglu ? EPI_SWIGLU_FWD : EPI_GELU_FWD, swiglu, false, g, max_tiles, s));
+  {
+    ProfScope ps(MOE_PROF_GEMM1_FWD, s);
+    CHECK(launch_gemm(cfg, MODE_NN, swiglu ? EPI_SWIGLU_FWD : EPI_GELU_FWD, swiglu, false, g, max_tiles, s));
+  }
   // y = hidden W2
   g.A = swiglu ? sv + 2 * plane : sv + plane; g.B = W2; g.B2 = nullptr; g.N = d; g.K = f;
   g.C = y_perm; g.C2 = g.C3 = nullptr;
+  ProfScope ps(MOE_PROF_GEMM2_FWD, s);
   return launch_gemm(cfg, MODE_NN, EPI_STORE, false, false, g, max_tiles, s);
 }
 
@@ -176,6 +198,7 @@ int moe_combine(const moe_cfg* cfg, const void* y_perm, const float* topk_w, con
   ALIGNED(y_perm); ALIGNED(topk_w); ALIGNED(topk_idx); ALIGNED(row_of); ALIGNED(offsets); ALIGNED(kept);
   ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(out);
   if (cfg->T == 0) return MOE_OK;
+  ProfScope ps(MOE_PROF_COMBINE, (hipStream_t)stream);
   return launch_combine(cfg, y_perm, topk_w, topk_idx, row_of, offsets, kept, slice_lo, slice_hi, out, accumulate,
                         (hipStream_t)stream);
 }
@@ -190,6 +213,7 @@ int moe_combine_bwd(const moe_cfg* cfg, const void* d_out, const void* y_perm, c
   ALIGNED(d_out); ALIGNED(y_perm); ALIGNED(topk_w); ALIGNED(topk_idx); ALIGNED(row_of); ALIGNED(offsets);
   ALIGNED(kept); ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(dy_perm); ALIGNED(d_topk_w);
   if (cfg->T == 0) return MOE_OK;
+  ProfScope ps(MOE_PROF_COMBINE_BWD, (hipStream_t)stream);
   return launch_combine_bwd(cfg, d_out, y_perm, topk_w, topk_idx, row_of, offsets, kept, slice_lo, slice_hi, dy_perm,
                             d_topk_w, (hipStream_t)stream);
 }
@@ -226,19 +250,29 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
   // dH = dy W2^T, fused with the activation derivative -> dA (GELU) or dG, dU (SwiGLU)
   g.A = dy_perm; g.B = W2; g.N = f; g.K = d;
   g.C = dact; g.C2 = dact + plane; g.S1 = sv; g.S2 = sv + plane;
-  CHECK(launch_gemm(cfg, MODE_NT, swiglu ? EPI_SWIGLU_BWD : EPI_GELU_BWD, false, false, g, max_tiles, s));
+  {
+    ProfScope ps(MOE_PROF_DH_BWD, s);
+    CHECK(launch_gemm(cfg, MODE_NT, swiglu ? EPI_SWIGLU_BWD : EPI_GELU_BWD, false, false, g, max_tiles, s));
+  }
   // dW2[e] = H^T dy
   g.A = hidden; g.B = dy_perm; g.M = f; g.N = d; g.K = 0; g.C = dW2; g.C2 = nullptr; g.S1 = g.S2 = nullptr;
-  CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+  {
+    ProfScope ps(MOE_PROF_DW2_BWD, s);
+    CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+  }
   // dW1[e] = x_perm^T dA   (SwiGLU: dW1 from dG, dW1b from dU)
   g.A = x_perm; g.B = dact; g.M = d; g.N = f; g.C = dW1;
-  CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
-  if (swiglu) {
-    g.B = dact + plane; g.C = dW1b;
+  {
+    ProfScope ps(MOE_PROF_DW1_BWD, s);
     CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+    if (swiglu) {
+      g.B = dact + plane; g.C = dW1b;
+      CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+    }
   }
   // dx_perm = dA W1^T   (SwiGLU: dG W1^T + dU W1b^T)
   g.A = dact; g.A2 = dact + plane; g.B = W1; g.B2 = W1b; g.M = 0; g.N = d; g.K = f; g.C = dx_perm;
+  ProfScope ps(MOE_PROF_DX_BWD, s);
   return launch_gemm(cfg, MODE_NT, EPI_STORE, false, swiglu, g, max_tiles, s);
 }
 

@@ -6,6 +6,7 @@
 // stable rank itself.  Everything here is integer work and deterministic: per-block histograms,
 // a scan over blocks, and an in-block stable rank built from wave ballots.
 #include "common.h"
+#include "prof.h"
 
 namespace moe {
 
@@ -121,11 +122,13 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(
   const int R = offsets[E];
   for (int row = wave_global; row < R; row += nwaves) {
     const int a = src_of[row];
-    const int e = topk_idx[a];
-    int l, h;
-    share_of(lo, hi, kept[e], e, l, h);
-    const int pos = row - offsets[e];
-    if (pos < l || pos >= h) continue;
+    if (lo != nullptr) {   // with no shares given every row below offsets[E] is ours: skip the expert lookup
+      const int e = topk_idx[a];
+      int l, h;
+      share_of(lo, hi, kept[e], e, l, h);
+      const int pos = row - offsets[e];
+      if (pos < l || pos >= h) continue;
+    }
     const T* src = x + (size_t)(a / k) * d;
     T* dst = x_perm + (size_t)row * d;
     for (int c = lane * VN; c < d; c += 4 * WAVE * VN) {
@@ -155,6 +158,7 @@ int launch_dispatch(const moe_cfg* c, const void* x, const int32_t* idx, const i
   dispatch_rank_kernel<<<nblk > 0 ? nblk : 1, DP_THREADS, 0, s>>>(idx, blk_cnt, A, c->E, c->capacity, nblk, counts, kept, offsets, row_of, src_of);
   rc = launch_status();
   if (rc != MOE_OK || x_perm == nullptr || A == 0) return rc;
+  ProfScope ps(MOE_PROF_GATHER, s);
   const int waves_per_block = 256 / WAVE;
   const int grid = min((A + waves_per_block - 1) / waves_per_block, 256 * 32);
   if (c->dtype == MOE_DTYPE_BF16)
