@@ -1,0 +1,168 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+cfg1 is small enough for the whole oracle.  cfg2, cfg3, cfg4 and cfg4z are checked on samples the
+oracle computes exactly: every integer output in full; sampled permuted rows through the expert FFN
+forward and backward (rows are independent); sampled hidden columns over all rows of an expert's share,
+which gives exact columns of dW1 and rows of dW2; sampled tokens for out, d_topk_w, d_logits and dx;
+and the identity dWr = x^T d_logits on the GPU's own d_logits (whose sampled rows are checked).
+"""
+import numpy as np
+import pytest
+
+from paper_2504_03871_amd import synth as S
+from tests import gpu_util as U
+from tests.test_gpu_parity import run_case
+
+pytestmark = pytest.mark.gpu
+O = U.O
+
+
+@pytest.mark.timeout(600)
+def test_cfg1_full_oracle():
+    L, ref, rep = run_case(S.WORKLOADS["cfg1"])
+    print({k: (f"{v[0]:.2e}", f"{v[1]:.2e}") if isinstance(v, tuple) else v for k, v in rep.items()}, flush=True)
+
+
+def _rows_to_sample(rng, offsets, lo, hi, per_expert):
+    rows = []
+    for e in range(len(lo)):
+        n = int(hi[e] - lo[e])
+        if n <= 0:
+            continue
+        base = int(offsets[e] + lo[e])
+        pick = {0, n - 1, min(1, n - 1), max(n - 2, 0), min(255, n - 1), min(256, n - 1)}
+        pick |= set(int(v) for v in rng.integers(0, n, size=per_expert))
+        rows += [(e, base + p) for p in sorted(pick)]
+    return rows
+
+
+def sampled_check(w: S.Workload, rows_per_expert=6, cols_per_expert=8, n_tokens=48):
+    import torch
+    rng = np.random.default_rng(1234 + w.cid)
+    print(f"[{w.name}] generating inputs", flush=True)
+    inp = S.make_inputs(w, threads=16)
+    L = U.make_layer(w, inp)
+    tol = U.TOL[w.dtype]
+    lo = hi = None
+    L.route()
+    L.dispatch(gather=False)
+    torch.cuda.synchronize()
+    if w.partial:
+        lo, hi = S.partial_slices(w, U.host(L.kept))
+        L.set_slices(lo, hi)
+    U.fill_sentinels(L)
+    print(f"[{w.name}] running the HIP path", flush=True)
+    L.forward()
+    L.backward()
+    torch.cuda.synchronize()
+
+    # ---- gate and permutation: in full
+    print(f"[{w.name}] integer stages", flush=True)
+    g_logits = L.logits.cpu().numpy()
+    x64 = inp["x"].astype(np.float64)
+    ref_logits = O.route_logits(x64, inp["Wr"], inp["bias"])
+    U.assert_close("logits", g_logits.astype(np.float64), ref_logits, tol)
+    idx, wts = O.route_topk(g_logits, w.k)
+    assert (U.host(L.topk_idx) == idx).all()
+    U.assert_close("topk_w", U.host(L.topk_w), wts, 1e-5)
+    counts, kept, offsets, row_of, src_of = O.dispatch_plan(idx, w.E, w.capacity)
+    for name, r in (("counts", counts), ("kept", kept), ("offsets", offsets), ("row_of", row_of), ("src_of", src_of)):
+        assert (U.host(getattr(L, name)) == r).all(), name
+    lo_c, hi_c = O.clamp_slices(kept, lo, hi)
+    live = np.zeros(w.T * w.k, dtype=bool)
+    for e in range(w.E):
+        live[offsets[e] + lo_c[e]: offsets[e] + hi_c[e]] = True
+    if w.capacity and w.zipf_s > 0:
+        assert (row_of < 0).any()
+    # gather: exact on every in-share row, untouched elsewhere (bit patterns compared on the device)
+    xp_ref = torch.from_numpy(inp["x_bits"].view(np.int16)).to(L.device)[torch.from_numpy(np.maximum(src_of, 0) // w.k).to(L.device)]
+    live_d = torch.from_numpy(live).to(L.device)
+    assert torch.equal(L.x_perm.view(torch.int16)[live_d], xp_ref[live_d]), "x_perm"
+    for name, t in (("x_perm", L.x_perm), ("y_perm", L.y_perm), ("dy_perm", L.dy_perm), ("dx_perm", L.dx_perm)):
+        assert bool((t[~live_d] == U.SENTINEL).all()), f"{name}: rows outside the shares were written"
+
+    # ---- sampled rows through the expert FFN, forward and backward
+    print(f"[{w.name}] sampled rows", flush=True)
+    dout64 = inp["d_out"].astype(np.float64)
+    flat_w = wts.reshape(-1)
+    planes = ("A", "H") if w.act == S.ACT_GELU else ("G", "U", "H")
+    samples = _rows_to_sample(rng, offsets, lo_c, hi_c, rows_per_expert)
+    got = {p: [] for p in planes + ("Y", "dY", "dX")}
+    exp = {p: [] for p in planes + ("Y", "dY", "dX")}
+    by_e = {}
+    for e, r in samples:
+        by_e.setdefault(e, []).append(r)
+    toks = np.unique(np.concatenate([[0, w.T - 1], rng.integers(0, w.T, size=n_tokens)]))
+    ok = O.in_share(idx, row_of, offsets, lo_c, hi_c).reshape(w.T, w.k)
+    out_ref = np.zeros((len(toks), w.d))
+    dxe_ref = np.zeros((len(toks), w.d))
+    dw_ref = np.zeros((len(toks), w.k))
+    for e, rs in by_e.items():
+        W1 = inp["W1"][e].astype(np.float64)
+        W1b = inp["W1b"][e].astype(np.float64) if w.act == S.ACT_SWIGLU else None
+        W2 = inp["W2"][e].astype(np.float64)
+        rs = np.array(rs)
+        a = src_of[rs]
+        Xb = x64[a // w.k]
+        fw = O.ffn_fwd_block(Xb, W1, W1b, W2, w.act)
+        dY = flat_w[a][:, None] * dout64[a // w.k]
+        bw = O.ffn_bwd_block(dY, Xb, fw, W1, W1b, W2, w.act)
+        rt = torch.from_numpy(rs).to(L.device)
+        for i, p in enumerate(planes):
+            got[p].append(U.host(L.saved_plane(i)[rt]))
+            exp[p].append(fw[p])
+        for name, t, r in (("Y", L.y_perm, fw["Y"]), ("dY", L.dy_perm, dY), ("dX", L.dx_perm, bw["dX"])):
+            got[name].append(U.host(t[rt]))
+            exp[name].append(r)
+        # sampled hidden columns over the whole share of this expert: exact dW1[:, c], dW2[c, :]
+        cols = np.sort(rng.choice(w.f, size=cols_per_expert, replace=False))
+        r0, r1 = offsets[e] + lo_c[e], offsets[e] + hi_c[e]
+        aa = src_of[r0:r1]
+        Xe = x64[aa // w.k]
+        dYe = flat_w[aa][:, None] * dout64[aa // w.k]
+        fwc = O.ffn_fwd_block(Xe, W1[:, cols], None if W1b is None else W1b[:, cols], W2[cols, :], w.act)
+        bwc = O.ffn_bwd_block(dYe, Xe, fwc, W1[:, cols], None if W1b is None else W1b[:, cols], W2[cols, :], w.act)
+        ct = torch.from_numpy(cols).to(L.device)
+        U.assert_close(f"dW1[{e}][:, cols]", U.host(L.dW1[e][:, ct]), bwc["dW1"], tol)
+        U.assert_close(f"dW2[{e}][cols, :]", U.host(L.dW2[e][ct, :]), bwc["dW2"], tol)
+        if W1b is not None:
+            U.assert_close(f"dW1b[{e}][:, cols]", U.host(L.dW1b[e][:, ct]), bwc["dW1b"], tol)
+        # slots of the sampled tokens that this expert serves: out, d_topk_w and the expert part of dx
+        ti, jj = np.nonzero((idx[toks] == e) & ok[toks])
+        if len(ti):
+            ts = toks[ti]
+            fws = O.ffn_fwd_block(x64[ts], W1, W1b, W2, w.act)
+            wj = wts[ts, jj][:, None]
+            np.add.at(out_ref, ti, wj * fws["Y"])
+            dw_ref[ti, jj] = np.einsum("ij,ij->i", dout64[ts], fws["Y"])
+            bws = O.ffn_bwd_block(wj * dout64[ts], x64[ts], fws, W1, W1b, W2, w.act)
+            np.add.at(dxe_ref, ti, bws["dX"])
+        del W1, W1b, W2
+    rep = {}
+    for p in got:
+        rep[p] = U.assert_close(p, np.concatenate(got[p]), np.concatenate(exp[p]), tol)
+    # experts with an empty share keep zero weight gradients
+    for e in range(w.E):
+        if hi_c[e] == lo_c[e]:
+            assert bool((L.dW1[e] == 0).all()) and bool((L.dW2[e] == 0).all())
+
+    # ---- sampled tokens: out, d_topk_w, d_logits, dx
+    print(f"[{w.name}] sampled tokens", flush=True)
+    Wr64 = inp["Wr"].astype(np.float64)
+    dl_ref, _, dxg_ref = O.route_bwd(x64[toks], Wr64, idx[toks], wts[toks], dw_ref)
+    tt = torch.from_numpy(toks).to(L.device)
+    rep["out"] = U.assert_close("out", U.host(L.out[tt]), out_ref, tol)
+    rep["d_topk_w"] = U.assert_close("d_topk_w", U.host(L.d_topk_w[tt]), dw_ref, tol)
+    rep["d_logits"] = U.assert_close("d_logits", U.host(L.d_logits[tt]), dl_ref, tol)
+    rep["dx"] = U.assert_close("dx", U.host(L.dx[tt]), dxe_ref + dxg_ref, tol)
+    # dWr against x^T d_logits evaluated in fp64 on the GPU's own d_logits
+    dWr_ref = x64.T @ U.host(L.d_logits)
+    rep["dWr"] = U.assert_close("dWr = x^T d_logits", U.host(L.dWr), dWr_ref, 1e-4)
+    print({k: (f"{v[0]:.2e}", f"{v[1]:.2e}") for k, v in rep.items()}, flush=True)
+    return rep
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["cfg2", "cfg4", "cfg4z", "cfg3"])
+def test_sampled_full_size(name):
+    sampled_check(S.WORKLOADS[name])
