@@ -36,7 +36,7 @@ WsLayout ws_layout(const moe_cfg* c) {
   w.dispatch_blk_cnt = off;
   off += align_up(((A + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK) * (size_t)c->E * 4, 256);
   w.tile_map = off;
-  off += align_up(16 + (size_t)max_row_tiles((int)A, c->E, TILE_ROWS_MIN) * sizeof(RowTile), 256);
+  off += align_up(tile_map_bytes(max_row_tiles((int)A, c->E, TILE_ROWS_MIN), c->E), 256);
   w.route_partials = off;
   off += align_up(((size_t)(c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS) * c->d_model * c->E * 4, 256);
   w.route_wrt = off;
@@ -168,12 +168,12 @@ int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, c
   const WsLayout w = ws_layout(cfg);
   const int A = cfg->T * cfg->k, d = cfg->d_model, f = cfg->d_ff;
   const int tr = tile_rows_for(cfg), max_tiles = max_row_tiles(A, cfg->E, tr);
-  TileMap map = tile_map_at(static_cast<char*>(ws) + w.tile_map);
+  TileMap map = tile_map_at(static_cast<char*>(ws) + w.tile_map, max_row_tiles(A, cfg->E, TILE_ROWS_MIN));
   CHECK(launch_tile_map(offsets, kept, slice_lo, slice_hi, cfg->E, tr, map, s));
   const size_t plane = (size_t)A * f * elt_size(cfg);
   char* sv = static_cast<char*>(saved);
   GemmArgs g = {};
-  g.tiles = map.tiles; g.ntiles = map.header;
+  g.tiles = map.tiles; g.ntiles = map.header; g.order = map.order;
   g.offsets = offsets; g.kept = kept; g.lo = slice_lo; g.hi = slice_hi; g.E = cfg->E;
   // hidden = act(x_perm W1)
   g.A = x_perm; g.B = W1; g.B2 = W1b; g.N = f; g.K = d;
@@ -237,14 +237,14 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
   const WsLayout w = ws_layout(cfg);
   const int A = cfg->T * cfg->k, d = cfg->d_model, f = cfg->d_ff;
   const int tr = tile_rows_for(cfg), max_tiles = max_row_tiles(A, cfg->E, tr);
-  TileMap map = tile_map_at(static_cast<char*>(ws) + w.tile_map);
+  TileMap map = tile_map_at(static_cast<char*>(ws) + w.tile_map, max_row_tiles(A, cfg->E, TILE_ROWS_MIN));
   CHECK(launch_tile_map(offsets, kept, slice_lo, slice_hi, cfg->E, tr, map, s));
   const size_t plane = (size_t)A * f * elt_size(cfg);
   const char* sv = static_cast<const char*>(saved);
   char* dact = static_cast<char*>(ws) + w.ffn_bwd_dact;
   const void* hidden = swiglu ? sv + 2 * plane : sv + plane;
   GemmArgs g = {};
-  g.tiles = map.tiles; g.ntiles = map.header;
+  g.tiles = map.tiles; g.ntiles = map.header; g.order = map.order;
   g.offsets = offsets; g.kept = kept; g.lo = slice_lo; g.hi = slice_hi; g.E = cfg->E;
   g.accumulate = accumulate;
   // dH = dy W2^T, fused with the activation derivative -> dA (GELU) or dG, dU (SwiGLU)

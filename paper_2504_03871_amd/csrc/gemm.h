@@ -18,14 +18,18 @@ struct RowTile {
 };
 
 // Tile map in the workspace: header[0] = number of tiles, then the tiles.
+// then order[E] = the experts by descending share length (heaviest first).
 struct TileMap {
   int32_t* header;
   RowTile* tiles;
+  int32_t* order;
 };
-inline TileMap tile_map_at(void* ws_region) {
+inline size_t tile_map_bytes(int max_tiles, int E) { return 16 + (size_t)max_tiles * sizeof(RowTile) + (size_t)E * 4; }
+inline TileMap tile_map_at(void* ws_region, int max_tiles) {
   TileMap m;
   m.header = reinterpret_cast<int32_t*>(ws_region);
   m.tiles = reinterpret_cast<RowTile*>(reinterpret_cast<char*>(ws_region) + 16);
+  m.order = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws_region) + 16 + (size_t)max_tiles * sizeof(RowTile));
   return m;
 }
 inline int max_row_tiles(int A, int E, int tile_rows) { return (A + tile_rows - 1) / tile_rows + E; }
@@ -57,6 +61,7 @@ struct GemmArgs {
   const void* S2;
   const RowTile* tiles;
   const int32_t* ntiles;
+  const int32_t* order;     // experts by descending share length (weight-gradient GEMMs start the heaviest first)
   const int32_t* offsets;
   const int32_t* kept;
   const int32_t* lo;

@@ -46,7 +46,7 @@ static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
   }
   const int ntn = (g.N + BN - 1) / BN;
   long long tiles;
-  if (MODE == MODE_TN) tiles = (long long)ntn * ((g.M + T_BM - 1) / T_BM) * g.E;
+  if (MODE == MODE_TN) tiles = (long long)((ntn * ((g.M + T_BM - 1) / T_BM) + NUM_XCD - 1) / NUM_XCD * NUM_XCD) * g.E;
   else tiles = (long long)ntn * max_tiles;
   kern<<<dim3(gemm_bf16_grid(tiles)), T_WGM * T_WGN * 64, lds, s>>>(g);
   return launch_status();

@@ -253,10 +253,18 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
     const int ntn = (g.N + BN - 1) / BN;
     int rt, nt;
     if constexpr (MODE == MODE_TN) {
+      // Weight gradients: tile (expert, m tile, n tile) costs its expert's row count.  Every expert's
+      // tiles are dealt round-robin over the XCDs (block b -> XCD b % 8), so a skewed load is even
+      // across XCDs and the tiles an XCD holds of one expert share operand panels; experts start in
+      // order of descending row count.
       const int ntm = (g.M + BM - 1) / BM;
-      if (!block_to_tile(g.E * ntm, g.E * ntm, ntn, rt, nt)) return;
-      e = rt / ntm;
-      m0 = (rt % ntm) * BM;
+      const int P = ntm * ntn, P8 = (P + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+      const int p = blockIdx.x % P8;
+      if (p >= P) return;
+      e = g.order[blockIdx.x / P8];
+      m0 = (p / ntn) * BM;
+      nt = p % ntn;
+      rt = 0;
       int l, h;
       share_of(g.lo, g.hi, g.kept[e], e, l, h);
       row0 = g.offsets[e] + l;

@@ -13,15 +13,21 @@ namespace moe {
 __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept,
                                                        const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
                                                        int E, int tile_rows, int32_t* __restrict__ header,
-                                                       RowTile* __restrict__ tiles) {
-  __shared__ int s_full[MOE_MAX_E], s_rem[MOE_MAX_E], s_start[MOE_MAX_E + 1];
+                                                       RowTile* __restrict__ tiles, int32_t* __restrict__ order) {
+  __shared__ int s_full[MOE_MAX_E], s_rem[MOE_MAX_E], s_start[MOE_MAX_E + 1], s_len[MOE_MAX_E];
   __shared__ int s_nfull, s_npart;
   const int e = threadIdx.x;
   int l = 0, h = 0;
   if (e < E) share_of(lo, hi, kept[e], e, l, h);
   s_full[e] = (h - l) / tile_rows;
   s_rem[e] = (h - l) % tile_rows;
+  s_len[e] = h - l;
   __syncthreads();
+  if (e < E) {   // experts by descending share length, ties by id
+    int rank = 0;
+    for (int o = 0; o < E; ++o) rank += (s_len[o] > s_len[e]) || (s_len[o] == s_len[e] && o < e);
+    order[rank] = e;
+  }
   if (threadIdx.x == 0) {
     int run = 0, parts = 0;
     for (int i = 0; i < E; ++i) { s_start[i] = run; run += s_full[i]; parts += (s_rem[i] > 0); }
@@ -56,7 +62,7 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
 
 int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, int E,
                     int tile_rows, TileMap map, hipStream_t s) {
-  tile_map_kernel<<<1, 256, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles);
+  tile_map_kernel<<<1, 256, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles, map.order);
   return launch_status();
 }
 
