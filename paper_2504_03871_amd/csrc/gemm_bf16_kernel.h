@@ -245,7 +245,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
   static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of K steps per stage");
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps wave-dependent values scalar
   const int wm = wave / WGN, wn = wave % WGN;
 
   int e, row0, mvalid, klen, m0 = 0, n0;
@@ -331,33 +332,35 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
                                      ((wn * WTN + j) * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2);
   }
 
-#pragma unroll 1
-  for (int pass = 0; pass < (CHAIN ? 2 : 1); ++pass) {
-    // buffer descriptors of this tile's operands, pitches and the advance per K stage (bytes)
-    const bf16* A = reinterpret_cast<const bf16*>(pass == 0 ? g.A : g.A2);
-    const bf16* B = reinterpret_cast<const bf16*>(pass == 0 ? g.B : g.B2);
-    const bf16* B2 = reinterpret_cast<const bf16*>(g.B2);
-    rsrc_t ra, rb, rb2;
+  {
+    // operand bases of this tile (a chained GEMM has two operand pairs and runs their K ranges back to
+    // back through one pipeline), byte counts the tile may read, pitches and the advance per K stage
+    const bf16* A0 = reinterpret_cast<const bf16*>(g.A);
+    const bf16* A1 = reinterpret_cast<const bf16*>(CHAIN ? g.A2 : g.A);
+    const bf16* B0 = reinterpret_cast<const bf16*>(g.B);
+    const bf16* B1 = reinterpret_cast<const bf16*>(g.B2);   // SwiGLU: second weight matrix
+    size_t aoff, boff, abytes, bbytes;
     unsigned pa, pb, astep, bstep;
     if constexpr (MODE == MODE_TN) {
       // A = [rows][M] from (row0, m0), B = [rows][N] from (row0, n0); rows past the share read as zero
-      ra = make_rsrc(A + (size_t)row0 * g.M + m0, ((size_t)klen * g.M - m0) * 2);
-      rb = make_rsrc(B + (size_t)row0 * g.N + n0, ((size_t)klen * g.N - n0) * 2);
-      rb2 = rb;
+      aoff = (size_t)row0 * g.M + m0;  abytes = ((size_t)klen * g.M - m0) * 2;
+      boff = (size_t)row0 * g.N + n0;  bbytes = ((size_t)klen * g.N - n0) * 2;
       pa = g.M * 2; pb = g.N * 2; astep = BKT * pa; bstep = BKT * pb;
     } else if constexpr (MODE == MODE_NN) {
       // A = [rows][K] rows row0..row0+mvalid; B = W_e [K][N] from column n0
-      ra = make_rsrc(A + (size_t)row0 * g.K, (size_t)mvalid * g.K * 2);
-      rb = make_rsrc(B + (size_t)e * g.K * g.N + n0, ((size_t)g.K * g.N - n0) * 2);
-      rb2 = make_rsrc(B2 + (size_t)e * g.K * g.N + n0, ((size_t)g.K * g.N - n0) * 2);
+      aoff = (size_t)row0 * g.K;  abytes = (size_t)mvalid * g.K * 2;
+      boff = (size_t)e * g.K * g.N + n0;  bbytes = ((size_t)g.K * g.N - n0) * 2;
       pa = g.K * 2; pb = g.N * 2; astep = BKT * 2; bstep = BKT * pb;
     } else {
       // A as above; B = W_e [N][K] rows n0..N
-      ra = make_rsrc(A + (size_t)row0 * g.K, (size_t)mvalid * g.K * 2);
-      rb = make_rsrc(B + ((size_t)e * g.N + n0) * g.K, (size_t)(g.N - n0) * g.K * 2);
-      rb2 = rb;
+      aoff = (size_t)row0 * g.K;  abytes = (size_t)mvalid * g.K * 2;
+      boff = ((size_t)e * g.N + n0) * g.K;  bbytes = (size_t)(g.N - n0) * g.K * 2;
       pa = g.K * 2; pb = g.K * 2; astep = BKT * 2; bstep = BKT * 2;
     }
+    const rsrc_t ra = make_rsrc(A0 + aoff, abytes), ra1 = make_rsrc(A1 + aoff, abytes);
+    const rsrc_t rb = make_rsrc(B0 + boff, bbytes), rb1 = make_rsrc(B1 + boff, bbytes);
+    const int KT1 = KT;                      // stages of one operand pair
+    const int KTT = CHAIN ? 2 * KT1 : KT1;   // stages in all
     unsigned a_vo[StA::CH], b_vo[StB::CH];
 #pragma unroll
     for (int i = 0; i < StA::CH; ++i) a_vo[i] = StA::goff(i, tid, pa);
@@ -370,9 +373,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
 
 #define MOE_LOAD(n_, kt_)                                                             \
   do {                                                                                \
-    sa##n_.load(ra, a_vo, (unsigned)(kt_) * astep);                                   \
-    sb##n_.load(rb, b_vo, (unsigned)(kt_) * bstep);                                   \
-    if constexpr (DUAL) sc##n_.load(rb2, b_vo, (unsigned)(kt_) * bstep);              \
+    const int kq__ = (kt_);                                                           \
+    const bool sec__ = CHAIN && kq__ >= KT1;                                          \
+    const unsigned kl__ = (unsigned)(sec__ ? kq__ - KT1 : kq__);                      \
+    sa##n_.load(sec__ ? ra1 : ra, a_vo, kl__ * astep);                                \
+    sb##n_.load(sec__ ? rb1 : rb, b_vo, kl__ * bstep);                                \
+    if constexpr (DUAL) sc##n_.load(rb1, b_vo, kl__ * bstep);                         \
   } while (0)
 #define MOE_STORE(n_, buf_)                                                           \
   do {                                                                                \
@@ -417,13 +423,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
     { const int t__ = cur; cur = nxt; nxt = wr; wr = t__; }                                                 \
   } while (0)
 
-    if (KT > 0) {
+    if (KTT > 0) {
       MOE_LOAD(0, 0);
-      if (KT > 1) MOE_LOAD(1, 1);
-      __syncthreads();   // every wave has finished reading the previous pass's LDS stages
+      if (KTT > 1) MOE_LOAD(1, 1);
       MOE_STORE(0, 0);
-      if (KT > 1) MOE_STORE(1, STAGE);
-      if (KT > 2) MOE_LOAD(1, 2);
+      if (KTT > 1) MOE_STORE(1, STAGE);
+      if (KTT > 2) MOE_LOAD(1, 2);
       __syncthreads();
       int cur = 0, nxt = STAGE, wr = 2 * STAGE;
       // A partly filled row tile multiplies only the 32-row MFMA bands that hold valid rows (ni of
@@ -432,13 +437,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
   do {                                                                                          \
     MOE_FRAGS(0, cur, 0, NI_);                                                                  \
     int kt = 0;                                                                                 \
-    _Pragma("unroll 1") for (; kt + 4 < KT; kt += 2) {                                          \
+    _Pragma("unroll 1") for (; kt + 4 < KTT; kt += 2) {                                         \
       MOE_ITER(kt, 0, 1, true, true, true, NI_);                                                \
       MOE_ITER(kt + 1, 1, 0, true, true, true, NI_);                                            \
     }                                                                                           \
-    _Pragma("unroll 1") for (; kt < KT; kt += 2) {                                              \
-      MOE_ITER(kt, 0, 1, kt + 3 < KT, kt + 2 < KT, kt + 1 < KT, NI_);                           \
-      if (kt + 1 < KT) MOE_ITER(kt + 1, 1, 0, kt + 4 < KT, kt + 3 < KT, kt + 2 < KT, NI_);      \
+    _Pragma("unroll 1") for (; kt < KTT; kt += 2) {                                             \
+      MOE_ITER(kt, 0, 1, kt + 3 < KTT, kt + 2 < KTT, kt + 1 < KTT, NI_);                        \
+      if (kt + 1 < KTT) MOE_ITER(kt + 1, 1, 0, kt + 4 < KTT, kt + 3 < KTT, kt + 2 < KTT, NI_);  \
     }                                                                                           \
   } while (0)
       if (ni == WTM) MOE_MAINLOOP(WTM);
