@@ -109,7 +109,9 @@ __global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
   }
 }
 
-// x_perm[row] = x[src_of[row] / k] for the rows inside this GPU's shares.  One wave per row.
+// x_perm[row] = x[src_of[row] / k] for the rows inside this GPU's shares.  A wave copies GR rows at a
+// time (their index look-ups and 16-byte loads are all issued before the first store).
+constexpr int GR = 4;
 template <typename T>
 __global__ __launch_bounds__(256) void dispatch_gather_kernel(
     const T* __restrict__ x, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ src_of,
@@ -120,25 +122,33 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(
   const int wave_global = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
   const int nwaves = gridDim.x * blockDim.x / WAVE;
   const int R = offsets[E];
-  for (int row = wave_global; row < R; row += nwaves) {
-    const int a = src_of[row];
-    if (lo != nullptr) {   // with no shares given every row below offsets[E] is ours: skip the expert lookup
-      const int e = topk_idx[a];
-      int l, h;
-      share_of(lo, hi, kept[e], e, l, h);
-      const int pos = row - offsets[e];
-      if (pos < l || pos >= h) continue;
+  for (int base = wave_global * GR; base < R; base += nwaves * GR) {
+    int tok[GR];
+#pragma unroll
+    for (int u = 0; u < GR; ++u) {
+      const int row = base + u;
+      tok[u] = -1;
+      if (row < R) {
+        const int a = src_of[row];
+        bool mine = true;
+        if (lo != nullptr) {   // with no shares given every row below offsets[E] is ours: skip the expert lookup
+          const int e = topk_idx[a];
+          int l, h;
+          share_of(lo, hi, kept[e], e, l, h);
+          const int pos = row - offsets[e];
+          mine = pos >= l && pos < h;
+        }
+        if (mine) tok[u] = a / k;
+      }
     }
-    const T* src = x + (size_t)(a / k) * d;
-    T* dst = x_perm + (size_t)row * d;
-    for (int c = lane * VN; c < d; c += 4 * WAVE * VN) {
-      Vec16<T> v[4];
+    for (int c = lane * VN; c < d; c += WAVE * VN) {
+      Vec16<T> v[GR];
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (c + u * WAVE * VN < d) v[u].load(src + c + u * WAVE * VN);
+      for (int u = 0; u < GR; ++u)
+        if (tok[u] >= 0) v[u].load(x + (size_t)tok[u] * d + c);
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (c + u * WAVE * VN < d) v[u].store(dst + c + u * WAVE * VN);
+      for (int u = 0; u < GR; ++u)
+        if (tok[u] >= 0) v[u].store(x_perm + (size_t)(base + u) * d + c);
     }
   }
 }
@@ -160,7 +170,7 @@ int launch_dispatch(const moe_cfg* c, const void* x, const int32_t* idx, const i
   if (rc != MOE_OK || x_perm == nullptr || A == 0) return rc;
   ProfScope ps(MOE_PROF_GATHER, s);
   const int waves_per_block = 256 / WAVE;
-  const int grid = min((A + waves_per_block - 1) / waves_per_block, 256 * 32);
+  const int grid = min((A + waves_per_block * GR - 1) / (waves_per_block * GR), 256 * 32);
   if (c->dtype == MOE_DTYPE_BF16)
     dispatch_gather_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)x, idx, src_of, offsets, kept, lo, hi, (bf16*)x_perm, A, c->d_model, c->E, c->k);
   else

@@ -175,12 +175,12 @@ __device__ __forceinline__ float sigmoid_fast(float g) {
 
 // Row-layout epilogue on four consecutive columns starting at flat index idx (bf16 tensors).
 template <int EPI>
-__device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f32x4& a, const f32x4& a2) {
+__device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f32x4& a, const f32x4& a2,
+                                          const u32x2& sv1, const u32x2& sv2) {
   auto st = [](void* base, size_t i, float v0, float v1, float v2, float v3) {
     *reinterpret_cast<u32x2*>(reinterpret_cast<bf16*>(base) + i) = u32x2{pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
   };
-  auto ld = [](const void* base, size_t i, float* f) {
-    const u32x2 r = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(base) + i);
+  auto ld = [](const u32x2& r, float* f) {   // four saved bf16 values, loaded by the caller ahead of time
     f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
     f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
   };
@@ -201,7 +201,7 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
     st(g.C3, idx, h[0], h[1], h[2], h[3]);
   } else if constexpr (EPI == EPI_GELU_BWD) {
     float s[4], o[4];
-    ld(g.S1, idx, s);
+    ld(sv1, s);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float ex;
@@ -211,8 +211,8 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
     st(g.C, idx, o[0], o[1], o[2], o[3]);
   } else if constexpr (EPI == EPI_SWIGLU_BWD) {
     float gg[4], uu[4], dg[4], du[4];
-    ld(g.S1, idx, gg);
-    ld(g.S2, idx, uu);
+    ld(sv1, gg);
+    ld(sv2, uu);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float sg = sigmoid_fast(gg[i]);
@@ -474,9 +474,23 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
     constexpr int C = WTN * 32, P = C + 8, LPR = C / 4, RPP = 64 / LPR, PASSES = 32 / RPP;
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * P);
     const int rr = lane / LPR, c4 = lane % LPR;
+    constexpr bool NEED_S1 = (EPI == EPI_GELU_BWD || EPI == EPI_SWIGLU_BWD), NEED_S2 = (EPI == EPI_SWIGLU_BWD);
 #pragma unroll
     for (int i = 0; i < WTM; ++i) {
       f32x4 va[PASSES], vb[DUAL ? PASSES : 1];
+      // saved tensors the backward epilogues read: issued for the whole band before the LDS round trip,
+      // so their latency hides behind it (rows past the tile read the tile's first row and are dropped)
+      u32x2 s1[NEED_S1 ? PASSES : 1], s2[NEED_S2 ? PASSES : 1];
+      if constexpr (NEED_S1) {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+          const int m = (wm * WTM + i) * 32 + p * RPP + rr, n = wn * C + c4 * 4;
+          const bool ok = m < mvalid && n < nvalid;
+          const size_t idx = (size_t)(row0 + (ok ? m : 0)) * g.N + n0 + (ok ? n : 0);
+          s1[p] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S1) + idx);
+          if constexpr (NEED_S2) s2[p] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S2) + idx);
+        }
+      }
 #pragma unroll
       for (int half = 0; half < (DUAL ? 2 : 1); ++half) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -501,7 +515,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
         const int m = (wm * WTM + i) * 32 + p * RPP + rr;
         const int n = wn * C + c4 * 4;
         if (m < mvalid && n < nvalid)
-          epilogue4<EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0]);
+          epilogue4<EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0], s1[NEED_S1 ? p : 0],
+                         s2[NEED_S2 ? p : 0]);
       }
     }
   }

@@ -7,127 +7,177 @@
 
 namespace moe {
 
-constexpr int RT_TPW = 4;                 // tokens a wave accumulates at once
-constexpr int RT_WAVES = 4;               // waves per block
-constexpr int RT_TPB = RT_TPW * RT_WAVES; // tokens per block
-constexpr int RT_EB = 8;                  // experts per accumulation pass
+// Forward kernel.  A block of 256 threads owns TOK tokens.  Thread (token, k part, expert group) keeps
+// the dot products of its token with four experts over its share of every d chunk, so x Wr needs no
+// cross-lane reduction beyond adding the k parts (adjacent lanes) at the end.  x chunks [TOK][DC] and
+// Wr chunks [DC][E4] are staged through LDS (coalesced global loads, prefetched into registers one
+// chunk ahead); the four weights of a step come from one 16-byte LDS read shared by all tokens.
+// Top-k: the G = KS*EGP lanes of a token scan the logits in LDS (expert g, g+G, ...) and run k rounds
+// of a lexicographic arg-max (larger value first, then lower expert id) with xor shuffles.
+constexpr int RT_THREADS = 256;
+constexpr int RT_XPAD = 8;   // elements of padding per staged x row (keeps 16-byte alignment, spreads banks)
 
-// One step of the transposing wave reduction: halves the number of live values per lane and
-// doubles the number of lanes each value has been summed over.
-template <int N>
-__device__ __forceinline__ void fold(float (&v)[RT_TPW * RT_EB], int lane, int bit) {
-  const bool upper = (lane & bit) != 0;
-#pragma unroll
-  for (int i = 0; i < N; ++i) {
-    const float keep = upper ? v[N + i] : v[i];
-    const float give = upper ? v[i] : v[N + i];
-    v[i] = keep + __shfl_xor(give, bit, WAVE);
-  }
+struct RouteGeom {
+  int egp_log2;   // lanes per (token, k part): pow2 >= ceil(E/4)
+  int ks_log2;    // k parts per token
+  int tok;        // tokens per block = 256 / (KS * EGP)
+  int dc;         // d elements per chunk
+  int e4;         // padded expert count = 4 * EGP
+};
+static RouteGeom route_geom(int E) {
+  RouteGeom g;
+  const int eg = (E + 3) / 4;
+  g.egp_log2 = 0;
+  while ((1 << g.egp_log2) < eg) ++g.egp_log2;
+  g.ks_log2 = 0;
+  while ((1 << (g.ks_log2 + g.egp_log2)) < 8) ++g.ks_log2;
+  g.tok = RT_THREADS >> (g.ks_log2 + g.egp_log2);
+  g.e4 = 4 << g.egp_log2;
+  g.dc = 64;
+  while (g.dc * g.e4 > 2048) g.dc >>= 1;
+  return g;
 }
 
 template <typename T>
-__global__ __launch_bounds__(RT_WAVES* WAVE) void route_kernel(
+__global__ __launch_bounds__(RT_THREADS) void route_kernel(
     const T* __restrict__ x, const float* __restrict__ Wr, const float* __restrict__ bias,
     const float* __restrict__ logits_in, float* __restrict__ logits_out,
-    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d, int E, int k) {
-  __shared__ float s_logit[RT_TPB * MOE_MAX_E];
-  const int lane = threadIdx.x & (WAVE - 1);
-  const int wave = threadIdx.x / WAVE;
-  const int tok0 = blockIdx.x * RT_TPB;
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d, int E, int k, RouteGeom gm) {
+  constexpr int VN = Vec16<T>::N;
+  extern __shared__ __attribute__((aligned(16))) char rsm[];
+  const int EGP = 1 << gm.egp_log2, KS = 1 << gm.ks_log2, G = EGP * KS, TOK = gm.tok, DC = gm.dc, E4 = gm.e4;
+  const int xpitch = DC + RT_XPAD;
+  T* xs = reinterpret_cast<T*>(rsm);                                                   // [TOK][xpitch]
+  float* wsm = reinterpret_cast<float*>(rsm + (size_t)TOK * xpitch * sizeof(T));       // [DC][E4]
+  float* s_logit = wsm + (size_t)DC * E4;                                              // [TOK][E]
+  const int tid = threadIdx.x;
+  const int eg = tid & (EGP - 1), ks = (tid >> gm.egp_log2) & (KS - 1), tl = tid >> (gm.egp_log2 + gm.ks_log2);
+  const int tok0 = blockIdx.x * TOK;
+  const int ntok = min(TOK, Tn - tok0);
 
   if (logits_in != nullptr) {
-    const int n = min(RT_TPB, Tn - tok0) * E;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) s_logit[i] = logits_in[(size_t)tok0 * E + i];
+    for (int i = tid; i < ntok * E; i += RT_THREADS) s_logit[i] = logits_in[(size_t)tok0 * E + i];
   } else {
-    constexpr int VN = Vec16<T>::N;
-    const int wt0 = tok0 + wave * RT_TPW;   // first token of this wave
-    for (int e0 = 0; e0 < E; e0 += RT_EB) {
-      float acc[RT_TPW * RT_EB];
+    const int xv_per_row = DC / VN, n_xv = TOK * xv_per_row;   // 16-byte vectors of one x chunk
+    const int n_wv = DC * E4 / 4;                              // float4 of one Wr chunk
+    Vec16<T> xr[2];
+    float4 wr[2];
+    auto fetch = [&](int c0) {
 #pragma unroll
-      for (int i = 0; i < RT_TPW * RT_EB; ++i) acc[i] = 0.f;
-      for (int c = lane * VN; c < d; c += WAVE * VN) {
-        float xv[RT_TPW][VN];
-#pragma unroll
-        for (int t = 0; t < RT_TPW; ++t) {
-          const int tok = min(wt0 + t, Tn - 1);   // clamp: rows past the end are computed, not stored
-          Vec16<T> v;
-          v.load(x + (size_t)tok * d + c);
-          v.unpack(xv[t]);
+      for (int u = 0; u < 2; ++u) {
+        const int q = tid + u * RT_THREADS;
+        if (q < n_xv) {
+          const int r = q / xv_per_row, c = c0 + (q % xv_per_row) * VN;
+          if (r < ntok && c < d) xr[u].load(x + (size_t)(tok0 + r) * d + c);
+          else { float z[VN] = {}; xr[u].pack(z); }
         }
-#pragma unroll
-        for (int i = 0; i < VN; ++i) {
-          float wv[RT_EB];
-#pragma unroll
-          for (int e = 0; e < RT_EB; ++e) wv[e] = (e0 + e < E) ? Wr[(size_t)(c + i) * E + e0 + e] : 0.f;
-#pragma unroll
-          for (int t = 0; t < RT_TPW; ++t)
-#pragma unroll
-            for (int e = 0; e < RT_EB; ++e) acc[t * RT_EB + e] = fmaf(xv[t][i], wv[e], acc[t * RT_EB + e]);
+        if (q < n_wv) {
+          const int i = c0 + (q * 4) / E4, e = (q * 4) % E4;
+          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (i < d) {
+            const float* src = Wr + (size_t)i * E + e;
+            if ((E & 3) == 0) { if (e < E) v = *reinterpret_cast<const float4*>(src); }
+            else {
+              if (e < E) v.x = src[0];
+              if (e + 1 < E) v.y = src[1];
+              if (e + 2 < E) v.z = src[2];
+              if (e + 3 < E) v.w = src[3];
+            }
+          }
+          wr[u] = v;
         }
       }
-      // 32 values over 64 lanes: after the folds lane l holds value l>>1, summed over the wave
-      fold<16>(acc, lane, 32);
-      fold<8>(acc, lane, 16);
-      fold<4>(acc, lane, 8);
-      fold<2>(acc, lane, 4);
-      fold<1>(acc, lane, 2);
-      const float total = acc[0] + __shfl_xor(acc[0], 1, WAVE);
-      const int vi = lane >> 1, t = vi / RT_EB, e = e0 + vi % RT_EB;
-      if ((lane & 1) == 0 && e < E)
-        s_logit[(wave * RT_TPW + t) * E + e] = total + (bias != nullptr ? bias[e] : 0.f);
+    };
+    auto stash = [&]() {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int q = tid + u * RT_THREADS;
+        if (q < n_xv) xr[u].store(xs + (size_t)(q / xv_per_row) * xpitch + (q % xv_per_row) * VN);
+        if (q < n_wv) *reinterpret_cast<float4*>(wsm + (size_t)q * 4) = wr[u];
+      }
+    };
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const int part = DC / KS;   // elements of a chunk this thread multiplies
+    fetch(0);
+    for (int c0 = 0; c0 < d; c0 += DC) {
+      __syncthreads();   // the previous chunk has been consumed
+      stash();
+      __syncthreads();
+      if (c0 + DC < d) fetch(c0 + DC);
+      const T* xrow = xs + (size_t)tl * xpitch + ks * part;
+      const float* wcol = wsm + (size_t)(ks * part) * E4 + eg * 4;
+      for (int ii = 0; ii < part; ii += VN) {
+        Vec16<T> xv;
+        xv.load(xrow + ii);
+        float xf[VN];
+        xv.unpack(xf);
+#pragma unroll
+        for (int u = 0; u < VN; ++u) {
+          const float4 w4 = *reinterpret_cast<const float4*>(wcol + (size_t)(ii + u) * E4);
+          acc[0] = fmaf(xf[u], w4.x, acc[0]);
+          acc[1] = fmaf(xf[u], w4.y, acc[1]);
+          acc[2] = fmaf(xf[u], w4.z, acc[2]);
+          acc[3] = fmaf(xf[u], w4.w, acc[3]);
+        }
+      }
+    }
+    // add the k parts (lanes EGP apart), fixed order
+    for (int s = EGP; s < G; s <<= 1) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[q] += __shfl_xor(acc[q], s, WAVE);
+    }
+    if (ks == 0 && tl < ntok) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int e = eg * 4 + q;
+        if (e < E) s_logit[tl * E + e] = acc[q] + (bias != nullptr ? bias[e] : 0.f);
+      }
     }
   }
   __syncthreads();
-  if (logits_out != nullptr) {
-    const int n = min(RT_TPB, Tn - tok0) * E;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) logits_out[(size_t)tok0 * E + i] = s_logit[i];
-  }
+  if (logits_out != nullptr)
+    for (int i = tid; i < ntok * E; i += RT_THREADS) logits_out[(size_t)tok0 * E + i] = s_logit[i];
 
-  // top-k: lane owns experts lane, lane+64, ...; k rounds of a wave-wide lexicographic arg-max
-  for (int t = 0; t < RT_TPW; ++t) {
-    const int tl = wave * RT_TPW + t, tok = tok0 + tl;
-    if (tok >= Tn) break;   // uniform per wave
-    float v[MOE_MAX_E / WAVE];
+  // top-k by the G lanes of each token (G <= 64 and a power of two: the lanes sit in one wave)
+  const int g = tid & (G - 1);
+  const bool live = tl < ntok;
+  unsigned taken = 0;
+  float sel[MOE_MAX_K];
+  int sid[MOE_MAX_K];
 #pragma unroll
-    for (int s = 0; s < MOE_MAX_E / WAVE; ++s) {
-      const int e = lane + s * WAVE;
-      v[s] = e < E ? s_logit[tl * E + e] : 0.f;
-    }
-    unsigned taken = 0;
-    float sel[MOE_MAX_K];
-    int sid[MOE_MAX_K];
-#pragma unroll
-    for (int j = 0; j < MOE_MAX_K; ++j) {
-      if (j < k) {
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
-#pragma unroll
-        for (int s = 0; s < MOE_MAX_E / WAVE; ++s) {
-          const int e = lane + s * WAVE;
-          if (e < E && !((taken >> s) & 1u) && (bi == 0x7fffffff || v[s] > bv)) { bv = v[s]; bi = e; }
+  for (int j = 0; j < MOE_MAX_K; ++j) {
+    if (j < k) {
+      float bv = -INFINITY;
+      int bi = 0x7fffffff;
+      if (live) {
+        int slot = 0;
+        for (int e = g; e < E; e += G, ++slot) {
+          const float v = s_logit[tl * E + e];
+          if (!((taken >> slot) & 1u) && (bi == 0x7fffffff || v > bv)) { bv = v; bi = e; }
         }
-#pragma unroll
-        for (int sft = 32; sft > 0; sft >>= 1) {
-          const float ov = __shfl_xor(bv, sft, WAVE);
-          const int oi = __shfl_xor(bi, sft, WAVE);
-          // a real candidate beats "none"; larger value wins; equal values: lower id wins
-          const bool better = (oi != 0x7fffffff) && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
-          if (better) { bv = ov; bi = oi; }
-        }
-        sel[j] = bv;
-        sid[j] = bi;
-        if ((bi & (WAVE - 1)) == lane) taken |= 1u << (bi / WAVE);
       }
+      for (int sft = G >> 1; sft > 0; sft >>= 1) {
+        const float ov = __shfl_xor(bv, sft, WAVE);
+        const int oi = __shfl_xor(bi, sft, WAVE);
+        // a real candidate beats "none"; larger value wins; equal values: lower id wins
+        const bool better = (oi != 0x7fffffff) && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+        if (better) { bv = ov; bi = oi; }
+      }
+      sel[j] = bv;
+      sid[j] = bi;
+      if (bi != 0x7fffffff && (bi & (G - 1)) == g) taken |= 1u << (bi / G);
     }
+  }
+  if (live) {
     float z[MOE_MAX_K], zs = 0.f;
 #pragma unroll
     for (int j = 0; j < MOE_MAX_K; ++j)
       if (j < k) { z[j] = expf(sel[j] - sel[0]); zs += z[j]; }
 #pragma unroll
     for (int j = 0; j < MOE_MAX_K; ++j)
-      if (j < k && lane == j) {
-        topk_idx[(size_t)tok * k + j] = sid[j];
-        topk_w[(size_t)tok * k + j] = z[j] / zs;
+      if (j < k && g == (j & (G - 1))) {
+        topk_idx[(size_t)(tok0 + tl) * k + j] = sid[j];
+        topk_w[(size_t)(tok0 + tl) * k + j] = z[j] / zs;
       }
   }
 }
@@ -211,10 +261,18 @@ __global__ __launch_bounds__(RB_MAX_WAVES* WAVE) void route_bwd_dwr_kernel(
   constexpr int COLS = WAVE * VEC;
   const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE, nw = blockDim.x / WAVE;
   float* acc = smem + (size_t)wave * E * COLS;   // [E][COLS], private to the wave
+  float* s_ds = smem + (size_t)nw * E * COLS;    // [ROUTE_BWD_TOKENS][k]: the chunk's non-zero d_logits ...
+  int* s_e = reinterpret_cast<int*>(s_ds + ROUTE_BWD_TOKENS * MOE_MAX_K);   // ... and their experts
   const int c0 = blockIdx.x * COLS + lane * VEC;
   const int t0 = blockIdx.y * ROUTE_BWD_TOKENS;
   const int nt = min(ROUTE_BWD_TOKENS, Tn - t0);
   for (int i = lane; i < E * COLS; i += WAVE) acc[i] = 0.f;
+  for (int i = threadIdx.x; i < nt * k; i += blockDim.x) {
+    const int e = topk_idx[(size_t)t0 * k + i];
+    s_e[i] = e;
+    s_ds[i] = d_logits[(size_t)(t0 + i / k) * E + e];
+  }
+  __syncthreads();
   const bool live = c0 < d;   // d is a multiple of VEC
   for (int tb = wave; tb < nt; tb += nw * RB_BATCH) {
     float xv[RB_BATCH][VEC];
@@ -229,8 +287,8 @@ __global__ __launch_bounds__(RB_MAX_WAVES* WAVE) void route_bwd_dwr_kernel(
       const int t = tb + u * nw;
       if (t < nt) {
         for (int j = 0; j < k; ++j) {
-          const int e = topk_idx[(size_t)(t0 + t) * k + j];        // wave-uniform
-          const float ds = d_logits[(size_t)(t0 + t) * E + e];
+          const int e = s_e[t * k + j];        // wave-uniform
+          const float ds = s_ds[t * k + j];
 #pragma unroll
           for (int v = 0; v < VEC; ++v) acc[e * COLS + lane * VEC + v] = fmaf(ds, xv[u][v], acc[e * COLS + lane * VEC + v]);
         }
@@ -252,6 +310,7 @@ __global__ void route_bwd_reduce_kernel(const float* __restrict__ partials, floa
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   float s = 0.f;
+#pragma unroll 8
   for (int c = 0; c < chunks; ++c) s += partials[(size_t)c * n + i];   // fixed order: deterministic
   dWr[i] = s;
 }
@@ -259,11 +318,14 @@ __global__ void route_bwd_reduce_kernel(const float* __restrict__ partials, floa
 // ---------------------------------------------------------------- launchers
 int launch_route(const moe_cfg* c, const void* x, const float* Wr, const float* bias, const float* logits_in,
                  float* logits_out, int32_t* idx, float* w, hipStream_t s) {
-  const int grid = (c->T + RT_TPB - 1) / RT_TPB;
+  const RouteGeom gm = route_geom(c->E);
+  const int grid = (c->T + gm.tok - 1) / gm.tok;
+  const size_t es = c->dtype == MOE_DTYPE_BF16 ? 2 : 4;
+  const size_t lds = (size_t)gm.tok * (gm.dc + RT_XPAD) * es + (size_t)gm.dc * gm.e4 * 4 + (size_t)gm.tok * c->E * 4;
   if (c->dtype == MOE_DTYPE_BF16)
-    route_kernel<bf16><<<grid, RT_WAVES * WAVE, 0, s>>>((const bf16*)x, Wr, bias, logits_in, logits_out, idx, w, c->T, c->d_model, c->E, c->k);
+    route_kernel<bf16><<<grid, RT_THREADS, lds, s>>>((const bf16*)x, Wr, bias, logits_in, logits_out, idx, w, c->T, c->d_model, c->E, c->k, gm);
   else
-    route_kernel<float><<<grid, RT_WAVES * WAVE, 0, s>>>((const float*)x, Wr, bias, logits_in, logits_out, idx, w, c->T, c->d_model, c->E, c->k);
+    route_kernel<float><<<grid, RT_THREADS, lds, s>>>((const float*)x, Wr, bias, logits_in, logits_out, idx, w, c->T, c->d_model, c->E, c->k, gm);
   return launch_status();
 }
 
@@ -272,7 +334,7 @@ static int launch_dwr(const moe_cfg* c, const void* x, const int32_t* idx, const
                       int chunks, hipStream_t s) {
   int nw = RB_MAX_WAVES;
   while (nw > 1 && (size_t)nw * c->E * WAVE * VEC * 4 > 128 * 1024) nw >>= 1;
-  const size_t lds = (size_t)nw * c->E * WAVE * VEC * 4;
+  const size_t lds = (size_t)nw * c->E * WAVE * VEC * 4 + (size_t)ROUTE_BWD_TOKENS * MOE_MAX_K * 8;
   auto kern = route_bwd_dwr_kernel<T, VEC>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return set_hip_error(e);
