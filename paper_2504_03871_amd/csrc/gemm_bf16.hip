@@ -5,37 +5,13 @@ namespace moe {
 
 // Block tile 256 x 256 (SwiGLU forward: 256 x 128 for each of its two weight matrices), K stage 32,
 // 2 x 4 waves: two waves per SIMD, so one wave's LDS and global traffic hides under the other's MFMAs.
+// Global loads write LDS directly (four stages in flight).
 constexpr int T_BM = 256, T_BN = 256, T_BN_DUAL = 128, T_BK = 32, T_WGM = 2, T_WGN = 4;
 int gemm_bf16_tile_rows() { return T_BM; }
-
-// Narrow variant: 256 x 128 tiles, 2 x 2 waves, two blocks per CU.  Used when the wide tiling would
-// leave most of the chip idle in its last round (few tiles: the N = d_model GEMMs of small layers);
-// twice as many, independently scheduled blocks fill the tail and overlap epilogues with MFMA work.
-constexpr int N_BN = 128, N_WGM = 2, N_WGN = 2;
-constexpr int NUM_CU = 256;
-
-template <int MODE, int EPI, bool DUAL, bool CHAIN>
-static int launch_narrow(const GemmArgs& g, int max_tiles, hipStream_t s) {
-  constexpr int lds = gemm_bf16_lds_bytes<T_BM, N_BN, T_BK, DUAL, N_WGM, N_WGN>();
-  auto kern = gemm_bf16_kernel<MODE, EPI, DUAL, CHAIN, T_BM, N_BN, T_BK, N_WGM, N_WGN>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (err != hipSuccess) return set_hip_error(err);
-    attr_done = true;
-  }
-  const long long tiles = (long long)((g.N + N_BN - 1) / N_BN) * max_tiles;
-  kern<<<dim3(gemm_bf16_grid(tiles)), N_WGM * N_WGN * 64, lds, s>>>(g);
-  return launch_status();
-}
 
 template <int MODE, int EPI, bool DUAL, bool CHAIN>
 static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
   constexpr int BN = DUAL ? T_BN_DUAL : T_BN;
-  if constexpr (MODE != MODE_TN && EPI == EPI_STORE && !DUAL && !CHAIN) {
-    // fewer than three rounds of wide tiles: the last round's idle CUs cost more than the narrower tile
-    if ((long long)((g.N + BN - 1) / BN) * max_tiles < 3 * NUM_CU) return launch_narrow<MODE, EPI, DUAL, CHAIN>(g, max_tiles, s);
-  }
   constexpr int lds = gemm_bf16_lds_bytes<T_BM, BN, T_BK, DUAL, T_WGM, T_WGN>();
   auto kern = gemm_bf16_kernel<MODE, EPI, DUAL, CHAIN, T_BM, BN, T_BK, T_WGM, T_WGN>;
   static bool attr_done = false;   // benign race: the attribute call is idempotent

@@ -3,11 +3,15 @@
 // Work decomposition: block tile BM x BN, WGM x WGN waves, each wave owns (BM/WGM) x (BN/WGN) as a
 // grid of 32x32 MFMA tiles; K advances BKT elements per stage.
 //
-// Pipeline: a ring of three LDS stages.  Global loads for stage kt+3 are issued at the top of
-// iteration kt into one of two register sets and written to LDS one iteration later, so a load has
-// two iterations of MFMA work to land.  Stage kt+1 is complete and visible a full iteration before
-// it is needed, which lets each wave fetch the first fragments of the next stage before the
-// block barrier: the barrier only guards buffer reuse and is off the MFMA critical path.
+// Pipeline: a ring of four LDS stages filled by buffer loads that write LDS directly (no staging
+// registers, no LDS store instructions).  Iteration kt issues the loads of stage kt+3, multiplies
+// stage kt, then waits for its own loads of stage kt+2 and joins the block barrier; so a load has
+// between one and two iterations of MFMA work to land, and stage kt+1 is complete and visible a full
+// iteration before it is needed, which lets each wave fetch the first fragments of the next stage
+// before the barrier: the barrier only guards buffer reuse and is off the MFMA critical path.
+// LDS fragment reads are issued as raw instructions with explicit waits: the compiler cannot tell
+// that a fragment read never touches the stage a direct load is filling and would otherwise wait
+// for every outstanding global load before each read.
 //
 // Operands: one whose K index is contiguous in memory is kept as [rows][BKT] in LDS and read with
 // 16-byte LDS reads; one whose K index is strided is kept exactly as it lies in memory, [BKT][cols],
@@ -33,14 +37,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
-#ifndef MOE_DBG_NOLOAD   // timing experiments only (the harness defines these); always 0 in the library
-#define MOE_DBG_NOLOAD 0
-#define MOE_DBG_NOFRAG 0
-#define MOE_DBG_NOSTORE 0
-#define MOE_DBG_NOSYNC 0
-#endif
 constexpr int NUM_XCD = 8;
-constexpr int NBUF = 3;   // LDS stages in the ring
+constexpr int NBUF = 4;   // LDS stages in the ring
 
 // ---- LDS layouts -------------------------------------------------------------------------------
 // K-contiguous tile: [rows][BKT] bf16.  The 16-byte chunks of a row are XOR-swizzled with the index
@@ -58,40 +56,35 @@ __device__ __forceinline__ int ks_off(int krow, int col_byte) {
   return krow * (W * 2) + ((((col_byte >> 6) ^ (krow & 3)) << 6) | (col_byte & 63));
 }
 
-template <int BKT>
-__device__ __forceinline__ bf16x8 lds_read_kc(const char* tile, int row, int chunk) {
-  return *reinterpret_cast<const bf16x8*>(tile + kc_off<BKT>(row, chunk));
+// Fragment reads.  Eight K values of one K step for column l%32 of a K-strided tile come from two
+// transposing reads: the instruction works on blocks of 16 lanes, lane s of a block reads 8 bytes at
+// (K row s/4, columns 4*(s%4)..+3) and receives the four K rows of column s; the second read lies
+// four K rows further on.  All fragment reads are raw instructions (see the pipeline note above);
+// the caller waits for the data itself (lds_wait).
+typedef __attribute__((address_space(3))) char lds_char;
+__device__ __forceinline__ unsigned lds_addr(const char* p) { return (unsigned)(uintptr_t)(const lds_char*)p; }
+// `off` must fold to a constant (it is the instruction's immediate offset).
+__device__ __forceinline__ s16x4 ds_read_tr_raw(unsigned addr, int off) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(off));
+  return v;
 }
-// Eight K values of K step `kstep` for column col_base + l%32 from a K-strided tile.  The
-// transposing read works on blocks of 16 lanes: lane s of a block reads 8 bytes at (K row s/4,
-// columns 4*(s%4)..+3) and receives the four K rows of column s.
 template <int W>
-__device__ __forceinline__ bf16x8 lds_read_ks(const char* tile, int kstep, int col_base, int lane) {
-  const int b = lane >> 4, s = lane & 15;
-  const int krow = kstep * 16 + (b >> 1) * 8 + (s >> 2);
-  const int colb = (col_base + (b & 1) * 16 + (s & 3) * 4) * 2;
-  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + ks_off<W>(krow, colb)));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + ks_off<W>(krow + 4, colb)));
-  union { struct { s16x4 a, b; } p; bf16x8 v; } u;
-  u.p.a = lo;
-  u.p.b = hi;
-  return u.v;
-}
-
-// Same, from a precomputed per-lane address: the second half lies four K rows further on.
-template <int W>
-__device__ __forceinline__ bf16x8 lds_read_ks2(const char* p) {
-  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * W * 2));
+__device__ __forceinline__ bf16x8 lds_read_ks2_raw(unsigned addr, int off) {
   union { struct { s16x4 a, b; } q; bf16x8 v; } u;
-  u.q.a = lo;
-  u.q.b = hi;
+  u.q.a = ds_read_tr_raw(addr, off);
+  u.q.b = ds_read_tr_raw(addr, off + 4 * W * 2);
   return u.v;
 }
+__device__ __forceinline__ bf16x8 lds_read_b128_raw(unsigned addr, int off) {
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(off));
+  return v;
+}
+// Wait until every LDS read issued so far has returned; tied to `v` so that its uses stay behind the wait.
+__device__ __forceinline__ void lds_wait(bf16x8& v) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v)); }
 
-// ---- global -> register -> LDS staging of one stage --------------------------------------------
+// ---- global -> LDS loads of one stage ------------------------------------------------------------
 // Global loads are raw buffer loads: the descriptor's byte count is set to the part of the operand
 // this tile may read, and the hardware returns zero for anything past it.  That gives the ragged
 // edges (rows past an expert's share, K rows past the share in the weight-gradient GEMM, columns past
@@ -102,31 +95,32 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, size_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
 }
 
-// One operand tile of one stage.  KC: [ROWS][BKT], thread chunk id -> (row id/CPR, chunk id%CPR).
+// 16 bytes per lane from a buffer straight into LDS: lane l of the wave lands at lds + 16*l
+// (lds must be wave-uniform).  Completion is tracked by vmcnt like any other buffer load.
+__device__ __forceinline__ void load_to_lds16(rsrc_t rs, char* lds, unsigned voffset) {
+  typedef __attribute__((address_space(3))) void lds_void;
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)lds, 16, voffset, 0, 0, 0);
+}
+
+// One operand tile of one stage, cut into 16-byte chunks; thread tid moves chunks tid + NT*i.
+// KC: [ROWS][BKT], chunk id -> (row id/CPR, chunk id%CPR).
 // KS: [BKT][ROWS] (ROWS = tile width), chunk id -> (K row id/(ROWS/8), chunk id%(ROWS/8)).
 template <bool KC, int ROWS, int NT, int BKT>
 struct Stage {
   static constexpr int CPR = KC ? BKT / 8 : ROWS / 8;
   static constexpr int CH = ROWS * BKT / 8 / NT;
   static_assert(CH >= 1, "tile too small for this many threads");
-  u32x4 r[CH];
-  // byte offset of chunk i of this thread inside the operand (pitch in bytes), and inside the LDS tile
+  // A direct load places lane l of a wave at byte 16*l of the instruction's LDS window, so chunk id
+  // lands at byte 16*id of the tile; this is the operand byte offset (pitch in bytes) whose data
+  // belongs there: the tile's swizzle, inverted.
   static __device__ __forceinline__ unsigned goff(int i, int tid, unsigned pitch) {
-    const int id = tid + NT * i;
-    return (unsigned)(id / CPR) * pitch + (unsigned)(id % CPR) * 16u;
-  }
-  static __device__ __forceinline__ int loff(int i, int tid) {
-    const int id = tid + NT * i;
-    if constexpr (KC) return kc_off<BKT>(id / CPR, id % CPR);
-    else return ks_off<ROWS>(id / CPR, (id % CPR) * 16);
-  }
-  __device__ __forceinline__ void load(rsrc_t rs, const unsigned (&voff)[CH], unsigned adv) {
-#pragma unroll
-    for (int i = 0; i < CH; ++i) r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff[i] + adv, 0, 0);
-  }
-  __device__ __forceinline__ void store(char* tile, const int (&lo)[CH]) const {
-#pragma unroll
-    for (int i = 0; i < CH; ++i) *reinterpret_cast<u32x4*>(tile + lo[i]) = r[i];
+    const int id = tid + NT * i, r = id / CPR, pc = id % CPR;
+    if constexpr (KC) {
+      constexpr int RP = 256 / (BKT * 2);
+      return (unsigned)r * pitch + (unsigned)(pc ^ ((r / RP) & (CPR - 1))) * 16u;
+    } else {
+      return (unsigned)r * pitch + (unsigned)((((pc >> 2) ^ (r & 3)) << 2) | (pc & 3)) * 16u;
+    }
   }
 };
 
@@ -234,7 +228,7 @@ constexpr int gemm_bf16_lds_bytes() {
 }
 
 template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN>
-__global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 128) ? 2 : 1) void gemm_bf16_kernel(GemmArgs g) {
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM / 32, WTN = BN / WGN / 32;
   constexpr int KS = BKT / 16;               // MFMA K steps per stage (even)
@@ -243,6 +237,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
   constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2;
   constexpr int STAGE = gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
   static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of K steps per stage");
+  static_assert(NBUF == 4, "the ring rotation below is written for four stages");
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -303,12 +298,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
   typedef Stage<A_KC, BM, NT, BKT> StA;
   typedef Stage<B_KC, BN, NT, BKT> StB;
 
-  // per-lane LDS offsets (constant for the whole kernel)
-  int a_lo[StA::CH], b_lo[StB::CH];
-#pragma unroll
-  for (int i = 0; i < StA::CH; ++i) a_lo[i] = StA::loff(i, tid);
-#pragma unroll
-  for (int i = 0; i < StB::CH; ++i) b_lo[i] = StB::loff(i, tid) + A_BYTES;
   // fragment read offsets inside a stage.  K-contiguous: one per K step (the row term and the 32-row
   // stride are the same for every MFMA tile); K-strided: one per MFMA tile (K steps are a constant apart).
   int a_fr[A_KC ? KS : WTM], b_fr[B_KC ? KS : WTN];
@@ -361,98 +350,112 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN == 4 && BM * BN <= 256 * 
     const rsrc_t rb = make_rsrc(B0 + boff, bbytes), rb1 = make_rsrc(B1 + boff, bbytes);
     const int KT1 = KT;                      // stages of one operand pair
     const int KTT = CHAIN ? 2 * KT1 : KT1;   // stages in all
+    // Iteration kt issues the loads of stage kt+3, multiplies stage kt, then waits until its own loads
+    // of stage kt+2 have landed (all but the newest stage) and joins the block barrier, after which
+    // stage kt+2 is visible to every wave and stage kt's buffer may be overwritten.
+    constexpr int L = StA::CH + StB::CH * (DUAL ? 2 : 1);                    // loads per thread per stage
+    constexpr int WAIT_L = (L & 15) | ((L >> 4) << 14) | 0x70 | (15 << 8);   // s_waitcnt vmcnt(L) only
+    constexpr int WAIT_0 = 0x70 | (15 << 8);                                 // s_waitcnt vmcnt(0) only
     unsigned a_vo[StA::CH], b_vo[StB::CH];
 #pragma unroll
     for (int i = 0; i < StA::CH; ++i) a_vo[i] = StA::goff(i, tid, pa);
 #pragma unroll
     for (int i = 0; i < StB::CH; ++i) b_vo[i] = StB::goff(i, tid, pb);
-
-    StA sa0, sa1;
-    StB sb0, sb1, sc0, sc1;   // sc*: second weight tile of the SwiGLU forward
+    const int wbase = wave * 1024;   // a wave's 64 lanes fill 1 KB of the tile per load
+    const unsigned smem_base = lds_addr(smem);
+    // The next K step's fragment reads are spread over the first MFMAs of the current one, UPM read
+    // units per MFMA (scheduling fences keep that order), so the LDS pipe sees a steady trickle
+    // instead of bursts and every read has at least half a K step of MFMAs to land.
+    constexpr int UPM = 2;
+    static_assert(UPM * WTM * WTN >= WTM + WTN, "not every fragment would be read");
     bf16x8 af[2][WTM], bfr[2][WTN], bfr2[2][DUAL ? WTN : 1];
-
-#define MOE_LOAD(n_, kt_)                                                             \
-  do {                                                                                \
-    const int kq__ = (kt_);                                                           \
-    const bool sec__ = CHAIN && kq__ >= KT1;                                          \
-    const unsigned kl__ = (unsigned)(sec__ ? kq__ - KT1 : kq__);                      \
-    sa##n_.load(sec__ ? ra1 : ra, a_vo, kl__ * astep);                                \
-    sb##n_.load(sec__ ? rb1 : rb, b_vo, kl__ * bstep);                                \
-    if constexpr (DUAL) sc##n_.load(rb1, b_vo, kl__ * bstep);                         \
-  } while (0)
-#define MOE_STORE(n_, buf_)                                                           \
-  do {                                                                                \
-    char* st__ = smem + (buf_);                                                       \
-    sa##n_.store(st__, a_lo);                                                         \
-    sb##n_.store(st__, b_lo);                                                         \
-    if constexpr (DUAL) sc##n_.store(st__ + B_BYTES, b_lo);                           \
-  } while (0)
-#define MOE_FRAGS(slot_, buf_, ks_, NI_)                                                                    \
+#define MOE_LOAD(kt_, buf_)                                                                                 \
   do {                                                                                                      \
-    const char* st__ = smem + (buf_);                                                                       \
-    _Pragma("unroll") for (int i = 0; i < WTM; ++i) if (i < (NI_)) {                                        \
-      if constexpr (A_KC) af[slot_][i] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + i * 32 * BKT * 2); \
-      else af[slot_][i] = lds_read_ks2<BM>(st__ + a_fr[i] + (ks_) * 16 * BM * 2);                           \
-    }                                                                                                       \
-    _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                       \
-      if constexpr (B_KC) bfr[slot_][j] = *reinterpret_cast<const bf16x8*>(st__ + b_fr[ks_] + j * 32 * BKT * 2); \
-      else bfr[slot_][j] = lds_read_ks2<BN>(st__ + b_fr[j] + (ks_) * 16 * BN * 2);                          \
-      if constexpr (DUAL) bfr2[slot_][j] = lds_read_ks2<BN>(st__ + B_BYTES + b_fr[j] + (ks_) * 16 * BN * 2); \
+    const int kq__ = (kt_);                                                                                 \
+    const bool sec__ = CHAIN && kq__ >= KT1;                                                                \
+    const unsigned kl__ = (unsigned)(sec__ ? kq__ - KT1 : kq__);                                            \
+    char* st__ = smem + (buf_) + wbase;                                                                     \
+    _Pragma("unroll") for (int i = 0; i < StA::CH; ++i)                                                     \
+      load_to_lds16(sec__ ? ra1 : ra, st__ + NT * 16 * i, a_vo[i] + kl__ * astep);                          \
+    _Pragma("unroll") for (int i = 0; i < StB::CH; ++i) {                                                   \
+      load_to_lds16(sec__ ? rb1 : rb, st__ + A_BYTES + NT * 16 * i, b_vo[i] + kl__ * bstep);                \
+      if constexpr (DUAL) load_to_lds16(rb1, st__ + A_BYTES + B_BYTES + NT * 16 * i, b_vo[i] + kl__ * bstep); \
     }                                                                                                       \
   } while (0)
-// one iteration: loads for stage kt+3 into set LD_, multiply stage kt, write stage kt+2 from set ST_.
-// The three conditions are literal `true` in the steady-state loop, so that it has no branches and
-// the hardware wait counters stay exact; the last iterations use the run-time conditions.
-// cur / nxt / wr are the ring offsets of stages kt, kt+1, kt+2.
-#define MOE_ITER(kt_, LD_, ST_, DO_LOAD_, DO_STORE_, DO_NEXT_, NI_)                                         \
+// read unit u of K step ks_ of the stage at buf_ into fragment slot slot_: units 0..WTN-1 are the B
+// fragments, WTN..WTN+WTM-1 the A fragments (only the NI_ row bands that hold valid rows)
+#define MOE_UNIT(u_, slot_, buf_, ks_, NI_)                                                                 \
   do {                                                                                                      \
-    if (DO_LOAD_ && !MOE_DBG_NOLOAD) MOE_LOAD(LD_, (kt_) + 3);                                              \
+    const unsigned sa__ = smem_base + (buf_);                                                               \
+    if ((u_) < WTN) {                                                                                       \
+      const int j = (u_);                                                                                   \
+      if constexpr (B_KC) bfr[slot_][j] = lds_read_b128_raw(sa__ + b_fr[ks_], j * 32 * BKT * 2);            \
+      else bfr[slot_][j] = lds_read_ks2_raw<BN>(sa__ + b_fr[j], (ks_) * 16 * BN * 2);                       \
+      if constexpr (DUAL) bfr2[slot_][j] = lds_read_ks2_raw<BN>(sa__ + b_fr[j], B_BYTES + (ks_) * 16 * BN * 2); \
+    } else if ((u_) - WTN < WTM && (u_) - WTN < (NI_)) {                                                    \
+      const int i = (u_) - WTN;                                                                             \
+      if constexpr (A_KC) af[slot_][i] = lds_read_b128_raw(sa__ + a_fr[ks_], i * 32 * BKT * 2);             \
+      else af[slot_][i] = lds_read_ks2_raw<BM>(sa__ + a_fr[i], (ks_) * 16 * BM * 2);                        \
+    }                                                                                                       \
+  } while (0)
+// the raw reads of a slot must have returned before its MFMAs
+#define MOE_WAIT(slot_, NI_)                                                                                \
+  do {                                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < WTM; ++i) if (i < (NI_)) lds_wait(af[slot_][i]);                  \
+    _Pragma("unroll") for (int j = 0; j < WTN; ++j) { lds_wait(bfr[slot_][j]); if constexpr (DUAL) lds_wait(bfr2[slot_][j]); } \
+  } while (0)
+// One iteration.  DO_LOAD_ and DO_NEXT_ are literal `true` in the steady-state loop, so that it has
+// no branches; the last iterations use the run-time conditions.
+#define MOE_ITER(kt_, DO_LOAD_, DO_NEXT_, NI_)                                                              \
+  do {                                                                                                      \
+    if (DO_LOAD_) MOE_LOAD((kt_) + 3, b3);                                                                  \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                     \
-      if (MOE_DBG_NOFRAG) {}                                                                                \
-      else if (ks + 1 < KS) MOE_FRAGS((ks + 1) & 1, cur, ks + 1, NI_);                                      \
-      else if (DO_NEXT_) MOE_FRAGS((ks + 1) & 1, nxt, 0, NI_);                                              \
-      _Pragma("unroll") for (int i = 0; i < WTM; ++i) if (i < (NI_))                                        \
-        _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                   \
+      MOE_WAIT(ks & 1, NI_);                                                                                \
+      _Pragma("unroll") for (int m = 0; m < WTM * WTN; ++m) {                                               \
+        const int i = m / WTN, j = m % WTN;                                                                 \
+        _Pragma("unroll") for (int u = m * UPM; u < (m + 1) * UPM; ++u) {                                   \
+          if (ks + 1 < KS) MOE_UNIT(u, (ks + 1) & 1, b0, ks + 1, NI_);                                      \
+          else if (DO_NEXT_) MOE_UNIT(u, (ks + 1) & 1, b1, 0, NI_);                                         \
+        }                                                                                                   \
+        if (i < (NI_)) {                                                                                    \
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0); \
           if constexpr (DUAL)                                                                               \
             acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr2[ks & 1][j], acc2[i][j], 0, 0, 0); \
         }                                                                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
+      }                                                                                                     \
     }                                                                                                       \
-    if (DO_STORE_ && !MOE_DBG_NOSTORE) MOE_STORE(ST_, wr);                                                  \
-    if (!MOE_DBG_NOSYNC) __syncthreads();                                                                   \
-    { const int t__ = cur; cur = nxt; nxt = wr; wr = t__; }                                                 \
+    if (DO_LOAD_) __builtin_amdgcn_s_waitcnt(WAIT_L); else __builtin_amdgcn_s_waitcnt(WAIT_0);              \
+    asm volatile("" ::: "memory");                                                                          \
+    __builtin_amdgcn_s_barrier();                                                                           \
+    asm volatile("" ::: "memory");                                                                          \
+    { const int t__ = b0; b0 = b1; b1 = b2; b2 = b3; b3 = t__; }                                            \
   } while (0)
-
     if (KTT > 0) {
-      MOE_LOAD(0, 0);
-      if (KTT > 1) MOE_LOAD(1, 1);
-      MOE_STORE(0, 0);
-      if (KTT > 1) MOE_STORE(1, STAGE);
-      if (KTT > 2) MOE_LOAD(1, 2);
-      __syncthreads();
-      int cur = 0, nxt = STAGE, wr = 2 * STAGE;
+      int b0 = 0, b1 = STAGE, b2 = 2 * STAGE, b3 = 3 * STAGE;   // ring offsets of stages kt .. kt+3
+      MOE_LOAD(0, b0);
+      if (KTT > 1) MOE_LOAD(1, b1);
+      if (KTT > 2) { MOE_LOAD(2, b2); __builtin_amdgcn_s_waitcnt(WAIT_L); }
+      else __builtin_amdgcn_s_waitcnt(WAIT_0);
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
       // A partly filled row tile multiplies only the 32-row MFMA bands that hold valid rows (ni of
-      // them in this wave); the loads, LDS traffic and barriers stay the same for every wave.
+      // them in this wave); the loads and barriers stay the same for every wave.
 #define MOE_MAINLOOP(NI_)                                                                       \
   do {                                                                                          \
-    MOE_FRAGS(0, cur, 0, NI_);                                                                  \
+    _Pragma("unroll") for (int u = 0; u < WTM + WTN; ++u) MOE_UNIT(u, 0, b0, 0, NI_);           \
     int kt = 0;                                                                                 \
-    _Pragma("unroll 1") for (; kt + 4 < KTT; kt += 2) {                                         \
-      MOE_ITER(kt, 0, 1, true, true, true, NI_);                                                \
-      MOE_ITER(kt + 1, 1, 0, true, true, true, NI_);                                            \
-    }                                                                                           \
-    _Pragma("unroll 1") for (; kt < KTT; kt += 2) {                                             \
-      MOE_ITER(kt, 0, 1, kt + 3 < KTT, kt + 2 < KTT, kt + 1 < KTT, NI_);                        \
-      if (kt + 1 < KTT) MOE_ITER(kt + 1, 1, 0, kt + 4 < KTT, kt + 3 < KTT, kt + 2 < KTT, NI_);  \
-    }                                                                                           \
+    _Pragma("unroll 1") for (; kt + 3 < KTT; ++kt) MOE_ITER(kt, true, true, NI_);               \
+    _Pragma("unroll 1") for (; kt < KTT; ++kt) MOE_ITER(kt, false, kt + 1 < KTT, NI_);          \
   } while (0)
       if (ni == WTM) MOE_MAINLOOP(WTM);
       else MOE_MAINLOOP(ni);
 #undef MOE_MAINLOOP
     }
 #undef MOE_LOAD
-#undef MOE_STORE
-#undef MOE_FRAGS
+#undef MOE_UNIT
+#undef MOE_WAIT
 #undef MOE_ITER
   }
 

@@ -35,6 +35,9 @@ static RouteGeom route_geom(int E) {
   g.e4 = 4 << g.egp_log2;
   g.dc = 64;
   while (g.dc * g.e4 > 2048) g.dc >>= 1;
+  // few experts: longer chunks (fewer block barriers per token) while the Wr chunk stays within 8 KB
+  // and the x chunk within four 16-byte vectors per thread even for fp32 (TOK * DC * 4 / 16 <= 1024)
+  while (g.dc < 128 && g.dc * 2 * g.e4 <= 2048 && g.tok * g.dc * 2 <= 4096) g.dc <<= 1;
   return g;
 }
 
@@ -60,17 +63,21 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
   } else {
     const int xv_per_row = DC / VN, n_xv = TOK * xv_per_row;   // 16-byte vectors of one x chunk
     const int n_wv = DC * E4 / 4;                              // float4 of one Wr chunk
-    Vec16<T> xr[2];
+    Vec16<T> xr[4];
     float4 wr[2];
     auto fetch = [&](int c0) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int u = 0; u < 4; ++u) {
         const int q = tid + u * RT_THREADS;
         if (q < n_xv) {
           const int r = q / xv_per_row, c = c0 + (q % xv_per_row) * VN;
           if (r < ntok && c < d) xr[u].load(x + (size_t)(tok0 + r) * d + c);
           else { float z[VN] = {}; xr[u].pack(z); }
         }
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int q = tid + u * RT_THREADS;
         if (q < n_wv) {
           const int i = c0 + (q * 4) / E4, e = (q * 4) % E4;
           float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -90,9 +97,13 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     };
     auto stash = [&]() {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int u = 0; u < 4; ++u) {
         const int q = tid + u * RT_THREADS;
         if (q < n_xv) xr[u].store(xs + (size_t)(q / xv_per_row) * xpitch + (q % xv_per_row) * VN);
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int q = tid + u * RT_THREADS;
         if (q < n_wv) *reinterpret_cast<float4*>(wsm + (size_t)q * 4) = wr[u];
       }
     };
