@@ -59,47 +59,42 @@ __device__ __forceinline__ int ks_off(int krow, int col_byte) {
 // Fragment reads.  Eight K values of one K step for column l%32 of a K-strided tile come from two
 // transposing reads: the instruction works on blocks of 16 lanes, lane s of a block reads 8 bytes at
 // (K row s/4, columns 4*(s%4)..+3) and receives the four K rows of column s; the second read lies
-// four K rows further on.  All fragment reads are raw instructions (see the pipeline note above);
-// the caller waits for the data itself (lds_wait).
-typedef __attribute__((address_space(3))) char lds_char;
-__device__ __forceinline__ unsigned lds_addr(const char* p) { return (unsigned)(uintptr_t)(const lds_char*)p; }
-// `off` must fold to a constant (it is the instruction's immediate offset).
-__device__ __forceinline__ s16x4 ds_read_tr_raw(unsigned addr, int off) {
-  s16x4 v;
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(off));
-  return v;
-}
+// four K rows further on.  `p` is the lane's address of the first read.
 template <int W>
-__device__ __forceinline__ bf16x8 lds_read_ks2_raw(unsigned addr, int off) {
+__device__ __forceinline__ bf16x8 lds_read_ks2(const char* p) {
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * W * 2));
   union { struct { s16x4 a, b; } q; bf16x8 v; } u;
-  u.q.a = ds_read_tr_raw(addr, off);
-  u.q.b = ds_read_tr_raw(addr, off + 4 * W * 2);
+  u.q.a = lo;
+  u.q.b = hi;
   return u.v;
 }
-__device__ __forceinline__ bf16x8 lds_read_b128_raw(unsigned addr, int off) {
-  bf16x8 v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(off));
-  return v;
-}
-// Wait until every LDS read issued so far has returned; tied to `v` so that its uses stay behind the wait.
-__device__ __forceinline__ void lds_wait(bf16x8& v) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v)); }
 
 // ---- global -> LDS loads of one stage ------------------------------------------------------------
 // Global loads are raw buffer loads: the descriptor's byte count is set to the part of the operand
 // this tile may read, and the hardware returns zero for anything past it.  That gives the ragged
 // edges (rows past an expert's share, K rows past the share in the weight-gradient GEMM, columns past
 // the matrix) for free, with no predicates, no branches and one 32-bit offset register per load.
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef __attribute__((address_space(3))) char lds_char;
+__device__ __forceinline__ unsigned lds_addr(const char* p) { return (unsigned)(uintptr_t)(const lds_char*)p; }
+typedef u32x4 rsrc_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base, size_t bytes) {
+  const unsigned long long a = (unsigned long long)base;
   const unsigned n = bytes > 0xffffffffull ? 0xffffffffu : (unsigned)bytes;
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+  // raw buffer: base address, stride 0, byte count, 32-bit untyped data format
+  return rsrc_t{(unsigned)a, (unsigned)(a >> 32) & 0xffffu, n, 0x00020000u};
 }
 
-// 16 bytes per lane from a buffer straight into LDS: lane l of the wave lands at lds + 16*l
-// (lds must be wave-uniform).  Completion is tracked by vmcnt like any other buffer load.
-__device__ __forceinline__ void load_to_lds16(rsrc_t rs, char* lds, unsigned voffset) {
-  typedef __attribute__((address_space(3))) void lds_void;
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)lds, 16, voffset, 0, 0, 0);
+// 16 bytes per lane from a buffer straight into LDS: lane l of the wave lands at LDS byte address
+// lds + 16*l (lds is wave-uniform; the instruction takes it from M0).  Completion is tracked by
+// vmcnt like any other buffer load.  Written as a raw instruction on purpose: the compiler must not
+// know that this load writes LDS, or it waits for every outstanding load before each LDS read it
+// cannot prove disjoint (the transposing reads).  The pipeline orders loads and reads itself with
+// explicit vmcnt waits and block barriers; the memory clobber keeps LDS reads from moving across.
+__device__ __forceinline__ void load_to_lds16(rsrc_t rs, unsigned lds, unsigned voffset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds), "v"(voffset), "s"(rs) : "memory", "m0");
 }
 
 // One operand tile of one stage, cut into 16-byte chunks; thread tid moves chunks tid + NT*i.
@@ -363,18 +358,19 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
     for (int i = 0; i < StB::CH; ++i) b_vo[i] = StB::goff(i, tid, pb);
     const int wbase = wave * 1024;   // a wave's 64 lanes fill 1 KB of the tile per load
     const unsigned smem_base = lds_addr(smem);
-    // The next K step's fragment reads are spread over the first MFMAs of the current one, UPM read
-    // units per MFMA (scheduling fences keep that order), so the LDS pipe sees a steady trickle
-    // instead of bursts and every read has at least half a K step of MFMAs to land.
-    constexpr int UPM = 2;
-    static_assert(UPM * WTM * WTN >= WTM + WTN, "not every fragment would be read");
-    bf16x8 af[2][WTM], bfr[2][WTN], bfr2[2][DUAL ? WTN : 1];
+    // Fragments are read two K steps (one stage) ahead of the MFMAs that use them, into three register
+    // slots, so a read has a whole K step of MFMAs to land before anything waits for it.
+    static_assert(KS == 2, "the fragment slots rotate with two K steps per stage");
+    constexpr int RPS = WTM * (A_KC ? 1 : 2) + WTN * (B_KC ? 1 : 2) * (DUAL ? 2 : 1);   // LDS reads per K step
+    constexpr int NM = WTM * WTN * (DUAL ? 2 : 1);                                      // MFMAs per K step
+    constexpr int RPM = (RPS + NM / 2 - 1) / (NM / 2);
+    bf16x8 af[3][WTM], bfr[3][WTN], bfr2[3][DUAL ? WTN : 1];
 #define MOE_LOAD(kt_, buf_)                                                                                 \
   do {                                                                                                      \
     const int kq__ = (kt_);                                                                                 \
     const bool sec__ = CHAIN && kq__ >= KT1;                                                                \
     const unsigned kl__ = (unsigned)(sec__ ? kq__ - KT1 : kq__);                                            \
-    char* st__ = smem + (buf_) + wbase;                                                                     \
+    const unsigned st__ = smem_base + (buf_) + wbase;                                                       \
     _Pragma("unroll") for (int i = 0; i < StA::CH; ++i)                                                     \
       load_to_lds16(sec__ ? ra1 : ra, st__ + NT * 16 * i, a_vo[i] + kl__ * astep);                          \
     _Pragma("unroll") for (int i = 0; i < StB::CH; ++i) {                                                   \
@@ -382,49 +378,49 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
       if constexpr (DUAL) load_to_lds16(rb1, st__ + A_BYTES + B_BYTES + NT * 16 * i, b_vo[i] + kl__ * bstep); \
     }                                                                                                       \
   } while (0)
-// read unit u of K step ks_ of the stage at buf_ into fragment slot slot_: units 0..WTN-1 are the B
-// fragments, WTN..WTN+WTM-1 the A fragments (only the NI_ row bands that hold valid rows)
-#define MOE_UNIT(u_, slot_, buf_, ks_, NI_)                                                                 \
+// fragments of K step ks_ of the stage at buf_ into slot slot_
+#define MOE_FRAGS(slot_, buf_, ks_)                                                                         \
   do {                                                                                                      \
-    const unsigned sa__ = smem_base + (buf_);                                                               \
-    if ((u_) < WTN) {                                                                                       \
-      const int j = (u_);                                                                                   \
-      if constexpr (B_KC) bfr[slot_][j] = lds_read_b128_raw(sa__ + b_fr[ks_], j * 32 * BKT * 2);            \
-      else bfr[slot_][j] = lds_read_ks2_raw<BN>(sa__ + b_fr[j], (ks_) * 16 * BN * 2);                       \
-      if constexpr (DUAL) bfr2[slot_][j] = lds_read_ks2_raw<BN>(sa__ + b_fr[j], B_BYTES + (ks_) * 16 * BN * 2); \
-    } else if ((u_) - WTN < WTM && (u_) - WTN < (NI_)) {                                                    \
-      const int i = (u_) - WTN;                                                                             \
-      if constexpr (A_KC) af[slot_][i] = lds_read_b128_raw(sa__ + a_fr[ks_], i * 32 * BKT * 2);             \
-      else af[slot_][i] = lds_read_ks2_raw<BM>(sa__ + a_fr[i], (ks_) * 16 * BM * 2);                        \
+    const char* st__ = smem + (buf_);                                                                       \
+    _Pragma("unroll") for (int i = 0; i < WTM; ++i) {                                                       \
+      if constexpr (A_KC) af[slot_][i] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + i * 32 * BKT * 2); \
+      else af[slot_][i] = lds_read_ks2<BM>(st__ + a_fr[i] + (ks_) * 16 * BM * 2);                           \
+    }                                                                                                       \
+    _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                       \
+      if constexpr (B_KC) bfr[slot_][j] = *reinterpret_cast<const bf16x8*>(st__ + b_fr[ks_] + j * 32 * BKT * 2); \
+      else bfr[slot_][j] = lds_read_ks2<BN>(st__ + b_fr[j] + (ks_) * 16 * BN * 2);                          \
+      if constexpr (DUAL) bfr2[slot_][j] = lds_read_ks2<BN>(st__ + B_BYTES + b_fr[j] + (ks_) * 16 * BN * 2); \
     }                                                                                                       \
   } while (0)
-// the raw reads of a slot must have returned before its MFMAs
-#define MOE_WAIT(slot_, NI_)                                                                                \
+// One K step: the reads for the same K step of the next stage, then the MFMAs of this one.  The
+// scheduling groups ask for that order, with the reads spread over the first half of the MFMAs (RPM
+// per MFMA), so the LDS pipe sees a steady trickle and no read is sunk down to its first use.
+#define MOE_STEP(ks_, cur_, tgt_, DO_NEXT_, NI_)                                                            \
   do {                                                                                                      \
-    _Pragma("unroll") for (int i = 0; i < WTM; ++i) if (i < (NI_)) lds_wait(af[slot_][i]);                  \
-    _Pragma("unroll") for (int j = 0; j < WTN; ++j) { lds_wait(bfr[slot_][j]); if constexpr (DUAL) lds_wait(bfr2[slot_][j]); } \
+    if (DO_NEXT_) MOE_FRAGS(tgt_, b1, ks_);                                                                 \
+    _Pragma("unroll") for (int i = 0; i < WTM; ++i) if (i < (NI_))                                          \
+      _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                     \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i], bfr[cur_][j], acc[i][j], 0, 0, 0); \
+        if constexpr (DUAL)                                                                                 \
+          acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i], bfr2[cur_][j], acc2[i][j], 0, 0, 0); \
+      }                                                                                                     \
+    if (DO_NEXT_) {                                                                                         \
+      _Pragma("unroll") for (int q = 0; q < NM / 2; ++q) {                                                  \
+        __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);                                                \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                  \
+      }                                                                                                     \
+      __builtin_amdgcn_sched_group_barrier(0x008, NM - NM / 2, 0);                                          \
+    }                                                                                                       \
   } while (0)
-// One iteration.  DO_LOAD_ and DO_NEXT_ are literal `true` in the steady-state loop, so that it has
-// no branches; the last iterations use the run-time conditions.
-#define MOE_ITER(kt_, DO_LOAD_, DO_NEXT_, NI_)                                                              \
+// One iteration; S0_ is the fragment slot of its first K step (the second uses the next slot, the
+// reads for the next stage go to the slot after that and then to S0_ again).  DO_LOAD_ and DO_NEXT_
+// are literal `true` in the steady-state loop, so that it has no branches; the last iterations use
+// the run-time conditions.
+#define MOE_ITER(kt_, S0_, DO_LOAD_, DO_NEXT_, NI_)                                                         \
   do {                                                                                                      \
     if (DO_LOAD_) MOE_LOAD((kt_) + 3, b3);                                                                  \
-    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                     \
-      MOE_WAIT(ks & 1, NI_);                                                                                \
-      _Pragma("unroll") for (int m = 0; m < WTM * WTN; ++m) {                                               \
-        const int i = m / WTN, j = m % WTN;                                                                 \
-        _Pragma("unroll") for (int u = m * UPM; u < (m + 1) * UPM; ++u) {                                   \
-          if (ks + 1 < KS) MOE_UNIT(u, (ks + 1) & 1, b0, ks + 1, NI_);                                      \
-          else if (DO_NEXT_) MOE_UNIT(u, (ks + 1) & 1, b1, 0, NI_);                                         \
-        }                                                                                                   \
-        if (i < (NI_)) {                                                                                    \
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0); \
-          if constexpr (DUAL)                                                                               \
-            acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr2[ks & 1][j], acc2[i][j], 0, 0, 0); \
-        }                                                                                                   \
-        __builtin_amdgcn_sched_barrier(0);                                                                  \
-      }                                                                                                     \
-    }                                                                                                       \
+    MOE_STEP(0, (S0_) % 3, ((S0_) + 2) % 3, DO_NEXT_, NI_);                                                 \
+    MOE_STEP(1, ((S0_) + 1) % 3, (S0_) % 3, DO_NEXT_, NI_);                                                 \
     if (DO_LOAD_) __builtin_amdgcn_s_waitcnt(WAIT_L); else __builtin_amdgcn_s_waitcnt(WAIT_0);              \
     asm volatile("" ::: "memory");                                                                          \
     __builtin_amdgcn_s_barrier();                                                                           \
@@ -441,21 +437,31 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
       // A partly filled row tile multiplies only the 32-row MFMA bands that hold valid rows (ni of
-      // them in this wave); the loads and barriers stay the same for every wave.
+      // them in this wave); the loads, fragment reads and barriers stay the same for every wave.  The loop is unrolled
+      // three times so that the fragment slots are compile-time constants.
 #define MOE_MAINLOOP(NI_)                                                                       \
   do {                                                                                          \
-    _Pragma("unroll") for (int u = 0; u < WTM + WTN; ++u) MOE_UNIT(u, 0, b0, 0, NI_);           \
+    MOE_FRAGS(0, b0, 0);                                                                        \
+    MOE_FRAGS(1, b0, 1);                                                                        \
     int kt = 0;                                                                                 \
-    _Pragma("unroll 1") for (; kt + 3 < KTT; ++kt) MOE_ITER(kt, true, true, NI_);               \
-    _Pragma("unroll 1") for (; kt < KTT; ++kt) MOE_ITER(kt, false, kt + 1 < KTT, NI_);          \
+    _Pragma("unroll 1") for (; kt + 5 < KTT; kt += 3) {                                         \
+      MOE_ITER(kt, 0, true, true, NI_);                                                         \
+      MOE_ITER(kt + 1, 2, true, true, NI_);                                                     \
+      MOE_ITER(kt + 2, 1, true, true, NI_);                                                     \
+    }                                                                                           \
+    _Pragma("unroll 1") for (; kt < KTT; kt += 3) {                                             \
+      MOE_ITER(kt, 0, kt + 3 < KTT, kt + 1 < KTT, NI_);                                         \
+      if (kt + 1 < KTT) MOE_ITER(kt + 1, 2, kt + 4 < KTT, kt + 2 < KTT, NI_);                   \
+      if (kt + 2 < KTT) MOE_ITER(kt + 2, 1, kt + 5 < KTT, kt + 3 < KTT, NI_);                   \
+    }                                                                                           \
   } while (0)
       if (ni == WTM) MOE_MAINLOOP(WTM);
       else MOE_MAINLOOP(ni);
 #undef MOE_MAINLOOP
     }
 #undef MOE_LOAD
-#undef MOE_UNIT
-#undef MOE_WAIT
+#undef MOE_FRAGS
+#undef MOE_STEP
 #undef MOE_ITER
   }
 
