@@ -158,6 +158,24 @@ __device__ __forceinline__ float phi_fast(float a, float& expo) {
   const float q = 0.5f * p * t * expo;
   return a >= 0.f ? 1.0f - q : q;
 }
+// gelu(a) = a Phi(a) through the lower tail t = Phi(-|a|) = 2^(x P(x) - 1), x = min(|a|, 6), where P is a
+// degree-6 polynomial fitted (Chebyshev nodes) to log2(erfc(x / sqrt 2)) / x on [0, 6].  Fitting the
+// logarithm of the tail keeps the relative error of t, and so of gelu(a) for negative a, below 2.5e-5;
+// the absolute error of gelu is below 2e-6 for every a (fp32 Horner evaluation included), far below
+// bf16 resolution.  Then gelu(a) = a (1 - t) for a >= 0 and a t for a < 0, i.e. max(a, 0) - |a t|.
+// One exponential and no reciprocal: about two thirds of the instructions of the erf form above.
+__device__ __forceinline__ float gelu_fast(float a) {
+  const float x = __builtin_fminf(__builtin_fabsf(a), 6.0f);
+  float p = -1.339070508e-06f;
+  p = fmaf(p, x, 5.169712902e-05f);
+  p = fmaf(p, x, -8.538773221e-04f);
+  p = fmaf(p, x, 8.219408847e-03f);
+  p = fmaf(p, x, -5.341951027e-02f);
+  p = fmaf(p, x, -4.589222869e-01f);
+  p = fmaf(p, x, -1.151119706e+00f);
+  const float t = __builtin_amdgcn_exp2f(fmaf(x, p, -1.0f));
+  return __builtin_fmaxf(a, 0.f) - __builtin_fabsf(a * t);
+}
 __device__ __forceinline__ float sigmoid_fast(float g) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.44269504088896340736f));
 }
@@ -177,9 +195,9 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
     st(g.C, idx, a[0], a[1], a[2], a[3]);
   } else if constexpr (EPI == EPI_GELU_FWD) {
     st(g.C, idx, a[0], a[1], a[2], a[3]);
-    float h[4], ex;
+    float h[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) h[i] = a[i] * phi_fast(a[i], ex);
+    for (int i = 0; i < 4; ++i) h[i] = gelu_fast(a[i]);
     st(g.C2, idx, h[0], h[1], h[2], h[3]);
   } else if constexpr (EPI == EPI_SWIGLU_FWD) {
     st(g.C, idx, a[0], a[1], a[2], a[3]);
