@@ -18,9 +18,9 @@
 // and read with the transposing 8-byte LDS read of gfx950, so nothing is ever transposed in global
 // memory and the same kernel serves x W (NN), dy W^T (NT) and x^T dy (TN).
 //
-// Epilogue (NN/NT): accumulators go through a per-wave LDS slab to turn the MFMA register layout
-// into rows, so that every output (and every saved tensor the backward epilogues read) moves as
-// 8-byte pieces that fill whole 128-byte lines.
+// Epilogue: accumulators go through a per-wave LDS slab to turn the MFMA register layout into rows,
+// so that every output (and every saved tensor the backward epilogues read) moves as 8-byte (bf16) or
+// 16-byte (fp32 weight gradients) pieces per lane that fill whole 128-byte lines.
 //
 // MFMA 32x32x16 register layout (checked on the hardware): lane l supplies row/column l%32 and the
 // eight K values (l/32)*8..+7 of the step; accumulator register v of lane l is row
@@ -483,20 +483,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
 #undef MOE_ITER
   }
 
-  if constexpr (MODE == MODE_TN) {
-    // fp32 weight gradients: 32 lanes x 4 bytes are a full line per row already
-#pragma unroll
-    for (int i = 0; i < WTM; ++i)
-#pragma unroll
-      for (int j = 0; j < WTN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = (wm * WTM + i) * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-          const int n = (wn * WTN + j) * 32 + (lane & 31);
-          if (m < mvalid && n < nvalid)
-            epilogue<bf16, EPI>(g, ((size_t)e * g.M + m0 + m) * g.N + n0 + n, acc[i][j][v], 0.f);
-        }
-  } else {
+  {
     // per-wave slab [32][WTN*32 + 8] fp32 (the ring is free: the loop ended with a block barrier)
     constexpr int C = WTN * 32, P = C + 8, LPR = C / 4, RPP = 64 / LPR, PASSES = 32 / RPP;
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * P);
@@ -541,9 +528,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
       for (int p = 0; p < PASSES; ++p) {
         const int m = (wm * WTM + i) * 32 + p * RPP + rr;
         const int n = wn * C + c4 * 4;
-        if (m < mvalid && n < nvalid)
-          epilogue4<EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0], s1[NEED_S1 ? p : 0],
-                         s2[NEED_S2 ? p : 0]);
+        if (m < mvalid && n < nvalid) {
+          if constexpr (MODE == MODE_TN) {   // fp32 weight gradient of expert e, 16 bytes per lane
+            f32x4* c = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + ((size_t)e * g.M + m0 + m) * g.N + n0 + n);
+            *c = g.accumulate ? *c + va[p] : va[p];
+          } else {
+            epilogue4<EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0], s1[NEED_S1 ? p : 0],
+                           s2[NEED_S2 ? p : 0]);
+          }
+        }
       }
     }
   }
