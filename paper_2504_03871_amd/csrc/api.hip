@@ -38,7 +38,11 @@ WsLayout ws_layout(const moe_cfg* c) {
   w.tile_map = off;
   off += align_up(tile_map_bytes(max_row_tiles((int)A, c->E, TILE_ROWS_MIN), c->E), 256);
   w.route_partials = off;
-  off += align_up(((size_t)(c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS) * c->d_model * c->E * 4, 256);
+  {
+    size_t rows = ((size_t)c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS;
+    if (c->E <= ROUTE_BWD_DENSE_E) rows = route_bwd_geom(c->T, c->d_model, (int)elt_size(c)).partial_rows;
+    off += align_up(rows * c->d_model * c->E * 4, 256);
+  }
   w.route_wrt = off;
   off += align_up((size_t)c->d_model * c->E * 4, 256);
   w.ffn_bwd_dact = off;

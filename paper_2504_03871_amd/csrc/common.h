@@ -32,7 +32,30 @@ struct WsLayout {
 WsLayout ws_layout(const moe_cfg* c);
 
 constexpr int DISPATCH_CHUNK = 1024;   // assignments ranked by one block
-constexpr int ROUTE_BWD_TOKENS = 128;  // tokens per block of the gate-backward kernel
+constexpr int ROUTE_BWD_TOKENS = 128;  // tokens per block of the gate-backward kernel (many experts)
+constexpr int ROUTE_BWD_DENSE_E = 16;  // up to this many experts the gate weight gradient keeps a dense [E] row in registers
+
+// Geometry of the dense gate-weight-gradient kernel: a thread owns one 16-byte column group, cg_pow2
+// threads span a token row (a power of two, at most 256; wider rows take several column blocks), a block
+// of 256 threads works on 256 / cg_pow2 token slices at once, each `tps` tokens long, and every slice
+// writes its own row of partial sums.  tps grows with the problem so that the grid stays near two
+// blocks per compute unit and the partial sums stay small.
+struct RouteBwdGeom { int cg_pow2, slices_per_block, tps, col_blocks, row_blocks, partial_rows; };
+inline RouteBwdGeom route_bwd_geom(int T, int d, int elt_bytes) {
+  RouteBwdGeom gm;
+  const int cg = d / (16 / elt_bytes);
+  gm.cg_pow2 = 4;   // at most 64 slices per block
+  while (gm.cg_pow2 < cg && gm.cg_pow2 < 256) gm.cg_pow2 <<= 1;
+  gm.slices_per_block = 256 / gm.cg_pow2;
+  gm.col_blocks = (cg + gm.cg_pow2 - 1) / gm.cg_pow2;
+  long long tps = ((long long)T * gm.col_blocks) / (512ll * gm.slices_per_block);
+  const int cap = 1024 / gm.slices_per_block;   // the block stages slices * tps * E <= 1024 * 16 floats in LDS
+  gm.tps = (int)(tps < 16 ? 16 : (tps > 256 ? 256 : tps));
+  if (gm.tps > cap) gm.tps = cap;
+  gm.row_blocks = (T + gm.tps * gm.slices_per_block - 1) / (gm.tps * gm.slices_per_block);
+  gm.partial_rows = gm.row_blocks * gm.slices_per_block;
+  return gm;
+}
 constexpr int TILE_ROWS_MIN = 64;      // smallest row-tile height any grouped GEMM uses (sizes the tile map)
 
 // ---------------------------------------------------------------- device side

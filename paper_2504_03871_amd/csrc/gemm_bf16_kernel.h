@@ -233,14 +233,14 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
 
 template <int BM, int BN, int BKT, bool DUAL>
 constexpr int gemm_bf16_stage_bytes() { return BM * BKT * 2 + BN * BKT * 2 * (DUAL ? 2 : 1); }
-template <int BM, int BN, int BKT, bool DUAL, int WGM, int WGN>
+template <int BM, int BN, int BKT, bool DUAL, int WGM, int WGN, int NB = NBUF>
 constexpr int gemm_bf16_lds_bytes() {
-  constexpr int ring = NBUF * gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
+  constexpr int ring = NB * gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
   constexpr int slab = WGM * WGN * 32 * (BN / WGN + 8) * 4;   // epilogue: one 32-row fp32 slab per wave
   return ring > slab ? ring : slab;
 }
 
-template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN>
+template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM / 32, WTN = BN / WGN / 32;
@@ -250,7 +250,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
   constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2;
   constexpr int STAGE = gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
   static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of K steps per stage");
-  static_assert(NBUF == 4, "the ring rotation below is written for four stages");
+  static_assert(NB >= 4, "loads run at least three stages ahead");
+  constexpr int D = NB - 1;   // loads run D stages ahead of the MFMAs
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -363,12 +364,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
     const rsrc_t rb = make_rsrc(B0 + boff, bbytes), rb1 = make_rsrc(B1 + boff, bbytes);
     const int KT1 = KT;                      // stages of one operand pair
     const int KTT = CHAIN ? 2 * KT1 : KT1;   // stages in all
-    // Iteration kt issues the loads of stage kt+3, multiplies stage kt, then waits until its own loads
-    // of stage kt+2 have landed (all but the newest stage) and joins the block barrier, after which
-    // stage kt+2 is visible to every wave and stage kt's buffer may be overwritten.
-    constexpr int L = StA::CH + StB::CH * (DUAL ? 2 : 1);                    // loads per thread per stage
-    constexpr int WAIT_L = (L & 15) | ((L >> 4) << 14) | 0x70 | (15 << 8);   // s_waitcnt vmcnt(L) only
-    constexpr int WAIT_0 = 0x70 | (15 << 8);                                 // s_waitcnt vmcnt(0) only
+    // Iteration kt issues the loads of stage kt+D, multiplies stage kt (reading the fragments of stage
+    // kt+1 meanwhile), then waits until its own loads of stage kt+2 have landed (all but the newest D-2
+    // stages) and joins the block barrier, after which stage kt+2 is visible to every wave and stage
+    // kt's buffer may be overwritten.
+    constexpr int L = StA::CH + StB::CH * (DUAL ? 2 : 1);   // loads per thread per stage
+    constexpr int PEND = L * (D - 2);                        // loads that may stay in flight at the barrier
+    static_assert(PEND < 64, "the wait counter has six bits");
+    constexpr int WAIT_L = (PEND & 15) | ((PEND >> 4) << 14) | 0x70 | (15 << 8);   // s_waitcnt vmcnt(PEND) only
+    constexpr int WAIT_0 = 0x70 | (15 << 8);                                       // s_waitcnt vmcnt(0) only
     unsigned a_vo[StA::CH], b_vo[StB::CH];
 #pragma unroll
     for (int i = 0; i < StA::CH; ++i) a_vo[i] = StA::goff(i, tid, pa);
@@ -436,20 +440,22 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
 // the run-time conditions.
 #define MOE_ITER(kt_, S0_, DO_LOAD_, DO_NEXT_, NI_)                                                         \
   do {                                                                                                      \
-    if (DO_LOAD_) MOE_LOAD((kt_) + 3, b3);                                                                  \
+    if (DO_LOAD_) MOE_LOAD((kt_) + D, bload);                                                               \
     MOE_STEP(0, (S0_) % 3, ((S0_) + 2) % 3, DO_NEXT_, NI_);                                                 \
     MOE_STEP(1, ((S0_) + 1) % 3, (S0_) % 3, DO_NEXT_, NI_);                                                 \
     if (DO_LOAD_) __builtin_amdgcn_s_waitcnt(WAIT_L); else __builtin_amdgcn_s_waitcnt(WAIT_0);              \
     asm volatile("" ::: "memory");                                                                          \
     __builtin_amdgcn_s_barrier();                                                                           \
     asm volatile("" ::: "memory");                                                                          \
-    { const int t__ = b0; b0 = b1; b1 = b2; b2 = b3; b3 = t__; }                                            \
+    bload = b0; b0 = b1; b1 = (b1 + STAGE == NB * STAGE) ? 0 : b1 + STAGE;                                  \
   } while (0)
     if (KTT > 0) {
-      int b0 = 0, b1 = STAGE, b2 = 2 * STAGE, b3 = 3 * STAGE;   // ring offsets of stages kt .. kt+3
-      MOE_LOAD(0, b0);
-      if (KTT > 1) MOE_LOAD(1, b1);
-      if (KTT > 2) { MOE_LOAD(2, b2); __builtin_amdgcn_s_waitcnt(WAIT_L); }
+      // ring offsets: stage kt, stage kt+1, and the buffer the loads of stage kt+D go to (the one before b0)
+      int b0 = 0, b1 = STAGE, bload = D * STAGE;
+#pragma unroll
+      for (int j = 0; j < D; ++j)
+        if (j < KTT) MOE_LOAD(j, j * STAGE);
+      if (KTT >= D) __builtin_amdgcn_s_waitcnt(WAIT_L);   // stages 0 and 1 have landed
       else __builtin_amdgcn_s_waitcnt(WAIT_0);
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
@@ -462,15 +468,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
     MOE_FRAGS(0, b0, 0);                                                                        \
     MOE_FRAGS(1, b0, 1);                                                                        \
     int kt = 0;                                                                                 \
-    _Pragma("unroll 1") for (; kt + 5 < KTT; kt += 3) {                                         \
+    _Pragma("unroll 1") for (; kt + D + 2 < KTT; kt += 3) {                                     \
       MOE_ITER(kt, 0, true, true, NI_);                                                         \
       MOE_ITER(kt + 1, 2, true, true, NI_);                                                     \
       MOE_ITER(kt + 2, 1, true, true, NI_);                                                     \
     }                                                                                           \
     _Pragma("unroll 1") for (; kt < KTT; kt += 3) {                                             \
-      MOE_ITER(kt, 0, kt + 3 < KTT, kt + 1 < KTT, NI_);                                         \
-      if (kt + 1 < KTT) MOE_ITER(kt + 1, 2, kt + 4 < KTT, kt + 2 < KTT, NI_);                   \
-      if (kt + 2 < KTT) MOE_ITER(kt + 2, 1, kt + 5 < KTT, kt + 3 < KTT, NI_);                   \
+      MOE_ITER(kt, 0, kt + D < KTT, kt + 1 < KTT, NI_);                                         \
+      if (kt + 1 < KTT) MOE_ITER(kt + 1, 2, kt + 1 + D < KTT, kt + 2 < KTT, NI_);               \
+      if (kt + 2 < KTT) MOE_ITER(kt + 2, 1, kt + 2 + D < KTT, kt + 3 < KTT, NI_);               \
     }                                                                                           \
   } while (0)
       if (ni == WTM) MOE_MAINLOOP(WTM);

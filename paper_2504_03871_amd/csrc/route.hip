@@ -317,13 +317,90 @@ __global__ __launch_bounds__(RB_MAX_WAVES* WAVE) void route_bwd_dwr_kernel(
   }
 }
 
-__global__ void route_bwd_reduce_kernel(const float* __restrict__ partials, float* __restrict__ dWr, int n, int chunks) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
+// Few experts (E <= EB <= ROUTE_BWD_DENSE_E): every thread keeps the whole [EB] x (16-byte column group)
+// block of the weight gradient in registers and adds d_logits[t][:] (x) x[t][cols] token after token,
+// zeros of the unselected experts included; no LDS read-modify-write, no branches, one 16-byte load of
+// x per token.  The slice's d_logits rows are staged in LDS once, padded with zeros to EB per row, and
+// read back as 16-byte broadcasts.  Geometry: RouteBwdGeom.
+template <typename T, int EB>
+__global__ __launch_bounds__(256) void route_bwd_dwr_dense_kernel(
+    const T* __restrict__ x, const float* __restrict__ d_logits, float* __restrict__ partials, int Tn, int d, int E,
+    RouteBwdGeom gm) {
+  extern __shared__ float4 s_dl4[];   // [slices_per_block][tps][EB] floats
+  float* s_dl = reinterpret_cast<float*>(s_dl4);
+  constexpr int VN = Vec16<T>::N, U = 4;
+  const int c = threadIdx.x & (gm.cg_pow2 - 1), slice = threadIdx.x / gm.cg_pow2;
+  const int col = (blockIdx.x * gm.cg_pow2 + c) * VN;
+  const int row = blockIdx.y * gm.slices_per_block + slice;   // row of partial sums = token slice
+  const int t0 = row * gm.tps;
+  const int nt = max(0, min(gm.tps, Tn - t0));
+  {   // the block's slices are adjacent tokens: one pass over them, zero past the last token and past E
+    const int tb = blockIdx.y * gm.slices_per_block * gm.tps, n = gm.slices_per_block * gm.tps * EB;
+    for (int i = threadIdx.x; i < n; i += 256) {
+      const int t = tb + i / EB, e = i % EB;
+      s_dl[i] = (t < Tn && e < E) ? d_logits[(size_t)t * E + e] : 0.f;
+    }
+  }
+  __syncthreads();
+  if (col >= d) return;
+  const float4* dl = s_dl4 + (size_t)slice * gm.tps * (EB / 4);
+  float acc[EB][VN];
+#pragma unroll
+  for (int e = 0; e < EB; ++e)
+#pragma unroll
+    for (int v = 0; v < VN; ++v) acc[e][v] = 0.f;
+  for (int tb = 0; tb < nt; tb += U) {
+    Vec16<T> xv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) xv[u].load(x + (size_t)(t0 + min(tb + u, nt - 1)) * d + col);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float xf[VN];
+      xv[u].unpack(xf);
+      const float live = (tb + u < nt) ? 1.f : 0.f;   // the clamped reload of the last token counts once
+#pragma unroll
+      for (int q = 0; q < EB / 4; ++q) {
+        const float4 g4 = dl[min(tb + u, nt - 1) * (EB / 4) + q];
+        const float g[4] = {g4.x * live, g4.y * live, g4.z * live, g4.w * live};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int v = 0; v < VN; ++v) acc[q * 4 + j][v] = fmaf(g[j], xf[v], acc[q * 4 + j][v]);
+      }
+    }
+  }
+  float* out = partials + (size_t)row * E * d + col;   // [row][e][col]: 16-byte stores, adjacent lanes adjacent
+#pragma unroll
+  for (int e = 0; e < EB; ++e)
+    if (e < E) {
+#pragma unroll
+      for (int v = 0; v < VN; v += 4)
+        *reinterpret_cast<float4*>(out + (size_t)e * d + v) = make_float4(acc[e][v], acc[e][v + 1], acc[e][v + 2], acc[e][v + 3]);
+    }
+}
+
+// dWr = sum over the rows of partial sums, in a fixed order (deterministic).  A block owns 64 adjacent
+// elements of a row of partial sums; its four waves take the rows r = w, w+4, ... (each a coalesced
+// 256-byte read), and the four wave sums are added in wave order.  EXPERT_MAJOR: the rows are laid
+// out [E][d] (the dense kernel) instead of [d][E] like dWr itself.
+template <bool EXPERT_MAJOR>
+__global__ __launch_bounds__(256) void route_bwd_reduce_kernel(const float* __restrict__ partials, float* __restrict__ dWr,
+                                                               int d, int E, int rows) {
+  __shared__ float s_part[4][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, n = d * E;
+  const int i = blockIdx.x * 64 + lane;
   float s = 0.f;
+  if (i < n) {
 #pragma unroll 8
-  for (int c = 0; c < chunks; ++c) s += partials[(size_t)c * n + i];   // fixed order: deterministic
-  dWr[i] = s;
+    for (int r = w; r < rows; r += 4) s += partials[(size_t)r * n + i];
+  }
+  s_part[w][lane] = s;
+  __syncthreads();
+  if (w == 0 && i < n) {
+    const float t = ((s_part[0][lane] + s_part[1][lane]) + s_part[2][lane]) + s_part[3][lane];
+    if (EXPERT_MAJOR) dWr[(size_t)(i % d) * E + i / d] = t;
+    else dWr[i] = t;
+  }
 }
 
 // ---------------------------------------------------------------- launchers
@@ -369,13 +446,27 @@ int launch_route_bwd(const moe_cfg* c, const void* x, const float* Wr, const int
   if (bf) route_bwd_dx_kernel<bf16><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (bf16*)dx, c->T, c->d_model, c->E, c->k);
   else route_bwd_dx_kernel<float><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (float*)dx, c->T, c->d_model, c->E, c->k);
   if ((rc = launch_status()) != MOE_OK) return rc;
+  if (c->E <= ROUTE_BWD_DENSE_E) {
+    const RouteBwdGeom gm = route_bwd_geom(c->T, c->d_model, bf ? 2 : 4);
+    const dim3 grid(gm.col_blocks, gm.row_blocks);
+    const int eb = c->E <= 4 ? 4 : (c->E <= 8 ? 8 : 16);
+    const size_t lds = (size_t)gm.slices_per_block * gm.tps * eb * 4;
+#define MOE_DWR_DENSE(TY, EB) \
+  route_bwd_dwr_dense_kernel<TY, EB><<<grid, 256, lds, s>>>((const TY*)x, d_logits, partials, c->T, c->d_model, c->E, gm)
+    if (bf) { if (eb == 4) MOE_DWR_DENSE(bf16, 4); else if (eb == 8) MOE_DWR_DENSE(bf16, 8); else MOE_DWR_DENSE(bf16, 16); }
+    else { if (eb == 4) MOE_DWR_DENSE(float, 4); else if (eb == 8) MOE_DWR_DENSE(float, 8); else MOE_DWR_DENSE(float, 16); }
+#undef MOE_DWR_DENSE
+    if ((rc = launch_status()) != MOE_OK) return rc;
+    route_bwd_reduce_kernel<true><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, gm.partial_rows);
+    return launch_status();
+  }
   // columns per thread: as many as 128 KiB of LDS allow for 4 waves x E experts (d is a multiple of 4)
   const int vec = (c->E <= 32) ? 4 : (c->E <= 64 ? 2 : 1);
   if (vec == 4) rc = bf ? launch_dwr<bf16, 4>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 4>(c, x, idx, d_logits, partials, chunks, s);
   else if (vec == 2) rc = bf ? launch_dwr<bf16, 2>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 2>(c, x, idx, d_logits, partials, chunks, s);
   else rc = bf ? launch_dwr<bf16, 1>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 1>(c, x, idx, d_logits, partials, chunks, s);
   if (rc != MOE_OK) return rc;
-  route_bwd_reduce_kernel<<<(n + 255) / 256, 256, 0, s>>>(partials, dWr, n, chunks);
+  route_bwd_reduce_kernel<false><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, chunks);
   return launch_status();
 }
 

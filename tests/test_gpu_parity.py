@@ -33,6 +33,9 @@ CASES = {
     "k_equals_E": W["cfg1"].scaled(T=130, d=128, f=192, E=3, k=3),
     "one_token": W["cfg1"].scaled(T=1, d=64, f=128, E=4, k=2),
     "many_experts": W["cfg1"].scaled(T=700, d=128, f=128, E=200, k=8),
+    # rows wider than one block of column groups, and not a power of two of them
+    "wide_rows": W["cfg1"].scaled(T=150, d=4160, f=128, E=4, k=2),
+    "d320_e16": W["cfg2"].scaled(T=900, d=320, f=256, E=16, k=2),
 }
 
 
