@@ -1,17 +1,17 @@
 // bf16 grouped GEMM kernel for the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
 //
-// Work decomposition: block tile BM x BN, WGM x WGN waves, each wave owns (BM/WGM) x (BN/WGN) as a
-// grid of 32x32 MFMA tiles; K advances BKT elements per stage.
+// Work decomposition: block tile BM x BN, WGM x WGN waves; a wave owns BN/WGN adjacent columns and the
+// 32-row bands b = wm, wm + WGM, ... of the tile, as a grid of 32x32 MFMA tiles; K advances BKT elements
+// per stage.  Interleaving the bands spreads a partly filled row tile over every wave row.
 //
-// Pipeline: a ring of four LDS stages filled by buffer loads that write LDS directly (no staging
-// registers, no LDS store instructions).  Iteration kt issues the loads of stage kt+3, multiplies
-// stage kt, then waits for its own loads of stage kt+2 and joins the block barrier; so a load has
-// between one and two iterations of MFMA work to land, and stage kt+1 is complete and visible a full
-// iteration before it is needed, which lets each wave fetch the first fragments of the next stage
-// before the barrier: the barrier only guards buffer reuse and is off the MFMA critical path.
-// LDS fragment reads are issued as raw instructions with explicit waits: the compiler cannot tell
-// that a fragment read never touches the stage a direct load is filling and would otherwise wait
-// for every outstanding global load before each read.
+// Pipeline: a ring of NB (four) LDS stages filled by buffer loads that write LDS directly (no staging
+// registers, no LDS store instructions).  Iteration kt issues the loads of stage kt+NB-1, multiplies
+// stage kt while reading the fragments of stage kt+1 into a third register slot, then waits for its
+// own loads of stage kt+2 and joins the block barrier.  A global load has one to two iterations of
+// MFMA work to land, an LDS read a whole K step, and the barrier only guards buffer reuse.
+// The direct loads are raw instructions: if the compiler knew that they write LDS it would wait for
+// every outstanding load before each LDS read it cannot prove disjoint.  The pipeline orders loads and
+// reads itself (explicit vmcnt waits, block barriers); the LDS reads stay compiler-tracked.
 //
 // Operands: one whose K index is contiguous in memory is kept as [rows][BKT] in LDS and read with
 // 16-byte LDS reads; one whose K index is strided is kept exactly as it lies in memory, [BKT][cols],
@@ -308,7 +308,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
 
   const int KT = (klen + BKT - 1) / BKT;
   // MFMA row bands of this wave that contain valid rows
-  const int ni = (MODE == MODE_TN) ? WTM : min(max((mvalid - wm * WTM * 32 + 31) / 32, 0), WTM);
+  // (row band b of the tile belongs to wave row b % WGM, as its band b / WGM: a partly filled tile then
+  // spreads its valid bands over all wave rows instead of loading the first ones only)
+  const int ni = (MODE == MODE_TN) ? WTM : min(max(((mvalid + 31) / 32 - wm + WGM - 1) / WGM, 0), WTM);
   typedef Stage<A_KC, BM, NT, BKT> StA;
   typedef Stage<B_KC, BN, NT, BKT> StB;
 
@@ -317,12 +319,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
   int a_fr[A_KC ? KS : WTM], b_fr[B_KC ? KS : WTN];
   if constexpr (A_KC) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) a_fr[ks] = kc_off<BKT>(wm * WTM * 32 + (lane & 31), ks * 2 + (lane >> 5));
+    for (int ks = 0; ks < KS; ++ks) a_fr[ks] = kc_off<BKT>(wm * 32 + (lane & 31), ks * 2 + (lane >> 5));
   } else {
 #pragma unroll
     for (int i = 0; i < WTM; ++i)
       a_fr[i] = ks_off<BM>(((lane >> 5) & 1) * 8 + ((lane & 15) >> 2),
-                           ((wm * WTM + i) * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2);
+                           ((i * WGM + wm) * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2);
   }
   if constexpr (B_KC) {
 #pragma unroll
@@ -405,7 +407,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
   do {                                                                                                      \
     const char* st__ = smem + (buf_);                                                                       \
     _Pragma("unroll") for (int i = 0; i < WTM; ++i) {                                                       \
-      if constexpr (A_KC) af[slot_][i] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + i * 32 * BKT * 2); \
+      if constexpr (A_KC) af[slot_][i] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + i * WGM * 32 * BKT * 2); \
       else af[slot_][i] = lds_read_ks2<BM>(st__ + a_fr[i] + (ks_) * 16 * BM * 2);                           \
     }                                                                                                       \
     _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                       \
@@ -504,7 +506,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
       if constexpr (NEED_S1) {
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
-          const int m = (wm * WTM + i) * 32 + p * RPP + rr, n = wn * C + c4 * 4;
+          const int m = (i * WGM + wm) * 32 + p * RPP + rr, n = wn * C + c4 * 4;
           const bool ok = m < mvalid && n < nvalid;
           const size_t idx = (size_t)(row0 + (ok ? m : 0)) * g.N + n0 + (ok ? n : 0);
           s1[p] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S1) + idx);
@@ -532,7 +534,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
       }
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) {
-        const int m = (wm * WTM + i) * 32 + p * RPP + rr;
+        const int m = (i * WGM + wm) * 32 + p * RPP + rr;
         const int n = wn * C + c4 * 4;
         if (m < mvalid && n < nvalid) {
           if constexpr (MODE == MODE_TN) {   // fp32 weight gradient of expert e, 16 bytes per lane
