@@ -497,21 +497,26 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * P);
     const int rr = lane / LPR, c4 = lane % LPR;
     constexpr bool NEED_S1 = (EPI == EPI_GELU_BWD || EPI == EPI_SWIGLU_BWD), NEED_S2 = (EPI == EPI_SWIGLU_BWD);
+    // Saved tensors the backward epilogues read: the loads of a band are issued one band ahead (those of
+    // the first band before anything else), so their latency hides behind the previous band's LDS round
+    // trip and arithmetic (rows past the tile read the tile's first row and are dropped).
+    u32x2 s1[NEED_S1 ? 2 : 1][NEED_S1 ? PASSES : 1], s2[NEED_S2 ? 2 : 1][NEED_S2 ? PASSES : 1];
+    auto load_saved = [&](int band, u32x2* d1, u32x2* d2) {
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int m = (band * WGM + wm) * 32 + p * RPP + rr, n = wn * C + c4 * 4;
+        const bool ok = m < mvalid && n < nvalid;
+        const size_t idx = (size_t)(row0 + (ok ? m : 0)) * g.N + n0 + (ok ? n : 0);
+        d1[p] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S1) + idx);
+        if constexpr (NEED_S2) d2[p] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S2) + idx);
+      }
+    };
+    if constexpr (NEED_S1) load_saved(0, s1[0], s2[0]);
 #pragma unroll
     for (int i = 0; i < WTM; ++i) {
       f32x4 va[PASSES], vb[DUAL ? PASSES : 1];
-      // saved tensors the backward epilogues read: issued for the whole band before the LDS round trip,
-      // so their latency hides behind it (rows past the tile read the tile's first row and are dropped)
-      u32x2 s1[NEED_S1 ? PASSES : 1], s2[NEED_S2 ? PASSES : 1];
       if constexpr (NEED_S1) {
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-          const int m = (i * WGM + wm) * 32 + p * RPP + rr, n = wn * C + c4 * 4;
-          const bool ok = m < mvalid && n < nvalid;
-          const size_t idx = (size_t)(row0 + (ok ? m : 0)) * g.N + n0 + (ok ? n : 0);
-          s1[p] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S1) + idx);
-          if constexpr (NEED_S2) s2[p] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S2) + idx);
-        }
+        if (i + 1 < WTM) load_saved(i + 1, s1[(i + 1) & 1], s2[NEED_S2 ? (i + 1) & 1 : 0]);
       }
 #pragma unroll
       for (int half = 0; half < (DUAL ? 2 : 1); ++half) {
@@ -541,8 +546,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
             f32x4* c = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + ((size_t)e * g.M + m0 + m) * g.N + n0 + n);
             *c = g.accumulate ? *c + va[p] : va[p];
           } else {
-            epilogue4<EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0], s1[NEED_S1 ? p : 0],
-                           s2[NEED_S2 ? p : 0]);
+            epilogue4<EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0],
+                           s1[NEED_S1 ? i & 1 : 0][NEED_S1 ? p : 0], s2[NEED_S2 ? i & 1 : 0][NEED_S2 ? p : 0]);
           }
         }
       }
