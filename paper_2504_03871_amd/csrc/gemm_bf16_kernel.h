@@ -145,25 +145,12 @@ __device__ __forceinline__ bool block_to_tile(int n_rt, int n_full_rt, int ntn, 
 }
 
 // ---- fast activation pieces for bf16 outputs ----------------------------------------------------
-// Phi(a) from the rational erf approximation 7.1.26 of Abramowitz & Stegun (|error| < 1.5e-7, far
-// below bf16 resolution); `expo` receives exp(-a^2/2), which gelu' needs as well.
-__device__ __forceinline__ float phi_fast(float a, float& expo) {
-  const float x = fabsf(a) * 0.70710678118654752440f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  expo = __builtin_amdgcn_exp2f(a * a * -0.72134752044448170368f);   // exp(-a^2/2)
-  const float q = 0.5f * p * t * expo;
-  return a >= 0.f ? 1.0f - q : q;
-}
 // gelu(a) = a Phi(a) through the lower tail t = Phi(-|a|) = 2^(x P(x) - 1), x = min(|a|, 6), where P is a
 // degree-6 polynomial fitted (Chebyshev nodes) to log2(erfc(x / sqrt 2)) / x on [0, 6].  Fitting the
 // logarithm of the tail keeps the relative error of t, and so of gelu(a) for negative a, below 2.5e-5;
 // the absolute error of gelu is below 2e-6 for every a (fp32 Horner evaluation included), far below
 // bf16 resolution.  Then gelu(a) = a (1 - t) for a >= 0 and a t for a < 0, i.e. max(a, 0) - |a t|.
-// One exponential and no reciprocal: about two thirds of the instructions of the erf form above.
+// One exponential and no reciprocal.
 __device__ __forceinline__ float gelu_fast(float a) {
   const float x = __builtin_fminf(__builtin_fabsf(a), 6.0f);
   float p = -1.339070508e-06f;
@@ -181,9 +168,15 @@ __device__ __forceinline__ float sigmoid_fast(float g) {
 }
 
 // Row-layout epilogue on four consecutive columns starting at flat index idx (bf16 tensors).
+// gelu'(v) of the bf16 number with bit pattern `bits`, from the LDS copy of the table (layout: gemm.h)
+__device__ __forceinline__ float gelu_grad_lookup(const float* tab, uint32_t bits) {
+  const int m = min(max((int)(bits & 0x7fffu) - (GELU_TAB_EXP0 << 7), 0), GELU_TAB_NMAG - 1);
+  return tab[m + (int)(bits >> 15) * GELU_TAB_NMAG];
+}
+
 template <int EPI>
 __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f32x4& a, const f32x4& a2,
-                                          const u32x2& sv1, const u32x2& sv2) {
+                                          const u32x2& sv1, const u32x2& sv2, const float* tab) {
   auto st = [](void* base, size_t i, float v0, float v1, float v2, float v3) {
     *reinterpret_cast<u32x2*>(reinterpret_cast<bf16*>(base) + i) = u32x2{pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
   };
@@ -207,15 +200,10 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
     for (int i = 0; i < 4; ++i) h[i] = a[i] * sigmoid_fast(a[i]) * a2[i];
     st(g.C3, idx, h[0], h[1], h[2], h[3]);
   } else if constexpr (EPI == EPI_GELU_BWD) {
-    float s[4], o[4];
-    ld(sv1, s);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float ex;
-      const float ph = phi_fast(s[i], ex);
-      o[i] = a[i] * fmaf(s[i] * 0.39894228040143267794f, ex, ph);
-    }
-    st(g.C, idx, o[0], o[1], o[2], o[3]);
+    // the saved pre-activation is a bf16 number: its derivative is looked up, not computed
+    const float o0 = a[0] * gelu_grad_lookup(tab, sv1.x & 0xffffu), o1 = a[1] * gelu_grad_lookup(tab, sv1.x >> 16);
+    const float o2 = a[2] * gelu_grad_lookup(tab, sv1.y & 0xffffu), o3 = a[3] * gelu_grad_lookup(tab, sv1.y >> 16);
+    st(g.C, idx, o0, o1, o2, o3);
   } else if constexpr (EPI == EPI_SWIGLU_BWD) {
     float gg[4], uu[4], dg[4], du[4];
     ld(sv1, gg);
@@ -233,11 +221,12 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
 
 template <int BM, int BN, int BKT, bool DUAL>
 constexpr int gemm_bf16_stage_bytes() { return BM * BKT * 2 + BN * BKT * 2 * (DUAL ? 2 : 1); }
-template <int BM, int BN, int BKT, bool DUAL, int WGM, int WGN, int NB = NBUF>
+// TAB: the GELU-derivative table sits behind the ring (the GELU backward epilogue)
+template <int BM, int BN, int BKT, bool DUAL, int WGM, int WGN, int NB = NBUF, bool TAB = false>
 constexpr int gemm_bf16_lds_bytes() {
   constexpr int ring = NB * gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
   constexpr int slab = WGM * WGN * 32 * (BN / WGN + 8) * 4;   // epilogue: one 32-row fp32 slab per wave
-  return ring > slab ? ring : slab;
+  return (ring > slab ? ring : slab) + (TAB ? GELU_TAB_FLOATS * 4 : 0);
 }
 
 template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>
@@ -451,6 +440,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
     asm volatile("" ::: "memory");                                                                          \
     bload = b0; b0 = b1; b1 = (b1 + STAGE == NB * STAGE) ? 0 : b1 + STAGE;                                  \
   } while (0)
+    if constexpr (EPI == EPI_GELU_BWD) {
+      // the derivative table rides along with the first stage loads (older than they are, so the
+      // first wait of the pipeline covers it): 1 KB per wave and instruction, behind the ring
+      static_assert(GELU_TAB_FLOATS * 4 % (NT * 16) == 0, "whole block-wide loads");
+      const rsrc_t rt = make_rsrc(g.gelu_grad_tab, (size_t)GELU_TAB_FLOATS * 4);
+#pragma unroll
+      for (int i = 0; i < GELU_TAB_FLOATS * 4 / (NT * 16); ++i)
+        load_to_lds16(rt, smem_base + NB * STAGE + i * NT * 16 + wbase, (unsigned)(i * NT + tid) * 16u);
+    }
     if (KTT > 0) {
       // ring offsets: stage kt, stage kt+1, and the buffer the loads of stage kt+D go to (the one before b0)
       int b0 = 0, b1 = STAGE, bload = D * STAGE;
@@ -497,6 +495,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * P);
     const int rr = lane / LPR, c4 = lane % LPR;
     constexpr bool NEED_S1 = (EPI == EPI_GELU_BWD || EPI == EPI_SWIGLU_BWD), NEED_S2 = (EPI == EPI_SWIGLU_BWD);
+    const float* tab_lds = reinterpret_cast<const float*>(smem + NB * STAGE);
     // Saved tensors the backward epilogues read: the loads of a band are issued one band ahead (those of
     // the first band before anything else), so their latency hides behind the previous band's LDS round
     // trip and arithmetic (rows past the tile read the tile's first row and are dropped).
@@ -547,7 +546,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
             *c = g.accumulate ? *c + va[p] : va[p];
           } else {
             epilogue4<EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0],
-                           s1[NEED_S1 ? i & 1 : 0][NEED_S1 ? p : 0], s2[NEED_S2 ? i & 1 : 0][NEED_S2 ? p : 0]);
+                           s1[NEED_S1 ? i & 1 : 0][NEED_S1 ? p : 0], s2[NEED_S2 ? i & 1 : 0][NEED_S2 ? p : 0], tab_lds);
           }
         }
       }

@@ -13,9 +13,20 @@ namespace moe {
 __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept,
                                                        const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
                                                        int E, int tile_rows, int32_t* __restrict__ header,
-                                                       RowTile* __restrict__ tiles, int32_t* __restrict__ order) {
+                                                       RowTile* __restrict__ tiles, int32_t* __restrict__ order,
+                                                       float* __restrict__ gelu_grad_tab) {
   __shared__ int s_full[MOE_MAX_E], s_rem[MOE_MAX_E], s_start[MOE_MAX_E + 1], s_len[MOE_MAX_E];
   __shared__ int s_nfull, s_npart;
+  if (gelu_grad_tab != nullptr) {   // gelu'(v) for the bf16 numbers v = +-2^-16 .. 8 (layout: gemm.h)
+    for (int i = threadIdx.x; i < GELU_TAB_FLOATS; i += blockDim.x) {
+      float v = 0.f;
+      if (i < 2 * GELU_TAB_NMAG) {
+        const uint32_t bits = (uint32_t)((i % GELU_TAB_NMAG) + (GELU_TAB_EXP0 << 7)) | (i >= GELU_TAB_NMAG ? 0x8000u : 0u);
+        v = gelu_grad_f(__uint_as_float(bits << 16));
+      }
+      gelu_grad_tab[i] = v;
+    }
+  }
   const int e = threadIdx.x;
   int l = 0, h = 0;
   if (e < E) share_of(lo, hi, kept[e], e, l, h);
@@ -61,8 +72,9 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
 }
 
 int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, int E,
-                    int tile_rows, TileMap map, hipStream_t s) {
-  tile_map_kernel<<<1, 256, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles, map.order);
+                    int tile_rows, TileMap map, bool with_gelu_tab, hipStream_t s) {
+  tile_map_kernel<<<1, 256, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles, map.order,
+                                    with_gelu_tab ? map.gelu_grad_tab : nullptr);
   return launch_status();
 }
 
