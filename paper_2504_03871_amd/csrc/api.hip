@@ -173,11 +173,12 @@ int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, c
   const int A = cfg->T * cfg->k, d = cfg->d_model, f = cfg->d_ff;
   const int tr = tile_rows_for(cfg), max_tiles = max_row_tiles(A, cfg->E, tr);
   TileMap map = tile_map_at(static_cast<char*>(ws) + w.tile_map, max_row_tiles(A, cfg->E, TILE_ROWS_MIN), cfg->E);
-  CHECK(launch_tile_map(offsets, kept, slice_lo, slice_hi, cfg->E, tr, map, false, s));
+  CHECK(launch_tile_map(offsets, kept, slice_lo, slice_hi, cfg->E, tr, map,
+                        !swiglu && cfg->dtype == MOE_DTYPE_BF16 ? GELU_TAB_PHI : GELU_TAB_NONE, s));
   const size_t plane = (size_t)A * f * elt_size(cfg);
   char* sv = static_cast<char*>(saved);
   GemmArgs g = {};
-  g.tiles = map.tiles; g.ntiles = map.header; g.order = map.order; g.gelu_grad_tab = map.gelu_grad_tab;
+  g.tiles = map.tiles; g.ntiles = map.header; g.order = map.order; g.gelu_tab = map.gelu_tab;
   g.offsets = offsets; g.kept = kept; g.lo = slice_lo; g.hi = slice_hi; g.E = cfg->E;
   // hidden = act(x_perm W1)
   g.A = x_perm; g.B = W1; g.B2 = W1b; g.N = f; g.K = d;
@@ -242,13 +243,14 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
   const int A = cfg->T * cfg->k, d = cfg->d_model, f = cfg->d_ff;
   const int tr = tile_rows_for(cfg), max_tiles = max_row_tiles(A, cfg->E, tr);
   TileMap map = tile_map_at(static_cast<char*>(ws) + w.tile_map, max_row_tiles(A, cfg->E, TILE_ROWS_MIN), cfg->E);
-  CHECK(launch_tile_map(offsets, kept, slice_lo, slice_hi, cfg->E, tr, map, !swiglu && cfg->dtype == MOE_DTYPE_BF16, s));
+  CHECK(launch_tile_map(offsets, kept, slice_lo, slice_hi, cfg->E, tr, map,
+                        !swiglu && cfg->dtype == MOE_DTYPE_BF16 ? GELU_TAB_GRAD : GELU_TAB_NONE, s));
   const size_t plane = (size_t)A * f * elt_size(cfg);
   const char* sv = static_cast<const char*>(saved);
   char* dact = static_cast<char*>(ws) + w.ffn_bwd_dact;
   const void* hidden = swiglu ? sv + 2 * plane : sv + plane;
   GemmArgs g = {};
-  g.tiles = map.tiles; g.ntiles = map.header; g.order = map.order; g.gelu_grad_tab = map.gelu_grad_tab;
+  g.tiles = map.tiles; g.ntiles = map.header; g.order = map.order; g.gelu_tab = map.gelu_tab;
   g.offsets = offsets; g.kept = kept; g.lo = slice_lo; g.hi = slice_hi; g.E = cfg->E;
   g.accumulate = accumulate;
   // dH = dy W2^T, fused with the activation derivative -> dA (GELU) or dG, dU (SwiGLU)

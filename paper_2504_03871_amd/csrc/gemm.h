@@ -17,22 +17,25 @@ struct RowTile {
   int32_t pad;
 };
 
-// Table of the GELU derivative for bf16 arguments, used by the bf16 backward epilogue: the saved
-// pre-activation is a bf16 number, so gelu'(a) can be looked up instead of computed, and the entry is
-// the derivative of exactly that number.  Entry [sign][m], m = (bits & 0x7fff) - (GELU_TAB_EXP0 << 7)
-// clamped to [0, GELU_TAB_NMAG): magnitudes from 2^-16 up to (not including) 8; smaller ones read the
-// first entry (0.5 to within 1.3e-5), larger ones the last (1 or 0 to within 1e-13).
+// Tables over the bf16 numbers for the bf16 GELU epilogues.  The pre-activation is stored as a bf16
+// number, so the forward applies GELU to exactly that number (as a separate activation kernel on the
+// stored tensor would) and the backward takes the derivative at it; both are looked up instead of
+// computed: Phi(v) for the forward (h = a Phi(v)), gelu'(v) for the backward.  Entry [sign][m],
+// m = (bits & 0x7fff) - (GELU_TAB_EXP0 << 7) clamped to [0, GELU_TAB_NMAG): magnitudes from 2^-16 up to
+// (not including) 8; smaller ones read the first entry (Phi and gelu' are 0.5 there to within 1.3e-5),
+// larger ones the last (gelu' is 1 or 0 there to within 1e-13; the last Phi entries are set to exactly 1 and 0).
+enum GeluTable { GELU_TAB_NONE = 0, GELU_TAB_PHI = 1, GELU_TAB_GRAD = 2 };
 constexpr int GELU_TAB_EXP0 = 111;                 // biased exponent of 2^-16
 constexpr int GELU_TAB_NMAG = (130 - 111) * 128;   // 2432 magnitudes per sign
 constexpr int GELU_TAB_FLOATS = 6144;              // 2 * 2432 entries, padded to 24 KB (whole 1 KB wave loads)
 
 // Tile map in the workspace: header[0] = number of tiles, header[1] = number of full tiles; then the
-// tiles; then order[E] = the experts by descending share length (heaviest first); then the table above.
+// tiles; then order[E] = the experts by descending share length (heaviest first); then one table as above.
 struct TileMap {
   int32_t* header;
   RowTile* tiles;
   int32_t* order;
-  float* gelu_grad_tab;
+  float* gelu_tab;
 };
 inline size_t tile_map_bytes(int max_tiles, int E) {
   return 16 + (size_t)max_tiles * sizeof(RowTile) + (((size_t)E * 4 + 15) & ~(size_t)15) + (size_t)GELU_TAB_FLOATS * 4;
@@ -43,7 +46,7 @@ inline TileMap tile_map_at(void* ws_region, int max_tiles, int E) {
   m.header = reinterpret_cast<int32_t*>(base);
   m.tiles = reinterpret_cast<RowTile*>(base + 16);
   m.order = reinterpret_cast<int32_t*>(base + 16 + (size_t)max_tiles * sizeof(RowTile));
-  m.gelu_grad_tab = reinterpret_cast<float*>(base + 16 + (size_t)max_tiles * sizeof(RowTile) + (((size_t)E * 4 + 15) & ~(size_t)15));
+  m.gelu_tab = reinterpret_cast<float*>(base + 16 + (size_t)max_tiles * sizeof(RowTile) + (((size_t)E * 4 + 15) & ~(size_t)15));
   return m;
 }
 inline int max_row_tiles(int A, int E, int tile_rows) { return (A + tile_rows - 1) / tile_rows + E; }
@@ -76,7 +79,7 @@ struct GemmArgs {
   const RowTile* tiles;
   const int32_t* ntiles;
   const int32_t* order;     // experts by descending share length (weight-gradient GEMMs start the heaviest first)
-  const float* gelu_grad_tab;   // bf16 GELU backward epilogue: table of the derivative (GELU_TAB_FLOATS floats)
+  const float* gelu_tab;    // bf16 GELU epilogues: Phi (forward) or gelu' (backward) over the bf16 numbers
   const int32_t* offsets;
   const int32_t* kept;
   const int32_t* lo;
@@ -86,9 +89,10 @@ struct GemmArgs {
   int accumulate;
 };
 
-// with_gelu_tab: also fill the derivative table (the backward pass of a bf16 GELU layer)
+// table: which GELU table to fill as well (bf16 GELU layers: GELU_TAB_PHI before the forward GEMMs,
+// GELU_TAB_GRAD before the backward ones)
 int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, int E,
-                    int tile_rows, TileMap map, bool with_gelu_tab, hipStream_t s);
+                    int tile_rows, TileMap map, int table, hipStream_t s);
 
 // fp32 storage, fp32 FMA (any shape that passes check_cfg)
 int launch_gemm_f32(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s);

@@ -12,7 +12,7 @@ int gemm_bf16_tile_rows() { return T_BM; }
 template <int MODE, int EPI, bool DUAL, bool CHAIN>
 static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
   constexpr int BN = DUAL ? T_BN_DUAL : T_BN;
-  constexpr int lds = gemm_bf16_lds_bytes<T_BM, BN, T_BK, DUAL, T_WGM, T_WGN, NBUF, EPI == EPI_GELU_BWD>();
+  constexpr int lds = gemm_bf16_lds_bytes<T_BM, BN, T_BK, DUAL, T_WGM, T_WGN, NBUF, EPI == EPI_GELU_BWD || EPI == EPI_GELU_FWD>();
   auto kern = gemm_bf16_kernel<MODE, EPI, DUAL, CHAIN, T_BM, BN, T_BK, T_WGM, T_WGN>;
   static bool attr_done = false;   // benign race: the attribute call is idempotent
   if (!attr_done) {

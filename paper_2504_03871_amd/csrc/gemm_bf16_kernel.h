@@ -145,31 +145,13 @@ __device__ __forceinline__ bool block_to_tile(int n_rt, int n_full_rt, int ntn, 
 }
 
 // ---- fast activation pieces for bf16 outputs ----------------------------------------------------
-// gelu(a) = a Phi(a) through the lower tail t = Phi(-|a|) = 2^(x P(x) - 1), x = min(|a|, 6), where P is a
-// degree-6 polynomial fitted (Chebyshev nodes) to log2(erfc(x / sqrt 2)) / x on [0, 6].  Fitting the
-// logarithm of the tail keeps the relative error of t, and so of gelu(a) for negative a, below 2.5e-5;
-// the absolute error of gelu is below 2e-6 for every a (fp32 Horner evaluation included), far below
-// bf16 resolution.  Then gelu(a) = a (1 - t) for a >= 0 and a t for a < 0, i.e. max(a, 0) - |a t|.
-// One exponential and no reciprocal.
-__device__ __forceinline__ float gelu_fast(float a) {
-  const float x = __builtin_fminf(__builtin_fabsf(a), 6.0f);
-  float p = -1.339070508e-06f;
-  p = fmaf(p, x, 5.169712902e-05f);
-  p = fmaf(p, x, -8.538773221e-04f);
-  p = fmaf(p, x, 8.219408847e-03f);
-  p = fmaf(p, x, -5.341951027e-02f);
-  p = fmaf(p, x, -4.589222869e-01f);
-  p = fmaf(p, x, -1.151119706e+00f);
-  const float t = __builtin_amdgcn_exp2f(fmaf(x, p, -1.0f));
-  return __builtin_fmaxf(a, 0.f) - __builtin_fabsf(a * t);
-}
 __device__ __forceinline__ float sigmoid_fast(float g) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.44269504088896340736f));
 }
 
 // Row-layout epilogue on four consecutive columns starting at flat index idx (bf16 tensors).
-// gelu'(v) of the bf16 number with bit pattern `bits`, from the LDS copy of the table (layout: gemm.h)
-__device__ __forceinline__ float gelu_grad_lookup(const float* tab, uint32_t bits) {
+// Entry of the LDS copy of a GELU table (layout: gemm.h) for the bf16 number with bit pattern `bits`.
+__device__ __forceinline__ float gelu_tab_lookup(const float* tab, uint32_t bits) {
   const int m = min(max((int)(bits & 0x7fffu) - (GELU_TAB_EXP0 << 7), 0), GELU_TAB_NMAG - 1);
   return tab[m + (int)(bits >> 15) * GELU_TAB_NMAG];
 }
@@ -187,11 +169,11 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
   if constexpr (EPI == EPI_STORE) {
     st(g.C, idx, a[0], a[1], a[2], a[3]);
   } else if constexpr (EPI == EPI_GELU_FWD) {
-    st(g.C, idx, a[0], a[1], a[2], a[3]);
-    float h[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) h[i] = gelu_fast(a[i]);
-    st(g.C2, idx, h[0], h[1], h[2], h[3]);
+    // h = a Phi(v), v = the pre-activation as stored (bf16): GELU of the saved tensor, Phi looked up
+    const uint32_t p0 = pack_bf16x2(a[0], a[1]), p1 = pack_bf16x2(a[2], a[3]);
+    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16*>(g.C) + idx) = u32x2{p0, p1};
+    st(g.C2, idx, a[0] * gelu_tab_lookup(tab, p0 & 0xffffu), a[1] * gelu_tab_lookup(tab, p0 >> 16),
+       a[2] * gelu_tab_lookup(tab, p1 & 0xffffu), a[3] * gelu_tab_lookup(tab, p1 >> 16));
   } else if constexpr (EPI == EPI_SWIGLU_FWD) {
     st(g.C, idx, a[0], a[1], a[2], a[3]);
     st(g.C2, idx, a2[0], a2[1], a2[2], a2[3]);
@@ -201,8 +183,8 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
     st(g.C3, idx, h[0], h[1], h[2], h[3]);
   } else if constexpr (EPI == EPI_GELU_BWD) {
     // the saved pre-activation is a bf16 number: its derivative is looked up, not computed
-    const float o0 = a[0] * gelu_grad_lookup(tab, sv1.x & 0xffffu), o1 = a[1] * gelu_grad_lookup(tab, sv1.x >> 16);
-    const float o2 = a[2] * gelu_grad_lookup(tab, sv1.y & 0xffffu), o3 = a[3] * gelu_grad_lookup(tab, sv1.y >> 16);
+    const float o0 = a[0] * gelu_tab_lookup(tab, sv1.x & 0xffffu), o1 = a[1] * gelu_tab_lookup(tab, sv1.x >> 16);
+    const float o2 = a[2] * gelu_tab_lookup(tab, sv1.y & 0xffffu), o3 = a[3] * gelu_tab_lookup(tab, sv1.y >> 16);
     st(g.C, idx, o0, o1, o2, o3);
   } else if constexpr (EPI == EPI_SWIGLU_BWD) {
     float gg[4], uu[4], dg[4], du[4];
@@ -221,7 +203,7 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
 
 template <int BM, int BN, int BKT, bool DUAL>
 constexpr int gemm_bf16_stage_bytes() { return BM * BKT * 2 + BN * BKT * 2 * (DUAL ? 2 : 1); }
-// TAB: the GELU-derivative table sits behind the ring (the GELU backward epilogue)
+// TAB: a GELU table sits behind the ring (the GELU epilogues)
 template <int BM, int BN, int BKT, bool DUAL, int WGM, int WGN, int NB = NBUF, bool TAB = false>
 constexpr int gemm_bf16_lds_bytes() {
   constexpr int ring = NB * gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
@@ -440,11 +422,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
     asm volatile("" ::: "memory");                                                                          \
     bload = b0; b0 = b1; b1 = (b1 + STAGE == NB * STAGE) ? 0 : b1 + STAGE;                                  \
   } while (0)
-    if constexpr (EPI == EPI_GELU_BWD) {
-      // the derivative table rides along with the first stage loads (older than they are, so the
+    if constexpr (EPI == EPI_GELU_BWD || EPI == EPI_GELU_FWD) {
+      // the GELU table rides along with the first stage loads (older than they are, so the
       // first wait of the pipeline covers it): 1 KB per wave and instruction, behind the ring
       static_assert(GELU_TAB_FLOATS * 4 % (NT * 16) == 0, "whole block-wide loads");
-      const rsrc_t rt = make_rsrc(g.gelu_grad_tab, (size_t)GELU_TAB_FLOATS * 4);
+      const rsrc_t rt = make_rsrc(g.gelu_tab, (size_t)GELU_TAB_FLOATS * 4);
 #pragma unroll
       for (int i = 0; i < GELU_TAB_FLOATS * 4 / (NT * 16); ++i)
         load_to_lds16(rt, smem_base + NB * STAGE + i * NT * 16 + wbase, (unsigned)(i * NT + tid) * 16u);

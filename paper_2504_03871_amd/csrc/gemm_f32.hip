@@ -14,17 +14,21 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
                                                        const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
                                                        int E, int tile_rows, int32_t* __restrict__ header,
                                                        RowTile* __restrict__ tiles, int32_t* __restrict__ order,
-                                                       float* __restrict__ gelu_grad_tab) {
+                                                       float* __restrict__ gelu_tab, int table) {
   __shared__ int s_full[MOE_MAX_E], s_rem[MOE_MAX_E], s_start[MOE_MAX_E + 1], s_len[MOE_MAX_E];
   __shared__ int s_nfull, s_npart;
-  if (gelu_grad_tab != nullptr) {   // gelu'(v) for the bf16 numbers v = +-2^-16 .. 8 (layout: gemm.h)
+  if (table != GELU_TAB_NONE) {   // Phi(v) or gelu'(v) for the bf16 numbers v = +-2^-16 .. 8 (layout: gemm.h)
     for (int i = threadIdx.x; i < GELU_TAB_FLOATS; i += blockDim.x) {
       float v = 0.f;
       if (i < 2 * GELU_TAB_NMAG) {
         const uint32_t bits = (uint32_t)((i % GELU_TAB_NMAG) + (GELU_TAB_EXP0 << 7)) | (i >= GELU_TAB_NMAG ? 0x8000u : 0u);
-        v = gelu_grad_f(__uint_as_float(bits << 16));
+        const float a = __uint_as_float(bits << 16);
+        v = table == GELU_TAB_PHI ? 0.5f * erfcf(-a * 0.70710678118654752440f) : gelu_grad_f(a);
+        // the last magnitude also stands for everything larger: Phi is exactly 1 or 0 there, so that
+        // h = a Phi stays a or 0 however large a is
+        if (table == GELU_TAB_PHI && i % GELU_TAB_NMAG == GELU_TAB_NMAG - 1) v = i >= GELU_TAB_NMAG ? 0.f : 1.f;
       }
-      gelu_grad_tab[i] = v;
+      gelu_tab[i] = v;
     }
   }
   const int e = threadIdx.x;
@@ -72,9 +76,9 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
 }
 
 int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, int E,
-                    int tile_rows, TileMap map, bool with_gelu_tab, hipStream_t s) {
+                    int tile_rows, TileMap map, int table, hipStream_t s) {
   tile_map_kernel<<<1, 256, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles, map.order,
-                                    with_gelu_tab ? map.gelu_grad_tab : nullptr);
+                                    map.gelu_tab, table);
   return launch_status();
 }
 
