@@ -108,9 +108,10 @@ def moe_saved_bytes(cfg) -> int:
     return n.value
 
 
-def moe_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, stream=None):
+def moe_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, ws=None, stream=None):
     _check("moe_route", lib().moe_route(ctypes.byref(cfg), _ptr(x), _ptr(Wr), _ptr(bias), _ptr(logits_in),
-                                        _ptr(logits_out), _ptr(topk_idx), _ptr(topk_w), _stream() if stream is None else stream))
+                                        _ptr(logits_out), _ptr(topk_idx), _ptr(topk_w), _ptr(ws),
+                                        _stream() if stream is None else stream))
 
 
 def moe_dispatch(cfg, x, topk_idx, slice_lo, slice_hi, counts, kept, offsets, row_of, src_of, x_perm, ws,

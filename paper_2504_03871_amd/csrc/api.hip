@@ -2,6 +2,7 @@
 #include "common.h"
 #include "gemm.h"
 #include "prof.h"
+#include <algorithm>
 
 namespace moe {
 
@@ -43,8 +44,8 @@ WsLayout ws_layout(const moe_cfg* c) {
     if (c->E <= ROUTE_BWD_DENSE_E) rows = route_bwd_geom(c->T, c->d_model, (int)elt_size(c)).partial_rows;
     off += align_up(rows * c->d_model * c->E * 4, 256);
   }
-  w.route_wrt = off;
-  off += align_up((size_t)c->d_model * c->E * 4, 256);
+  w.route_wrt = off;   // shared with the forward's gate weight in MFMA operand layout (never live together)
+  off += align_up(std::max((size_t)c->d_model * c->E * 4, route_wfrag_bytes(c->d_model, c->E)), 256);
   w.ffn_bwd_dact = off;
   off += align_up((c->act == MOE_ACT_SWIGLU ? 2 : 1) * A * c->d_ff * elt_size(c), 256);
   w.total = off;
@@ -52,7 +53,8 @@ WsLayout ws_layout(const moe_cfg* c) {
 }
 
 // defined in the kernel files
-int launch_route(const moe_cfg*, const void*, const float*, const float*, const float*, float*, int32_t*, float*, hipStream_t);
+int launch_route(const moe_cfg*, const void*, const float*, const float*, const float*, float*, int32_t*, float*, void*,
+                 hipStream_t);
 int launch_route_bwd(const moe_cfg*, const void*, const float*, const int32_t*, const float*, const float*, float*,
                      float*, void*, float*, float*, hipStream_t);
 int launch_dispatch(const moe_cfg*, const void*, const int32_t*, const int32_t*, const int32_t*, int32_t*, int32_t*,
@@ -129,15 +131,18 @@ int moe_saved_bytes(const moe_cfg* cfg, size_t* bytes) {
 }
 
 int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* bias, const float* logits_in,
-              float* logits_out, int32_t* topk_idx, float* topk_w, void* stream) {
+              float* logits_out, int32_t* topk_idx, float* topk_w, void* ws, void* stream) {
   CHECK(check_cfg(cfg));
   if (logits_in == nullptr) { REQUIRE(x); REQUIRE(Wr); REQUIRE(logits_out); }
+  if (logits_in == nullptr && cfg->dtype == MOE_DTYPE_BF16) REQUIRE(ws);
   REQUIRE(topk_idx);
   REQUIRE(topk_w);
   ALIGNED(x); ALIGNED(Wr); ALIGNED(bias); ALIGNED(logits_in); ALIGNED(logits_out); ALIGNED(topk_idx); ALIGNED(topk_w);
+  ALIGNED(ws);
   if (cfg->T == 0) return MOE_OK;
+  void* wfrag = ws != nullptr ? static_cast<char*>(ws) + ws_layout(cfg).route_wrt : nullptr;
   ProfScope ps(MOE_PROF_ROUTE, (hipStream_t)stream);
-  return launch_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, (hipStream_t)stream);
+  return launch_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, wfrag, (hipStream_t)stream);
 }
 
 int moe_dispatch(const moe_cfg* cfg, const void* x, const int32_t* topk_idx, const int32_t* slice_lo,

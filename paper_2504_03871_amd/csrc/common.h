@@ -30,6 +30,7 @@ struct WsLayout {
   size_t total;
 };
 WsLayout ws_layout(const moe_cfg* c);
+size_t route_wfrag_bytes(int d, int E);   // gate weight in MFMA operand layout (route.hip)
 
 constexpr int DISPATCH_CHUNK = 1024;   // assignments ranked by one block
 constexpr int ROUTE_BWD_TOKENS = 128;  // tokens per block of the gate-backward kernel (many experts)

@@ -41,6 +41,54 @@ static RouteGeom route_geom(int E) {
   return g;
 }
 
+// Top-k and weights of token `tok` from its E logits in LDS (row tl of s_logit), run by the G lanes g =
+// 0..G-1 of the token (G <= 64 and a power of two: the lanes sit in one wave).  Lane g scans the experts
+// g, g+G, ...; k rounds of a lexicographic arg-max (larger value first, then lower expert id) with xor
+// shuffles; weights = softmax over the selected logits.  Every lane of the wave must call this.
+// `ld` = row pitch of s_logit in floats.
+__device__ __forceinline__ void route_select(const float* s_logit, int ld, int tl, int g, int G, bool live, int tok, int E,
+                                             int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+  unsigned taken = 0;
+  float sel[MOE_MAX_K];
+  int sid[MOE_MAX_K];
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_K; ++j) {
+    if (j < k) {
+      float bv = -INFINITY;
+      int bi = 0x7fffffff;
+      if (live) {
+        int slot = 0;
+        for (int e = g; e < E; e += G, ++slot) {
+          const float v = s_logit[tl * ld + e];
+          if (!((taken >> slot) & 1u) && (bi == 0x7fffffff || v > bv)) { bv = v; bi = e; }
+        }
+      }
+      for (int sft = G >> 1; sft > 0; sft >>= 1) {
+        const float ov = __shfl_xor(bv, sft, WAVE);
+        const int oi = __shfl_xor(bi, sft, WAVE);
+        // a real candidate beats "none"; larger value wins; equal values: lower id wins
+        const bool better = (oi != 0x7fffffff) && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+        if (better) { bv = ov; bi = oi; }
+      }
+      sel[j] = bv;
+      sid[j] = bi;
+      if (bi != 0x7fffffff && (bi & (G - 1)) == g) taken |= 1u << (bi / G);
+    }
+  }
+  if (live) {
+    float z[MOE_MAX_K], zs = 0.f;
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j)
+      if (j < k) { z[j] = expf(sel[j] - sel[0]); zs += z[j]; }
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j)
+      if (j < k && g == (j & (G - 1))) {
+        topk_idx[(size_t)tok * k + j] = sid[j];
+        topk_w[(size_t)tok * k + j] = z[j] / zs;
+      }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     const T* __restrict__ x, const float* __restrict__ Wr, const float* __restrict__ bias,
@@ -149,48 +197,118 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
   if (logits_out != nullptr)
     for (int i = tid; i < ntok * E; i += RT_THREADS) logits_out[(size_t)tok0 * E + i] = s_logit[i];
 
-  // top-k by the G lanes of each token (G <= 64 and a power of two: the lanes sit in one wave)
-  const int g = tid & (G - 1);
-  const bool live = tl < ntok;
-  unsigned taken = 0;
-  float sel[MOE_MAX_K];
-  int sid[MOE_MAX_K];
+  route_select(s_logit, E, tl, tid & (G - 1), G, tl < ntok, tok0 + tl, E, k, topk_idx, topk_w);
+}
+
+// ---------------------------------------------------------------- forward on the matrix cores (bf16 x)
+// logits = x Wr as a [T x d] x [d x E] product on v_mfma_f32_32x32x16_bf16.  x is bf16 already; the fp32
+// gate weight is split into two bf16 terms, w = hi + lo with hi = bf16(w), lo = bf16(w - hi), and both
+// products are accumulated in fp32, which keeps the weight to about 16 mantissa bits (relative error
+// 2^-17 per product, far below the bf16 resolution of x itself).
+//
+// A block of four waves owns 32 tokens; the waves split K in blocks of 64 (wave w: blocks w, w+4, ...),
+// each multiplies its share for all experts (NTL tiles of 32), and the four partial tiles are added in
+// wave order through LDS (deterministic).  Operands come straight from memory, no LDS staging:
+//  * A: lane (row r = l%32, half h = l/32) reads the 64 contiguous bytes x[t0+r][kb*64 + h*32 .. +31],
+//    i.e. a full 128-byte line per token row, and uses 8 of those 32 elements in each of four MFMA steps;
+//  * B: wr_frag_kernel writes the two bf16 terms once per call in exactly the register layout of those
+//    steps: unit ((((nt*nkb + kb)*4 + s)*2 + term)*64 + lane) holds, for lane (expert c = l%32 of tile nt,
+//    half h), the eight values Wr[kb*64 + h*32 + s*8 + i][nt*32 + c], i = 0..7 (zero past d or E); a wave
+//    reads a unit group as one contiguous kilobyte.
+// The K order inside a step differs from memory order, which a dot product does not mind as long as
+// both operands agree.  MFMA register layout: see gemm_bf16_kernel.h.
+typedef bf16 rt_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float rt_f32x16 __attribute__((ext_vector_type(16)));
+constexpr int RM_TOK = 32;
+
+__global__ void wr_frag_kernel(const float* __restrict__ Wr, rt_bf16x8* __restrict__ wfrag, int d, int E, int nkb, int ntl) {
+  const int u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= ntl * nkb * 4 * 2 * 64) return;
+  const int lane = u & 63, term = (u >> 6) & 1, s = (u >> 7) & 3, kb = (u >> 9) % nkb, nt = (u >> 9) / nkb;
+  const int c = nt * 32 + (lane & 31), k0 = kb * 64 + (lane >> 5) * 32 + s * 8;
+  rt_bf16x8 v;
 #pragma unroll
-  for (int j = 0; j < MOE_MAX_K; ++j) {
-    if (j < k) {
-      float bv = -INFINITY;
-      int bi = 0x7fffffff;
-      if (live) {
-        int slot = 0;
-        for (int e = g; e < E; e += G, ++slot) {
-          const float v = s_logit[tl * E + e];
-          if (!((taken >> slot) & 1u) && (bi == 0x7fffffff || v > bv)) { bv = v; bi = e; }
-        }
-      }
-      for (int sft = G >> 1; sft > 0; sft >>= 1) {
-        const float ov = __shfl_xor(bv, sft, WAVE);
-        const int oi = __shfl_xor(bi, sft, WAVE);
-        // a real candidate beats "none"; larger value wins; equal values: lower id wins
-        const bool better = (oi != 0x7fffffff) && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
-        if (better) { bv = ov; bi = oi; }
-      }
-      sel[j] = bv;
-      sid[j] = bi;
-      if (bi != 0x7fffffff && (bi & (G - 1)) == g) taken |= 1u << (bi / G);
+  for (int i = 0; i < 8; ++i) {
+    const float w = (c < E && k0 + i < d) ? Wr[(size_t)(k0 + i) * E + c] : 0.f;
+    const bf16 hi = (bf16)w;
+    v[i] = term == 0 ? hi : (bf16)(w - (float)hi);
+  }
+  wfrag[u] = v;
+}
+
+template <int NTL>
+__global__ __launch_bounds__(256) void route_mfma_kernel(
+    const bf16* __restrict__ x, const rt_bf16x8* __restrict__ wfrag, const float* __restrict__ bias,
+    float* __restrict__ logits_out, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d, int E, int k) {
+  extern __shared__ float part[];   // [4 waves][32 tokens][LD]; the sum ends up in part[0]
+  constexpr int LD = NTL * 32;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tok0 = blockIdx.x * RM_TOK, nkb = d / 64;
+  const int r = lane & 31, h = lane >> 5;
+  const bf16* xrow = x + (size_t)min(tok0 + r, Tn - 1) * d + h * 32;   // rows past the batch repeat the last token
+  rt_f32x16 acc[NTL];
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[nt][v] = 0.f;
+  // x (and, with one expert tile, the weight units too) of the next K block are loaded while this one
+  // multiplies: a block lives for a handful of K blocks per wave, so exposed load latency is what it costs
+  constexpr bool PFB = (NTL == 1);
+  rt_bf16x8 a[4], an[4], b[PFB ? 8 : 1], bn[PFB ? 8 : 1];
+  {
+    const int kb0 = min(wave, nkb - 1);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      a[s] = *reinterpret_cast<const rt_bf16x8*>(xrow + (size_t)kb0 * 64 + s * 8);
+      an[s] = a[s];
+    }
+    if constexpr (PFB) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) { b[q] = wfrag[((size_t)kb0 * 8 + q) * 64 + lane]; bn[q] = b[q]; }
     }
   }
-  if (live) {
-    float z[MOE_MAX_K], zs = 0.f;
+  for (int kb = wave; kb < nkb; kb += 4) {
+    if (kb + 4 < nkb) {
 #pragma unroll
-    for (int j = 0; j < MOE_MAX_K; ++j)
-      if (j < k) { z[j] = expf(sel[j] - sel[0]); zs += z[j]; }
+      for (int s = 0; s < 4; ++s) an[s] = *reinterpret_cast<const rt_bf16x8*>(xrow + (size_t)(kb + 4) * 64 + s * 8);
+      if constexpr (PFB) {
 #pragma unroll
-    for (int j = 0; j < MOE_MAX_K; ++j)
-      if (j < k && g == (j & (G - 1))) {
-        topk_idx[(size_t)(tok0 + tl) * k + j] = sid[j];
-        topk_w[(size_t)(tok0 + tl) * k + j] = z[j] / zs;
+        for (int q = 0; q < 8; ++q) bn[q] = wfrag[((size_t)(kb + 4) * 8 + q) * 64 + lane];
       }
+    }
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt) {
+      const rt_bf16x8* wf = wfrag + ((size_t)(nt * nkb + kb) * 8) * 64 + lane;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], PFB ? b[s * 2] : wf[(s * 2) * 64], acc[nt], 0, 0, 0);
+        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], PFB ? b[s * 2 + 1] : wf[(s * 2 + 1) * 64], acc[nt], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) a[s] = an[s];
+    if constexpr (PFB) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) b[q] = bn[q];
+    }
   }
+  // partial tiles to LDS: accumulator register v of lane l is token (v/4)*8 + (l/32)*4 + v%4, expert l%32
+  float* mine = part + (size_t)wave * RM_TOK * LD;
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mine[((v >> 2) * 8 + h * 4 + (v & 3)) * LD + nt * 32 + r] = acc[nt][v];
+  __syncthreads();
+  for (int i = tid; i < RM_TOK * LD; i += 256) {
+    const int e = i % LD;
+    const float sum = ((part[i] + part[RM_TOK * LD + i]) + part[2 * RM_TOK * LD + i]) + part[3 * RM_TOK * LD + i];
+    part[i] = sum + ((bias != nullptr && e < E) ? bias[e] : 0.f);
+  }
+  __syncthreads();
+  const int ntok = min(RM_TOK, Tn - tok0);
+  for (int i = tid; i < ntok * E; i += 256) logits_out[(size_t)tok0 * E + i] = part[(i / E) * LD + i % E];
+  const int tl = tid >> 3;   // eight lanes per token
+  route_select(part, LD, tl, tid & 7, 8, tl < ntok, tok0 + tl, E, k, topk_idx, topk_w);
 }
 
 // ---------------------------------------------------------------- backward
@@ -404,8 +522,38 @@ __global__ __launch_bounds__(256) void route_bwd_reduce_kernel(const float* __re
 }
 
 // ---------------------------------------------------------------- launchers
+size_t route_wfrag_bytes(int d, int E) {
+  const int ntl = E <= 32 ? 1 : (E <= 64 ? 2 : (E <= 128 ? 4 : 8));
+  return (size_t)ntl * ((d + 63) / 64) * 8 * 64 * 16;
+}
+
+template <int NTL>
+static int launch_route_mfma(const moe_cfg* c, const void* x, const float* Wr, const float* bias, float* logits_out,
+                             int32_t* idx, float* w, void* wfrag, hipStream_t s) {
+  const int nkb = c->d_model / 64, units = NTL * nkb * 8 * 64;
+  wr_frag_kernel<<<(units + 255) / 256, 256, 0, s>>>(Wr, (rt_bf16x8*)wfrag, c->d_model, c->E, nkb, NTL);
+  int rc = launch_status();
+  if (rc != MOE_OK) return rc;
+  const size_t lds = (size_t)4 * RM_TOK * NTL * 32 * 4;
+  auto kern = route_mfma_kernel<NTL>;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return set_hip_error(e);
+  }
+  kern<<<(c->T + RM_TOK - 1) / RM_TOK, 256, lds, s>>>((const bf16*)x, (const rt_bf16x8*)wfrag, bias, logits_out, idx, w,
+                                                     c->T, c->d_model, c->E, c->k);
+  return launch_status();
+}
+
+// wfrag: workspace for the gate weight in MFMA operand layout (route_wfrag_bytes), used for bf16 x
 int launch_route(const moe_cfg* c, const void* x, const float* Wr, const float* bias, const float* logits_in,
-                 float* logits_out, int32_t* idx, float* w, hipStream_t s) {
+                 float* logits_out, int32_t* idx, float* w, void* wfrag, hipStream_t s) {
+  if (c->dtype == MOE_DTYPE_BF16 && logits_in == nullptr) {
+    if (c->E <= 32) return launch_route_mfma<1>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    if (c->E <= 64) return launch_route_mfma<2>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    if (c->E <= 128) return launch_route_mfma<4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    return launch_route_mfma<8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+  }
   const RouteGeom gm = route_geom(c->E);
   const int grid = (c->T + gm.tok - 1) / gm.tok;
   const size_t es = c->dtype == MOE_DTYPE_BF16 ? 2 : 4;

@@ -69,7 +69,7 @@ class MoELayer:
 
     # ---- the hot path, one library call per line -------------------------------------------------
     def route(self, logits_in=None):
-        B.moe_route(self.cfg, self.x, self.Wr, self.bias, logits_in, self.logits, self.topk_idx, self.topk_w)
+        B.moe_route(self.cfg, self.x, self.Wr, self.bias, logits_in, self.logits, self.topk_idx, self.topk_w, self.ws)
 
     def dispatch(self, gather=True):
         B.moe_dispatch(self.cfg, self.x, self.topk_idx, self.slice_lo, self.slice_hi, self.counts, self.kept,

@@ -62,8 +62,11 @@ def test_pointer_validation_happens_before_any_launch():
         B.moe_route(cfg, None, P, None, None, P, P, P, stream=s)
     assert ei.value.code == -1
     with pytest.raises(B.MoeError) as ei:
-        B.moe_route(cfg, P, P, None, None, P, Q, P, stream=s)
+        B.moe_route(cfg, P, P, None, None, P, Q, P, ws=P, stream=s)
     assert ei.value.code == -5
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_route(cfg, P, P, None, None, P, P, P, ws=None, stream=s)      # bf16 gate needs the workspace
+    assert ei.value.code == -1
     with pytest.raises(B.MoeError) as ei:
         B.moe_dispatch(cfg, P, P, P, None, P, P, P, P, P, P, P, stream=s)      # only one slice bound
     assert ei.value.code == -4
