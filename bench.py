@@ -204,6 +204,37 @@ def main():
             d.update(bytes=sb[n], GBps=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4))
         stages[n] = d
 
+    # ---- the box itself: CU count and clock behind the MFMA peak, and what a plain device-to-device copy of
+    # 1 GiB reaches (read + write bytes over time), the practical ceiling of the HBM-bound kernels
+    props = torch.cuda.get_device_properties(dev)
+    big_src = torch.empty(512 * 1024 * 1024, dtype=torch.uint8, device=dev)
+    big_dst = torch.empty_like(big_src)
+    for _ in range(2):
+        big_dst.copy_(big_src)
+    ce = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ce[0].record()
+    for _ in range(5):
+        big_dst.copy_(big_src)
+    ce[1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * big_src.numel() / (ce[0].elapsed_time(ce[1]) * 1e-3) / 1e9
+    del big_src, big_dst
+    max_clock = None
+    try:   # rocminfo: the GPU agent's "Max Clock Freq. (MHz)"
+        import re
+        import subprocess
+        txt = subprocess.run(["rocminfo"], capture_output=True, text=True, timeout=30).stdout
+        for agent in txt.split("Agent ")[1:]:
+            if "gfx" in agent and "Device Type:             GPU" in agent:
+                m = re.search(r"Max Clock Freq\. \(MHz\):\s*(\d+)", agent)
+                if m:
+                    max_clock = int(m.group(1))
+                    break
+    except Exception:
+        pass
+    device = {"name": props.name, "compute_units": props.multi_processor_count, "max_clock_MHz": max_clock,
+              "copy_512MiB_GBps": round(copy_gbs, 1), "copy_frac_hbm": round(copy_gbs / PEAK_HBM_GBS, 4)}
+
     if args.copy_probe:
         src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device=dev)
         dst = torch.empty_like(src)
@@ -249,6 +280,7 @@ def main():
         "cpu_baseline": cpu,
         "kernels": kernels,
         "stages": stages,
+        "device": device,
     }
     print(json.dumps(out))
 
