@@ -36,6 +36,9 @@ CASES = {
     # rows wider than one block of column groups, and not a power of two of them
     "wide_rows": W["cfg1"].scaled(T=150, d=4160, f=128, E=4, k=2),
     "d320_e16": W["cfg2"].scaled(T=900, d=320, f=256, E=16, k=2),
+    # two and four expert tiles in the matrix-core gate kernel, a token count that is not a multiple of 32
+    "e48_k4": W["cfg1"].scaled(T=333, d=192, f=128, E=48, k=4),
+    "e100_k6": W["cfg1"].scaled(T=77, d=128, f=64, E=100, k=6),
 }
 
 
