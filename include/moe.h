@@ -180,10 +180,10 @@ MOE_API int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, co
 enum {
   MOE_PROF_GEMM1_FWD = 0,   /* x_perm W1 (+ activation) */
   MOE_PROF_GEMM2_FWD = 1,   /* H W2 */
-  MOE_PROF_DH_BWD = 2,      /* dy W2^T (+ activation derivative) */
-  MOE_PROF_DW2_BWD = 3,     /* H^T dy */
-  MOE_PROF_DW1_BWD = 4,     /* x_perm^T dA (SwiGLU: both weight gradients) */
-  MOE_PROF_DX_BWD = 5,      /* dA W1^T */
+  MOE_PROF_DH_BWD = 2,      /* dy W2^T (+ activation derivative); bf16 with few tiles: the same launch also does H^T dy */
+  MOE_PROF_DW2_BWD = 3,     /* H^T dy, when it has a launch of its own */
+  MOE_PROF_DW1_BWD = 4,     /* x_perm^T dA (SwiGLU: both weight gradients), those with a launch of their own */
+  MOE_PROF_DX_BWD = 5,      /* dA W1^T; bf16 with few tiles: the same launch also does x_perm^T dA */
   MOE_PROF_GATHER = 6,      /* row gather of moe_dispatch */
   MOE_PROF_COMBINE = 7,     /* moe_combine kernel */
   MOE_PROF_COMBINE_BWD = 8, /* moe_combine_bwd kernel */

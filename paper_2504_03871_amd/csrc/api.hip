@@ -258,33 +258,44 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
   g.tiles = map.tiles; g.ntiles = map.header; g.order = map.order; g.gelu_tab = map.gelu_tab;
   g.offsets = offsets; g.kept = kept; g.lo = slice_lo; g.hi = slice_hi; g.E = cfg->E;
   g.accumulate = accumulate;
-  // dH = dy W2^T, fused with the activation derivative -> dA (GELU) or dG, dU (SwiGLU)
-  g.A = dy_perm; g.B = W2; g.N = f; g.K = d;
-  g.C = dact; g.C2 = dact + plane; g.S1 = sv; g.S2 = sv + plane;
+  // Four GEMMs: dH = dy W2^T fused with the activation derivative -> dA (GELU) or dG, dU (SwiGLU);
+  // dW2[e] = H^T dy;  dW1[e] = x_perm^T dA (SwiGLU: dW1 from dG, dW1b from dU);
+  // dx_perm = dA W1^T (SwiGLU: dG W1^T + dU W1b^T).
+  GemmArgs gh = g, gw2 = g, gw1 = g, gx = g;
+  gh.A = dy_perm; gh.B = W2; gh.N = f; gh.K = d; gh.C = dact; gh.C2 = dact + plane; gh.S1 = sv; gh.S2 = sv + plane;
+  gw2.A = hidden; gw2.B = dy_perm; gw2.M = f; gw2.N = d;  gw2.C = dW2;
+  gw1.A = x_perm; gw1.B = dact; gw1.M = d; gw1.N = f; gw1.C = dW1;
+  gx.A = dact; gx.A2 = dact + plane; gx.B = W1; gx.B2 = W1b; gx.N = d; gx.K = f; gx.C = dx_perm;
+  const int epi_h = swiglu ? EPI_SWIGLU_BWD : EPI_GELU_BWD;
+  // bf16: a row-tile GEMM with few rounds of tiles shares its launch with the weight-gradient GEMM that
+  // follows it (dH with dW2, dx with dW1), whose tiles then start on the compute units that its last,
+  // partly filled round leaves idle.  With many rounds that idle share is small and separate launches
+  // keep the cache to one GEMM at a time.  (Timing brackets: a shared launch counts under the row-tile GEMM.)
+  const bool bf = cfg->dtype == MOE_DTYPE_BF16;
+  const long long few = 8ll * 256;   // tiles: about eight rounds on this chip
+  const bool pair_h = bf && (long long)((f + tr - 1) / tr) * max_tiles <= few;
+  const bool pair_x = bf && (long long)((d + tr - 1) / tr) * max_tiles <= few;
   {
     ProfScope ps(MOE_PROF_DH_BWD, s);
-    CHECK(launch_gemm(cfg, MODE_NT, swiglu ? EPI_SWIGLU_BWD : EPI_GELU_BWD, false, false, g, max_tiles, s));
+    if (pair_h) CHECK(launch_gemm_bf16_pair(epi_h, false, gh, max_tiles, gw2, s));
+    else CHECK(launch_gemm(cfg, MODE_NT, epi_h, false, false, gh, max_tiles, s));
   }
-  // dW2[e] = H^T dy
-  g.A = hidden; g.B = dy_perm; g.M = f; g.N = d; g.K = 0; g.C = dW2; g.C2 = nullptr; g.S1 = g.S2 = nullptr;
-  {
+  if (!pair_h) {
     ProfScope ps(MOE_PROF_DW2_BWD, s);
-    CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+    CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, gw2, 0, s));
   }
-  // dW1[e] = x_perm^T dA   (SwiGLU: dW1 from dG, dW1b from dU)
-  g.A = x_perm; g.B = dact; g.M = d; g.N = f; g.C = dW1;
-  {
+  if (!pair_x || swiglu) {
     ProfScope ps(MOE_PROF_DW1_BWD, s);
-    CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+    if (!pair_x) CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, gw1, 0, s));
     if (swiglu) {
-      g.B = dact + plane; g.C = dW1b;
-      CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, g, 0, s));
+      GemmArgs gw1b = gw1;
+      gw1b.B = dact + plane; gw1b.C = dW1b;
+      CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, gw1b, 0, s));
     }
   }
-  // dx_perm = dA W1^T   (SwiGLU: dG W1^T + dU W1b^T)
-  g.A = dact; g.A2 = dact + plane; g.B = W1; g.B2 = W1b; g.M = 0; g.N = d; g.K = f; g.C = dx_perm;
   ProfScope ps(MOE_PROF_DX_BWD, s);
-  return launch_gemm(cfg, MODE_NT, EPI_STORE, false, swiglu, g, max_tiles, s);
+  if (pair_x) return launch_gemm_bf16_pair(EPI_STORE, swiglu, gx, max_tiles, gw1, s);
+  return launch_gemm(cfg, MODE_NT, EPI_STORE, false, swiglu, gx, max_tiles, s);
 }
 
 int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx, const float* topk_w,

@@ -98,6 +98,8 @@ int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* 
 int launch_gemm_f32(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s);
 // bf16 storage, MFMA with fp32 accumulation
 int launch_gemm_bf16(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s);
+// one launch for an NT GEMM (epilogue epi1, chained or not) followed by a TN weight-gradient GEMM
+int launch_gemm_bf16_pair(int epi1, bool chain1, const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s);
 int gemm_bf16_tile_rows();
 
 #ifdef __HIPCC__

@@ -28,6 +28,37 @@ static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
   return launch_status();
 }
 
+// A row-tile GEMM (NT) and a weight-gradient GEMM (TN) in one launch; the first one's blocks come first.
+template <int EPI1, bool CHAIN1>
+static int launch_pair(const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s) {
+  constexpr int lds1 = gemm_bf16_lds_bytes<T_BM, T_BN, T_BK, false, T_WGM, T_WGN, NBUF, EPI1 == EPI_GELU_BWD>();
+  constexpr int lds2 = gemm_bf16_lds_bytes<T_BM, T_BN, T_BK, false, T_WGM, T_WGN>();
+  constexpr int lds = lds1 > lds2 ? lds1 : lds2;
+  auto kern = gemm_bf16_pair_kernel<MODE_NT, EPI1, CHAIN1, MODE_TN, EPI_DW, T_BM, T_BN, T_BK, T_WGM, T_WGN>;
+  static bool attr_done = false;   // benign race: the attribute call is idempotent
+  if (!attr_done) {
+    hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (err != hipSuccess) return set_hip_error(err);
+    attr_done = true;
+  }
+  // the first GEMM's block count is a multiple of the XCD count, so that a tile number still tells the
+  // XCD its block runs on for the second one (numbers past the last tile return at once)
+  const long long n1 = ((long long)((g1.N + T_BN - 1) / T_BN) * max_tiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+  const long long p2 = (long long)((g2.N + T_BN - 1) / T_BN) * ((g2.M + T_BM - 1) / T_BM);
+  const long long n2 = (p2 + NUM_XCD - 1) / NUM_XCD * NUM_XCD * g2.E;
+  if (n1 + n2 > 0x7fffffffll) return MOE_ERR_BAD_SHAPE;
+  kern<<<dim3(gemm_bf16_grid(n1 + n2)), T_WGM * T_WGN * 64, lds, s>>>(g1, g2, (int)n1);
+  return launch_status();
+}
+
+int launch_gemm_bf16_pair(int epi1, bool chain1, const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s) {
+  if (epi1 == EPI_GELU_BWD) return launch_pair<EPI_GELU_BWD, false>(g1, max_tiles, g2, s);
+  if (epi1 == EPI_SWIGLU_BWD) return launch_pair<EPI_SWIGLU_BWD, false>(g1, max_tiles, g2, s);
+  if (epi1 == EPI_STORE && !chain1) return launch_pair<EPI_STORE, false>(g1, max_tiles, g2, s);
+  if (epi1 == EPI_STORE && chain1) return launch_pair<EPI_STORE, true>(g1, max_tiles, g2, s);
+  return MOE_ERR_BAD_DTYPE;
+}
+
 int launch_gemm_bf16(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s) {
   if (mode == MODE_NN && epi == EPI_GELU_FWD) return launch_one<MODE_NN, EPI_GELU_FWD, false, false>(g, max_tiles, s);
   if (mode == MODE_NN && epi == EPI_SWIGLU_FWD && dual) return launch_one<MODE_NN, EPI_SWIGLU_FWD, true, false>(g, max_tiles, s);

@@ -124,10 +124,9 @@ struct Stage {
 // range per XCD (workgroups go to the eight XCDs round-robin), so tiles that run together on an XCD
 // share operand panels in its L2.  The partly filled row tiles follow in dispatch order: they are the
 // last blocks to start and fill the chip's final round.
-__device__ __forceinline__ bool block_to_tile(int n_rt, int n_full_rt, int ntn, int& rt, int& nt) {
+__device__ __forceinline__ bool block_to_tile(int b, int n_rt, int n_full_rt, int ntn, int& rt, int& nt) {
   constexpr int GROUP = 4;
   const int n_full = n_full_rt * ntn, n_all = n_rt * ntn;
-  const int b = blockIdx.x;
   if (b >= n_all) return false;
   if (b >= n_full) {                          // partial row tiles, largest first, in dispatch order
     rt = n_full_rt + (b - n_full) / ntn;
@@ -211,8 +210,10 @@ constexpr int gemm_bf16_lds_bytes() {
   return (ring > slab ? ring : slab) + (TAB ? GELU_TAB_FLOATS * 4 : 0);
 }
 
-template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>
-__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g) {
+// One output tile; vb = the tile's number in dispatch order.  Block-uniform control flow; returns at
+// once for numbers past the last tile (the grid is sized for the worst case).
+template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB>
+__device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, char* smem) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM / 32, WTN = BN / WGN / 32;
   constexpr int KS = BKT / 16;               // MFMA K steps per stage (even)
@@ -223,7 +224,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
   static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of K steps per stage");
   static_assert(NB >= 4, "loads run at least three stages ahead");
   constexpr int D = NB - 1;   // loads run D stages ahead of the MFMAs
-  extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps wave-dependent values scalar
@@ -240,9 +240,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
       // order of descending row count.
       const int ntm = (g.M + BM - 1) / BM;
       const int P = ntm * ntn, P8 = (P + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
-      const int p = blockIdx.x % P8;
+      const int p = vb % P8;
       if (p >= P) return;
-      e = g.order[blockIdx.x / P8];
+      e = g.order[vb / P8];
       m0 = (p / ntn) * BM;
       nt = p % ntn;
       rt = 0;
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
       mvalid = min(BM, g.M - m0);
       if (klen == 0 && g.accumulate) return;
     } else {
-      if (!block_to_tile(g.ntiles[0], g.ntiles[1], ntn, rt, nt)) return;
+      if (!block_to_tile(vb, g.ntiles[0], g.ntiles[1], ntn, rt, nt)) return;
       const RowTile t = g.tiles[rt];
       e = t.e;
       row0 = t.row0;
@@ -534,6 +534,25 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
       }
     }
   }
+}
+
+template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  gemm_bf16_tile<MODE, EPI, DUAL, CHAIN, BM, BN, BKT, WGM, WGN, NB>(g, blockIdx.x, smem);
+}
+
+// Two independent GEMMs in one launch: blocks below `first_blocks` take a tile of the first, the others a
+// tile of the second.  Blocks are dispatched in order, so the second GEMM's tiles start on the compute
+// units that the first one's last, partly filled round leaves idle (no stream or event in between,
+// and the two never compete for the cache from the start as two concurrent kernels would).
+template <int MODE1, int EPI1, bool CHAIN1, int MODE2, int EPI2, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_pair_kernel(GemmArgs g1, GemmArgs g2, int first_blocks) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  if ((int)blockIdx.x < first_blocks)
+    gemm_bf16_tile<MODE1, EPI1, false, CHAIN1, BM, BN, BKT, WGM, WGN, NB>(g1, blockIdx.x, smem);
+  else
+    gemm_bf16_tile<MODE2, EPI2, false, false, BM, BN, BKT, WGM, WGN, NB>(g2, blockIdx.x - first_blocks, smem);
 }
 
 inline unsigned gemm_bf16_grid(long long tiles) { return (unsigned)(tiles > 0 ? tiles : 1); }
