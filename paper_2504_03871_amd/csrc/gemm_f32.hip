@@ -17,8 +17,8 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
                                                        float* __restrict__ gelu_tab, int table) {
   __shared__ int s_full[MOE_MAX_E], s_rem[MOE_MAX_E], s_start[MOE_MAX_E + 1], s_len[MOE_MAX_E];
   __shared__ int s_nfull, s_npart;
-  if (table != GELU_TAB_NONE) {   // Phi(v) or gelu'(v) for the bf16 numbers v = +-2^-16 .. 8 (layout: gemm.h)
-    for (int i = threadIdx.x; i < GELU_TAB_FLOATS; i += blockDim.x) {
+  if (blockIdx.x > 0) {   // blocks past the first fill the table: Phi(v) or gelu'(v) for the bf16 numbers (layout: gemm.h)
+    for (int i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < GELU_TAB_FLOATS; i += (gridDim.x - 1) * blockDim.x) {
       float v = 0.f;
       if (i < 2 * GELU_TAB_NMAG) {
         const uint32_t bits = (uint32_t)((i % GELU_TAB_NMAG) + (GELU_TAB_EXP0 << 7)) | (i >= GELU_TAB_NMAG ? 0x8000u : 0u);
@@ -30,6 +30,7 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
       }
       gelu_tab[i] = v;
     }
+    return;
   }
   const int e = threadIdx.x;
   int l = 0, h = 0;
@@ -77,7 +78,8 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
 
 int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, int E,
                     int tile_rows, TileMap map, int table, hipStream_t s) {
-  tile_map_kernel<<<1, 256, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles, map.order,
+  const int grid = table == GELU_TAB_NONE ? 1 : 1 + GELU_TAB_FLOATS / 256;   // one thread per table entry
+  tile_map_kernel<<<grid, 256, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles, map.order,
                                     map.gelu_tab, table);
   return launch_status();
 }
