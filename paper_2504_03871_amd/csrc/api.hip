@@ -31,7 +31,7 @@ int check_cfg(const moe_cfg* c) {
 }
 
 WsLayout ws_layout(const moe_cfg* c) {
-  WsLayout w;
+  WsLayout w{};
   const size_t A = (size_t)c->T * c->k;
   size_t off = 0;
   w.dispatch_blk_cnt = off;
@@ -46,6 +46,9 @@ WsLayout ws_layout(const moe_cfg* c) {
   }
   w.route_wrt = off;   // shared with the forward's gate weight in MFMA operand layout (never live together)
   off += align_up(std::max((size_t)c->d_model * c->E * 4, route_wfrag_bytes(c->d_model, c->E)), 256);
+  w.ffn_split = off;
+  if (c->dtype == MOE_DTYPE_BF16 && split_k_applies(c->E, c->d_ff))
+    off += align_up(split_ws_bytes(c->E, std::max(c->d_model, 1)), 256);
   w.ffn_bwd_dact = off;
   off += align_up((c->act == MOE_ACT_SWIGLU ? 2 : 1) * A * c->d_ff * elt_size(c), 256);
   w.total = off;
@@ -195,6 +198,8 @@ int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, c
   // y = hidden W2
   g.A = swiglu ? sv + 2 * plane : sv + plane; g.B = W2; g.B2 = nullptr; g.N = d; g.K = f;
   g.C = y_perm; g.C2 = g.C3 = nullptr;
+  if (cfg->dtype == MOE_DTYPE_BF16 && split_k_applies(cfg->E, f))   // smallest row tiles: split-K (gemm.h)
+    g.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ffn_split);
   ProfScope ps(MOE_PROF_GEMM2_FWD, s);
   return launch_gemm(cfg, MODE_NN, EPI_STORE, false, false, g, max_tiles, s);
 }
@@ -295,6 +300,8 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
   }
   ProfScope ps(MOE_PROF_DX_BWD, s);
   if (pair_x) return launch_gemm_bf16_pair(EPI_STORE, swiglu, gx, max_tiles, gw1, s);
+  if (bf && !swiglu && split_k_applies(cfg->E, f))   // a launch of its own: its smallest row tiles use split-K
+    gx.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ffn_split);
   return launch_gemm(cfg, MODE_NT, EPI_STORE, false, swiglu, gx, max_tiles, s);
 }
 

@@ -26,6 +26,7 @@ struct WsLayout {
   size_t tile_map;          // int32 header + int4 entries (grouped GEMM row tiles)
   size_t route_partials;    // fp32 [nchunk][d][E]
   size_t route_wrt;         // fp32 [E][d]: transposed router weight
+  size_t ffn_split;         // fp32 partial sums of split-K row tiles (gemm.h), when split_k_applies
   size_t ffn_bwd_dact;      // storage type [planes][T*k][f]: dA (GELU) or dG | dU (SwiGLU)
   size_t total;
 };

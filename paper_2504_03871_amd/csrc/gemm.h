@@ -25,11 +25,25 @@ struct RowTile {
 // (not including) 8; smaller ones read the first entry (Phi and gelu' are 0.5 there to within 1.3e-5),
 // larger ones the last (gelu' is 1 or 0 there to within 1e-13; the last Phi entries are set to exactly 1 and 0).
 enum GeluTable { GELU_TAB_NONE = 0, GELU_TAB_PHI = 1, GELU_TAB_GRAD = 2 };
+// Split-K for the smallest row tiles.  A partly filled row tile of at most SPLIT_ROWS rows has almost no
+// MFMA work, but a block still walks all K stages for it at the pace of memory latency, and such tiles
+// run last, on a mostly idle chip.  For the plain-store GEMMs each of them is therefore cut into
+// SPLIT_K blocks along K that write fp32 partial sums [tile][k part][SPLIT_ROWS][N] into the workspace;
+// split_reduce adds the parts in fixed order and writes the bf16 rows.  Used when K is long enough
+// to matter and the experts are few (the partial sums take E * SPLIT_K * SPLIT_ROWS * N * 4 bytes).
+constexpr int SPLIT_ROWS = 64;
+constexpr int SPLIT_K = 8;
+constexpr int SPLIT_MAX_E = 32;
+constexpr int SPLIT_MIN_K = 2048;
+inline bool split_k_applies(int E, int K) { return E <= SPLIT_MAX_E && K >= SPLIT_MIN_K && K % (SPLIT_K * 32) == 0; }
+inline size_t split_ws_bytes(int E, int N) { return (size_t)E * SPLIT_K * SPLIT_ROWS * N * 4; }
+
 constexpr int GELU_TAB_EXP0 = 111;                 // biased exponent of 2^-16
 constexpr int GELU_TAB_NMAG = (130 - 111) * 128;   // 2432 magnitudes per sign
 constexpr int GELU_TAB_FLOATS = 6144;              // 2 * 2432 entries, padded to 24 KB (whole 1 KB wave loads)
 
-// Tile map in the workspace: header[0] = number of tiles, header[1] = number of full tiles; then the
+// Tile map in the workspace: header[0] = number of tiles, header[1] = number of full tiles, header[2] =
+// number of tiles of at most SPLIT_ROWS rows (the last ones of the list); then the
 // tiles; then order[E] = the experts by descending share length (heaviest first); then one table as above.
 struct TileMap {
   int32_t* header;
@@ -80,6 +94,7 @@ struct GemmArgs {
   const int32_t* ntiles;
   const int32_t* order;     // experts by descending share length (weight-gradient GEMMs start the heaviest first)
   const float* gelu_tab;    // bf16 GELU epilogues: Phi (forward) or gelu' (backward) over the bf16 numbers
+  float* split_ws;          // fp32 partial sums of the split row tiles, or NULL: no split-K (see SPLIT_K)
   const int32_t* offsets;
   const int32_t* kept;
   const int32_t* lo;
@@ -101,6 +116,8 @@ int launch_gemm_bf16(int mode, int epi, bool dual, bool chain, const GemmArgs& g
 // one launch for an NT GEMM (epilogue epi1, chained or not) followed by a TN weight-gradient GEMM
 int launch_gemm_bf16_pair(int epi1, bool chain1, const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s);
 int gemm_bf16_tile_rows();
+// adds the SPLIT_K partial sums of every split row tile and writes the bf16 rows of C [rows][N]
+int launch_split_reduce(const GemmArgs& g, hipStream_t s);
 
 #ifdef __HIPCC__
 // Element-wise epilogues, shared by both kernels.  `row` is the absolute permuted row, `col` the

@@ -24,7 +24,17 @@ static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
   long long tiles;
   if (MODE == MODE_TN) tiles = (long long)((ntn * ((g.M + T_BM - 1) / T_BM) + NUM_XCD - 1) / NUM_XCD * NUM_XCD) * g.E;
   else tiles = (long long)ntn * max_tiles;
+  const bool split = MODE != MODE_TN && EPI == EPI_STORE && !CHAIN && g.split_ws != nullptr;
+  if (split) tiles += (long long)g.E * ntn * (SPLIT_K - 1);   // every split row tile: SPLIT_K blocks per column tile instead of one
   kern<<<dim3(gemm_bf16_grid(tiles)), T_WGM * T_WGN * 64, lds, s>>>(g);
+  int rc = launch_status();
+  if (rc != MOE_OK || !split) return rc;
+  return launch_split_reduce(g, s);
+}
+
+int launch_split_reduce(const GemmArgs& g, hipStream_t s) {
+  const dim3 grid((SPLIT_ROWS * (g.N / 4) + 255) / 256, g.E);
+  split_reduce_kernel<<<grid, 256, 0, s>>>(g);
   return launch_status();
 }
 

@@ -230,6 +230,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
   const int wm = wave / WGN, wn = wave % WGN;
 
   int e, row0, mvalid, klen, m0 = 0, n0;
+  int split_tile = -1, ksplit = 0, kbase = 0;   // >= 0: this block computes one K part of a split row tile
   {
     const int ntn = (g.N + BN - 1) / BN;
     int rt, nt;
@@ -253,12 +254,29 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
       mvalid = min(BM, g.M - m0);
       if (klen == 0 && g.accumulate) return;
     } else {
-      if (!block_to_tile(vb, g.ntiles[0], g.ntiles[1], ntn, rt, nt)) return;
+      constexpr bool CAN_SPLIT = (EPI == EPI_STORE && !CHAIN);
+      const int n_rt = g.ntiles[0];
+      // split-K (gemm.h): the last n_sp row tiles are not part of the regular numbering; their blocks
+      // follow it, SPLIT_K per (row tile, column tile), each with a K range of its own
+      const int n_sp = (CAN_SPLIT && g.split_ws != nullptr) ? g.ntiles[2] : 0;
+      const int n_reg = n_rt - n_sp;
+      if (vb < n_reg * ntn) {
+        if (!block_to_tile(vb, n_reg, g.ntiles[1], ntn, rt, nt)) return;
+        klen = g.K;
+      } else {
+        const int q = vb - n_reg * ntn;
+        if (q >= n_sp * ntn * SPLIT_K) return;
+        ksplit = q % SPLIT_K;
+        nt = (q / SPLIT_K) % ntn;
+        split_tile = q / (SPLIT_K * ntn);
+        rt = n_reg + split_tile;
+        klen = g.K / SPLIT_K;
+        kbase = ksplit * klen;
+      }
       const RowTile t = g.tiles[rt];
       e = t.e;
       row0 = t.row0;
       mvalid = t.nrows;
-      klen = g.K;
     }
     n0 = nt * BN;
   }
@@ -323,14 +341,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
       boff = (size_t)row0 * g.N + n0;  bbytes = ((size_t)klen * g.N - n0) * 2;
       pa = g.M * 2; pb = g.N * 2; astep = BKT * pa; bstep = BKT * pb;
     } else if constexpr (MODE == MODE_NN) {
-      // A = [rows][K] rows row0..row0+mvalid; B = W_e [K][N] from column n0
-      aoff = (size_t)row0 * g.K;  abytes = (size_t)mvalid * g.K * 2;
-      boff = (size_t)e * g.K * g.N + n0;  bbytes = ((size_t)g.K * g.N - n0) * 2;
+      // A = [rows][K] rows row0..row0+mvalid; B = W_e [K][N] from column n0; both from K index kbase on
+      aoff = (size_t)row0 * g.K + kbase;  abytes = ((size_t)mvalid * g.K - kbase) * 2;
+      boff = ((size_t)e * g.K + kbase) * g.N + n0;  bbytes = ((size_t)(g.K - kbase) * g.N - n0) * 2;
       pa = g.K * 2; pb = g.N * 2; astep = BKT * 2; bstep = BKT * pb;
     } else {
       // A as above; B = W_e [N][K] rows n0..N
-      aoff = (size_t)row0 * g.K;  abytes = (size_t)mvalid * g.K * 2;
-      boff = ((size_t)e * g.N + n0) * g.K;  bbytes = (size_t)(g.N - n0) * g.K * 2;
+      aoff = (size_t)row0 * g.K + kbase;  abytes = ((size_t)mvalid * g.K - kbase) * 2;
+      boff = ((size_t)e * g.N + n0) * g.K + kbase;  bbytes = ((size_t)(g.N - n0) * g.K - kbase) * 2;
       pa = g.K * 2; pb = g.K * 2; astep = BKT * 2; bstep = BKT * 2;
     }
     const rsrc_t ra = make_rsrc(A0 + aoff, abytes), ra1 = make_rsrc(A1 + aoff, abytes);
@@ -523,7 +541,9 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
         const int m = (i * WGM + wm) * 32 + p * RPP + rr;
         const int n = wn * C + c4 * 4;
         if (m < mvalid && n < nvalid) {
-          if constexpr (MODE == MODE_TN) {   // fp32 weight gradient of expert e, 16 bytes per lane
+          if (MODE != MODE_TN && split_tile >= 0) {   // fp32 partial sum of this block's K part
+            *reinterpret_cast<f32x4*>(g.split_ws + (((size_t)split_tile * SPLIT_K + ksplit) * SPLIT_ROWS + m) * g.N + n0 + n) = va[p];
+          } else if constexpr (MODE == MODE_TN) {   // fp32 weight gradient of expert e, 16 bytes per lane
             f32x4* c = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + ((size_t)e * g.M + m0 + m) * g.N + n0 + n);
             *c = g.accumulate ? *c + va[p] : va[p];
           } else {
@@ -534,6 +554,23 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
       }
     }
   }
+}
+
+// Second half of split-K: C[row][n..n+3] = sum over the SPLIT_K parts, in part order, of the fp32 partial
+// sums of split row tile blockIdx.y; a thread owns four adjacent columns of one row.
+__global__ __launch_bounds__(256) void split_reduce_kernel(GemmArgs g) {
+  const int n_sp = g.ntiles[2], st = blockIdx.y;
+  if (st >= n_sp) return;
+  const RowTile t = g.tiles[g.ntiles[0] - n_sp + st];
+  const int per_row = g.N / 4, i = blockIdx.x * 256 + threadIdx.x;
+  const int m = i / per_row, n = (i % per_row) * 4;
+  if (m >= t.nrows) return;
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ks = 0; ks < SPLIT_K; ++ks)
+    sum += *reinterpret_cast<const f32x4*>(g.split_ws + (((size_t)st * SPLIT_K + ks) * SPLIT_ROWS + m) * g.N + n);
+  *reinterpret_cast<u32x2*>(reinterpret_cast<bf16*>(g.C) + (size_t)(t.row0 + m) * g.N + n) =
+      u32x2{pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3])};
 }
 
 template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>

@@ -9,7 +9,7 @@ namespace moe {
 // Tile order: every full tile (tile_rows valid rows) first, in expert order, then the experts' last,
 // partly filled tiles by descending row count.  Blocks are dispatched in tile order, so the short
 // tiles fill the chip's last round instead of each costing a full round.
-// header[0] = number of tiles, header[1] = number of full tiles.
+// header[0] = number of tiles, header[1] = number of full tiles, header[2] = number of tiles of at most SPLIT_ROWS rows.
 __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept,
                                                        const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
                                                        int E, int tile_rows, int32_t* __restrict__ header,
@@ -46,11 +46,18 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
   }
   if (threadIdx.x == 0) {
     int run = 0, parts = 0;
-    for (int i = 0; i < E; ++i) { s_start[i] = run; run += s_full[i]; parts += (s_rem[i] > 0); }
+    int small = 0;
+    for (int i = 0; i < E; ++i) {
+      s_start[i] = run;
+      run += s_full[i];
+      parts += (s_rem[i] > 0);
+      small += (s_rem[i] > 0 && s_rem[i] <= SPLIT_ROWS);
+    }
     s_nfull = run;
     s_npart = parts;
     header[0] = run + parts;
     header[1] = run;
+    header[2] = small;   // they are the last entries: the partly filled tiles are sorted by descending size
   }
   __syncthreads();
   if (e < E) {
