@@ -9,7 +9,7 @@
  * expert assignment of Section 4.2 appears at this level: a half-open range [lo_e, hi_e) over the
  * kept-token list of expert e.
  *
- * Conventions for every entry point
+ * Conventions for every entry point (the two host-only planner calls moe_asymea_* state their own)
  *   - Returns MOE_OK (0) or a negative MOE_ERR_* code.  Arguments are validated before anything is
  *     launched; on an argument error nothing has been enqueued and no output is touched.
  *   - `cfg` is a host pointer.  Every other pointer is a DEVICE pointer owned by the caller and must
@@ -170,6 +170,45 @@ MOE_API int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const vo
 MOE_API int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx,
                   const float* topk_w, const float* d_topk_w,
                   float* d_logits, float* dWr, void* dx, void* ws, void* stream);
+
+/*
+ * Planner of the asymmetric expert assignment (Section 4.2 of the paper, Algorithm 1 and the paragraph
+ * on memory limits).  HOST-ONLY: runs on the CPU, enqueues nothing, and `o` is a HOST pointer.
+ *
+ * In the paper's notation: n experts per layer, L layers, M attention GPUs and N expert GPUs in a
+ * group (one must divide the other, else MOE_ERR_BAD_SHAPE), T_A_attn = time of one layer's attention
+ * module on an attention GPU, T_E_attn = time of one expert module on an attention GPU, T_E_exp = time of
+ * one layer's expert module on an expert GPU (any common unit; profile them with the expert batch a GPU
+ * sees per micro-batch, Section 5).  A chunk is n_1 = max(1, N/M) experts acquired by each attention GPU
+ * = n_2 = n_1 M / N experts offloaded by each expert GPU.  Per layer the bubble T_gather = T_E_exp -
+ * T_A_attn is accumulated; whenever it reaches T_squeeze = (T_E_exp N / n) n_1 + (T_E_attn N / n) n_2,
+ * floor(bubble / T_squeeze) chunks are offloaded at that layer and their time is taken off the bubble.
+ * o[l] (l = 0 .. L-1) receives the number of experts EACH expert GPU offloads at layer l, a multiple
+ * of n_2.
+ * Memory bounds: n_max >= 0 caps the sum of o at floor(n_max / n_2) chunks (what the attention GPUs can
+ * hold), n_min > 0 raises it to ceil(n_min / n_2) chunks (what the expert GPUs cannot hold), through the
+ * paper's coefficients alpha and beta on T_gather; n_min <= 0 and n_max < 0: the unmodified algorithm.
+ * All arithmetic is IEEE double in the paper's order; since the per-layer step is a rounded quotient, the
+ * total can fall one chunk short of a bound it aims at, never beyond n_max.
+ * T_gather <= 0 gives all zeros (MOE_ERR_BAD_SHAPE if a positive n_min was asked for).  MOE_ERR_BAD_SHAPE
+ * also for n, L < 1, non-finite times, T_squeeze <= 0, n_max < n_min.
+ */
+MOE_API int moe_asymea_plan(int32_t n, int32_t L, int32_t M, int32_t N, double T_A_attn, double T_E_attn,
+                    double T_E_exp, int32_t n_min, int32_t n_max, int32_t* o);
+
+/*
+ * From one layer's offload count to the slice arguments of the device entry points.  HOST-ONLY;
+ * slice_lo / slice_hi are HOST int32[n] arrays, to be copied to the device by the caller.
+ *
+ * The paper moves whole experts and leaves open which; here expert e lives on expert GPU e / (n/N)
+ * (N must divide n), each expert GPU gives up the LAST o_l of its n/N experts, and the offloaded experts,
+ * by ascending id, go to the attention GPUs in equal contiguous runs of o_l N / M.  role 0 = expert GPU
+ * `rank` (0 .. N-1), role 1 = attention GPU `rank` (0 .. M-1).  An expert this GPU computes gets
+ * [0, INT32_MAX) (the device clamps it to the kept count), every other expert [0, 0).  Over all M + N
+ * GPUs the ranges cover every expert exactly once.  o_l must be a multiple of n_2 in [0, n/N].
+ */
+MOE_API int moe_asymea_shares(int32_t n, int32_t M, int32_t N, int32_t o_l, int32_t role, int32_t rank,
+                      int32_t* slice_lo, int32_t* slice_hi);
 
 /*
  * Benchmark aid, not a step of the layer: while armed, every launch of kernel `which` made by this

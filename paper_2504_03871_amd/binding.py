@@ -19,7 +19,7 @@ MAX_E, MAX_K = 256, 8
 
 SYMBOLS = ("moe_error_string", "moe_last_hip_error", "moe_workspace_bytes", "moe_saved_bytes", "moe_route",
            "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
-           "moe_route_bwd", "moe_profile_kernel")
+           "moe_route_bwd", "moe_asymea_plan", "moe_asymea_shares", "moe_profile_kernel")
 
 PROF = {"gemm1_fwd": 0, "gemm2_fwd": 1, "dh_bwd": 2, "dw2_bwd": 3, "dw1_bwd": 4, "dx_bwd": 5, "gather": 6,
         "combine": 7, "combine_bwd": 8, "route": 9}
@@ -60,6 +60,8 @@ def lib():
             "moe_combine_bwd": [cfgp] + [p] * 12,
             "moe_expert_ffn_bwd": [cfgp] + [p] * 14 + [i32, p, p],
             "moe_route_bwd": [cfgp] + [p] * 10,
+            "moe_asymea_plan": [i32] * 4 + [ctypes.c_double] * 3 + [i32, i32, ctypes.POINTER(i32)],
+            "moe_asymea_shares": [i32] * 6 + [ctypes.POINTER(i32), ctypes.POINTER(i32)],
             "moe_profile_kernel": [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
                                    ctypes.c_int],
         }
@@ -156,6 +158,22 @@ def moe_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, ws,
     _check("moe_route_bwd", lib().moe_route_bwd(ctypes.byref(cfg), _ptr(x), _ptr(Wr), _ptr(topk_idx), _ptr(topk_w),
                                                 _ptr(d_topk_w), _ptr(d_logits), _ptr(dWr), _ptr(dx), _ptr(ws),
                                                 _stream() if stream is None else stream))
+
+
+def moe_asymea_plan(n, L, M, N, T_A_attn, T_E_attn, T_E_exp, n_min=0, n_max=-1):
+    """Experts each expert GPU offloads at every layer (host-only call; list of L ints)."""
+    o = (ctypes.c_int32 * max(int(L), 1))()
+    _check("moe_asymea_plan", lib().moe_asymea_plan(int(n), int(L), int(M), int(N), float(T_A_attn), float(T_E_attn),
+                                                    float(T_E_exp), int(n_min), int(n_max), o))
+    return list(o)[:int(L)]
+
+
+def moe_asymea_shares(n, M, N, o_l, role, rank):
+    """Host-side slice bounds (lo, hi lists of n ints) of one GPU for a layer that offloads o_l experts."""
+    lo, hi = (ctypes.c_int32 * max(int(n), 1))(), (ctypes.c_int32 * max(int(n), 1))()
+    _check("moe_asymea_shares", lib().moe_asymea_shares(int(n), int(M), int(N), int(o_l), int(role), int(rank),
+                                                        lo, hi))
+    return list(lo)[:int(n)], list(hi)[:int(n)]
 
 
 def moe_profile_kernel(which, start_events, stop_events, n):

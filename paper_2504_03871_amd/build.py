@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_hip.so")
-SOURCES = ["api.hip", "route.hip", "dispatch.hip", "combine.hip", "gemm_f32.hip", "gemm_bf16.hip"]
+SOURCES = ["api.hip", "route.hip", "dispatch.hip", "combine.hip", "gemm_f32.hip", "gemm_bf16.hip", "asymea.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          # packed fp32 instructions are kept off for every device compile of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

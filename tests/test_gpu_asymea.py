@@ -1,0 +1,68 @@
+"""Asymmetric expert assignment end to end on one GPU (Section 4.2 of the paper): the planner's offload
+count for a layer becomes per-GPU slice ranges, every GPU of the group (attention and expert GPUs, played
+one after the other by the single device) runs the layer on its share through the C ABI, each run is
+compared with the oracle on the same share, and the shares together must reproduce the unsplit layer."""
+import numpy as np
+import pytest
+
+from paper_2504_03871_amd import binding as B
+from paper_2504_03871_amd import synth as S
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    "f32_M2_N4": (S.WORKLOADS["cfg0"].scaled(T=300, d=64, f=96, E=8, k=2), 2, 4),
+    "bf16_M1_N2": (S.WORKLOADS["cfg1"].scaled(T=700, d=128, f=256, E=8, k=2), 1, 2),
+    "bf16_swiglu_M4_N2": (S.WORKLOADS["cfg3"].scaled(T=500, d=128, f=192, E=8, k=3), 4, 2),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_shares_of_a_group_add_up(name):
+    import torch
+    w, M, N = CASES[name]
+    print(f"\n[case {name}] {w} M={M} N={N}", flush=True)
+    # times chosen so that the plan offloads one chunk at the second of two layers
+    n_1 = max(1, N // M)
+    n_2 = n_1 * M // N
+    t_a, t_exp, t_attn = 3.0, 4.0, 3.0
+    t_sq = (t_exp * N / w.E) * n_1 + (t_attn * N / w.E) * n_2
+    L_layers = int(np.ceil(t_sq / (t_exp - t_a)))
+    plan = B.moe_asymea_plan(w.E, L_layers, M, N, t_a, t_attn, t_exp)
+    assert plan[-1] == n_2 and sum(plan[:-1]) == 0, plan
+    o_l = plan[-1]
+
+    inp = S.make_inputs(w)
+    tol = U.TOL[w.dtype]
+    L = U.make_layer(w, inp)
+    L.step()
+    torch.cuda.synchronize()
+    g_logits = L.logits.cpu().numpy()
+    full = U.run_oracle(w, inp, gpu_logits=g_logits)
+    names = ["out", "dx", "dW1", "dW2", "dWr", "d_logits", "d_topk_w"] + (["dW1b"] if w.act == S.ACT_SWIGLU else [])
+    total = {n: np.zeros_like(U.host(getattr(L, n))) for n in names}
+    rows = 0
+    for role, cnt in ((0, N), (1, M)):
+        for rank in range(cnt):
+            lo, hi = B.moe_asymea_shares(w.E, M, N, o_l, role, rank)
+            owned = [e for e in range(w.E) if hi[e] > 0]
+            assert len(owned) == (w.E // N - o_l if role == 0 else o_l * N // M)
+            L.set_slices(lo, hi)
+            U.fill_sentinels(L)
+            L.step()
+            torch.cuda.synchronize()
+            ref = U.run_oracle(w, inp, gpu_logits=g_logits, lo=np.array(lo), hi=np.array(hi))
+            rows += int((ref["hi"] - ref["lo"]).sum())
+            for n, r in (("out", "out"), ("dx", "dx"), ("dW1", "dW1"), ("dW2", "dW2"), ("dWr", "dWr"),
+                         ("d_logits", "dlogits"), ("d_topk_w", "dw")):
+                U.assert_close(f"{n} role {role} rank {rank}", U.host(getattr(L, n)), ref[r], tol)
+            for e in range(w.E):
+                if e not in owned:
+                    assert not U.host(L.dW1)[e].any() and not U.host(L.dW2)[e].any(), "foreign expert's gradient"
+            for n in names:
+                total[n] += U.host(getattr(L, n))
+    assert rows == int(full["kept"].sum()), "the shares must cover every kept row exactly once"
+    for n, r in (("out", "out"), ("dx", "dx"), ("dW1", "dW1"), ("dW2", "dW2"), ("dWr", "dWr"),
+                 ("d_logits", "dlogits"), ("d_topk_w", "dw")):
+        U.assert_close(f"sum of shares: {n}", total[n], full[r], tol)
