@@ -42,8 +42,10 @@ constexpr int GELU_TAB_EXP0 = 111;                 // biased exponent of 2^-16
 constexpr int GELU_TAB_NMAG = (130 - 111) * 128;   // 2432 magnitudes per sign
 constexpr int GELU_TAB_FLOATS = 6144;              // 2 * 2432 entries, padded to 24 KB (whole 1 KB wave loads)
 
-// Tile map in the workspace: header[0] = number of tiles, header[1] = number of full tiles, header[2] =
-// number of tiles of at most SPLIT_ROWS rows (the last ones of the list); then the
+// Tile map in the workspace: header[0] = number of tiles, header[1] = number of tiles at the head of the
+// list that are walked XCD by XCD (the full tiles; with many experts of few tiles each the list is
+// expert-major and this is all of it), header[2] = number of tiles of at most SPLIT_ROWS rows at the
+// end of the list that may be split along K (0 for an expert-major list); then the
 // tiles; then order[E] = the experts by descending share length (heaviest first); then one table as above.
 struct TileMap {
   int32_t* header;

@@ -9,14 +9,14 @@ namespace moe {
 // Tile order: every full tile (tile_rows valid rows) first, in expert order, then the experts' last,
 // partly filled tiles by descending row count.  Blocks are dispatched in tile order, so the short
 // tiles fill the chip's last round instead of each costing a full round.
-// header[0] = number of tiles, header[1] = number of full tiles, header[2] = number of tiles of at most SPLIT_ROWS rows.
+// header[0] = number of tiles, header[1] = tiles walked XCD by XCD, header[2] = trailing tiles that may be split along K (gemm.h).
 __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept,
                                                        const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
                                                        int E, int tile_rows, int32_t* __restrict__ header,
                                                        RowTile* __restrict__ tiles, int32_t* __restrict__ order,
                                                        float* __restrict__ gelu_tab, int table) {
   __shared__ int s_full[MOE_MAX_E], s_rem[MOE_MAX_E], s_start[MOE_MAX_E + 1], s_len[MOE_MAX_E];
-  __shared__ int s_nfull, s_npart;
+  __shared__ int s_nfull, s_npart, s_major;
   if (blockIdx.x > 0) {   // blocks past the first fill the table: Phi(v) or gelu'(v) for the bf16 numbers (layout: gemm.h)
     for (int i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < GELU_TAB_FLOATS; i += (gridDim.x - 1) * blockDim.x) {
       float v = 0.f;
@@ -55,9 +55,21 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
     }
     s_nfull = run;
     s_npart = parts;
+    // Many experts of few row tiles each: an expert's weight panels are used by two or three tiles only,
+    // so these must run together (same XCD, same time) or the panels are fetched once per tile.  The
+    // list is then expert-major (each expert's full tiles, then its partly filled one) and the whole of
+    // it is walked as the full region is.
+    s_major = E > SPLIT_MAX_E && run < 3 * E;
+    if (s_major) {
+      int pos = 0;
+      for (int i = 0; i < E; ++i) {
+        s_start[i] = pos;
+        pos += s_full[i] + (s_rem[i] > 0);
+      }
+    }
     header[0] = run + parts;
-    header[1] = run;
-    header[2] = small;   // they are the last entries: the partly filled tiles are sorted by descending size
+    header[1] = s_major ? run + parts : run;
+    header[2] = s_major ? 0 : small;   // the last entries: the partly filled tiles are sorted by descending size
   }
   __syncthreads();
   if (e < E) {
@@ -78,7 +90,7 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
       t.row0 = base + s_full[e] * tile_rows;
       t.nrows = s_rem[e];
       t.pad = 0;
-      tiles[s_nfull + rank] = t;
+      tiles[s_major ? s_start[e] + s_full[e] : s_nfull + rank] = t;
     }
   }
 }

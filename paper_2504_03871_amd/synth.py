@@ -126,6 +126,10 @@ WORKLOADS = {
     # cfg4 with the skewed router of cfg2, so that capacity overflow really drops tokens
     "cfg4z": Workload("cfg4z", 4, T=16384, d=2048, f=8192, E=32, k=4, capacity_factor=1.25,
                       partial=True, zipf_s=1.2),
+    # many small experts (the model trend Section 6.2 of the paper says favours it): 128 and 256 experts,
+    # top-8, narrow FFNs; a few hundred rows per expert, so partly filled row tiles dominate
+    "cfg5": Workload("cfg5", 5, T=8192, d=2048, f=1024, E=128, k=8, act=ACT_SWIGLU),
+    "cfg6": Workload("cfg6", 6, T=8192, d=2048, f=1024, E=256, k=8),
 }
 
 
