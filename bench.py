@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--checkpoint", action="store_true",
+                    help="time the step of an activation-checkpointed layer: gate, dispatch and the saved "
+                         "activations are computed again before the backward (not the default metric)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy three times (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -92,8 +95,9 @@ def main():
         L.set_slices(lo, hi)
     S_rows = int((hi - lo).sum())
 
+    step = L.step_checkpointed if args.checkpoint else L.step
     for _ in range(args.warmup):
-        L.step()
+        step()
     torch.cuda.synchronize()
 
     # ---- HIP events around individual kernels (the library brackets the launches it is armed for)
@@ -158,7 +162,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        L.step()
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     dom_ms = read(armed)[dom]
@@ -291,7 +295,8 @@ def main():
         "dtype": "bf16" if bf else "f32",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: T={w.T} d_model={w.d} d_ff={w.f} E={w.E} top-{w.k} "
-                               f"{'SwiGLU' if w.act == S.ACT_SWIGLU else 'GELU'} rows_computed={S_rows}"},
+                               f"{'SwiGLU' if w.act == S.ACT_SWIGLU else 'GELU'} rows_computed={S_rows}"
+                               + (", activation checkpointing (gate, dispatch, GEMM1 repeated)" if args.checkpoint else "")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,

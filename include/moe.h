@@ -123,6 +123,20 @@ MOE_API int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const voi
                        void* saved, void* y_perm, void* ws, void* stream);
 
 /*
+ * Activation checkpointing (the paper trains with it, Section 6.1): the first half of
+ * moe_expert_ffn_fwd again.  Fills every plane of `saved` from x_perm and the first-layer weights with
+ * the same kernel the forward call uses, so the planes are bit-identical to the forward's, and does
+ * nothing else (no W2, no y_perm).  A caller that checkpoints keeps ONE `saved` buffer for all layers:
+ * before a layer's backward it repeats moe_route and moe_dispatch for that layer's input, calls this,
+ * then moe_expert_ffn_bwd as usual.  Costs the FLOPs of GEMM1 (2 T k d_model d_ff, SwiGLU twice that)
+ * and saves (planes - 1) x T k d_ff elements per layer of resident activations.
+ * Arguments as in moe_expert_ffn_fwd.
+ */
+MOE_API int moe_expert_ffn_recompute(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b,
+                             const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo,
+                             const int32_t* slice_hi, void* saved, void* ws, void* stream);
+
+/*
  * Combine (Section 2.1: outputs weighted by the scores and summed).
  * out[t] = sum over slots j = 0..k-1, in that order, of topk_w[t][j] * y_perm[row_of[t*k+j]],
  * taking only slots that are kept and inside this GPU's shares; fp32 accumulation.

@@ -164,19 +164,12 @@ int moe_dispatch(const moe_cfg* cfg, const void* x, const int32_t* topk_idx, con
                          (hipStream_t)stream);
 }
 
-int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b, const void* W2,
-                       const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo, const int32_t* slice_hi,
-                       void* saved, void* y_perm, void* ws, void* stream) {
-  CHECK(check_cfg(cfg));
-  CHECK(check_slices(slice_lo, slice_hi));
-  REQUIRE(x_perm); REQUIRE(W1); REQUIRE(W2); REQUIRE(offsets); REQUIRE(kept); REQUIRE(saved); REQUIRE(y_perm); REQUIRE(ws);
+namespace {
+// GEMM1 with its activation epilogue into `saved`, then (y_perm != NULL) GEMM2.
+int ffn_fwd_impl(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b, const void* W2,
+                 const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo, const int32_t* slice_hi,
+                 void* saved, void* y_perm, void* ws, hipStream_t s) {
   const bool swiglu = cfg->act == MOE_ACT_SWIGLU;
-  if (swiglu) REQUIRE(W1b);
-  if (!swiglu && W1b != nullptr) return MOE_ERR_BAD_DTYPE;
-  ALIGNED(x_perm); ALIGNED(W1); ALIGNED(W1b); ALIGNED(W2); ALIGNED(offsets); ALIGNED(kept); ALIGNED(slice_lo);
-  ALIGNED(slice_hi); ALIGNED(saved); ALIGNED(y_perm); ALIGNED(ws);
-  if (cfg->T == 0) return MOE_OK;
-  hipStream_t s = (hipStream_t)stream;
   const WsLayout w = ws_layout(cfg);
   const int A = cfg->T * cfg->k, d = cfg->d_model, f = cfg->d_ff;
   const int tr = tile_rows_for(cfg), max_tiles = max_row_tiles(A, cfg->E, tr);
@@ -195,6 +188,7 @@ int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, c
     ProfScope ps(MOE_PROF_GEMM1_FWD, s);
     CHECK(launch_gemm(cfg, MODE_NN, swiglu ? EPI_SWIGLU_FWD : EPI_GELU_FWD, swiglu, false, g, max_tiles, s));
   }
+  if (y_perm == nullptr) return MOE_OK;
   // y = hidden W2
   g.A = swiglu ? sv + 2 * plane : sv + plane; g.B = W2; g.B2 = nullptr; g.N = d; g.K = f;
   g.C = y_perm; g.C2 = g.C3 = nullptr;
@@ -202,6 +196,38 @@ int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, c
     g.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ffn_split);
   ProfScope ps(MOE_PROF_GEMM2_FWD, s);
   return launch_gemm(cfg, MODE_NN, EPI_STORE, false, false, g, max_tiles, s);
+}
+}  // namespace
+
+int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b, const void* W2,
+                       const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo, const int32_t* slice_hi,
+                       void* saved, void* y_perm, void* ws, void* stream) {
+  CHECK(check_cfg(cfg));
+  CHECK(check_slices(slice_lo, slice_hi));
+  REQUIRE(x_perm); REQUIRE(W1); REQUIRE(W2); REQUIRE(offsets); REQUIRE(kept); REQUIRE(saved); REQUIRE(y_perm); REQUIRE(ws);
+  const bool swiglu = cfg->act == MOE_ACT_SWIGLU;
+  if (swiglu) REQUIRE(W1b);
+  if (!swiglu && W1b != nullptr) return MOE_ERR_BAD_DTYPE;
+  ALIGNED(x_perm); ALIGNED(W1); ALIGNED(W1b); ALIGNED(W2); ALIGNED(offsets); ALIGNED(kept); ALIGNED(slice_lo);
+  ALIGNED(slice_hi); ALIGNED(saved); ALIGNED(y_perm); ALIGNED(ws);
+  if (cfg->T == 0) return MOE_OK;
+  return ffn_fwd_impl(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, saved, y_perm, ws, (hipStream_t)stream);
+}
+
+int moe_expert_ffn_recompute(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b,
+                             const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo,
+                             const int32_t* slice_hi, void* saved, void* ws, void* stream) {
+  CHECK(check_cfg(cfg));
+  CHECK(check_slices(slice_lo, slice_hi));
+  REQUIRE(x_perm); REQUIRE(W1); REQUIRE(offsets); REQUIRE(kept); REQUIRE(saved); REQUIRE(ws);
+  const bool swiglu = cfg->act == MOE_ACT_SWIGLU;
+  if (swiglu) REQUIRE(W1b);
+  if (!swiglu && W1b != nullptr) return MOE_ERR_BAD_DTYPE;
+  ALIGNED(x_perm); ALIGNED(W1); ALIGNED(W1b); ALIGNED(offsets); ALIGNED(kept); ALIGNED(slice_lo); ALIGNED(slice_hi);
+  ALIGNED(saved); ALIGNED(ws);
+  if (cfg->T == 0) return MOE_OK;
+  return ffn_fwd_impl(cfg, x_perm, W1, W1b, nullptr, offsets, kept, slice_lo, slice_hi, saved, nullptr, ws,
+                      (hipStream_t)stream);
 }
 
 int moe_combine(const moe_cfg* cfg, const void* y_perm, const float* topk_w, const int32_t* topk_idx,

@@ -79,6 +79,11 @@ class MoELayer:
         B.moe_expert_ffn_fwd(self.cfg, self.x_perm, self.W1, self.W1b, self.W2, self.offsets, self.kept,
                              self.slice_lo, self.slice_hi, self.saved, self.y_perm, self.ws)
 
+    def ffn_recompute(self):
+        """Activation checkpointing: refill the saved planes from x_perm (first half of ffn_fwd)."""
+        B.moe_expert_ffn_recompute(self.cfg, self.x_perm, self.W1, self.W1b, self.offsets, self.kept,
+                                   self.slice_lo, self.slice_hi, self.saved, self.ws)
+
     def combine(self):
         B.moe_combine(self.cfg, self.y_perm, self.topk_w, self.topk_idx, self.row_of, self.offsets, self.kept,
                       self.slice_lo, self.slice_hi, self.out, 0)
@@ -115,4 +120,14 @@ class MoELayer:
 
     def step(self):
         self.forward()
+        self.backward()
+
+    def step_checkpointed(self):
+        """Forward, then the backward of a checkpointed layer: gate, dispatch and the saved activations
+        are computed again from the layer input before the gradients (y_perm is kept: the combine
+        backward needs the expert outputs)."""
+        self.forward()
+        self.route()
+        self.dispatch()
+        self.ffn_recompute()
         self.backward()

@@ -76,6 +76,12 @@ def test_pointer_validation_happens_before_any_launch():
     with pytest.raises(B.MoeError) as ei:
         B.moe_expert_ffn_fwd(cfg, P, P, P, P, P, P, None, None, P, P, P, stream=s)   # W1b given for GELU
     assert ei.value.code == -3
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_expert_ffn_recompute(cfg, P, P, None, P, P, None, None, None, P, stream=s)   # no saved buffer
+    assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_expert_ffn_recompute(cfg, P, P, None, P, P, None, None, Q, P, stream=s)
+    assert ei.value.code == -5
     sw = B.make_cfg(8, 64, 128, 4, 2, act=B.ACT_SWIGLU)
     with pytest.raises(B.MoeError) as ei:
         B.moe_expert_ffn_fwd(sw, P, P, None, P, P, P, None, None, P, P, P, stream=s)  # SwiGLU without W1b

@@ -1,0 +1,57 @@
+"""Activation checkpointing (Section 6.1 of the paper: all runs use it): the recompute entry point must
+refill the saved activations with the very bits the forward wrote, so that the backward of a checkpointed
+layer equals the backward of a layer that kept them."""
+import pytest
+
+from paper_2504_03871_amd import synth as S
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+W = S.WORKLOADS
+CASES = {
+    "f32": W["cfg0"],
+    "bf16_gelu": W["cfg1"].scaled(T=1000, d=256, f=512),
+    "bf16_gelu_split_k": W["cfg1"].scaled(T=620, d=128, f=2304, E=4, k=2),
+    "bf16_swiglu_partial_cap": W["cfg3"].scaled(T=1200, d=256, f=320, E=6, k=3, capacity_factor=0.8, partial=True,
+                                                zipf_s=0.7),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_recomputed_activations_and_gradients_are_bit_identical(name):
+    import torch
+    w = CASES[name]
+    print(f"\n[case {name}] {w}", flush=True)
+    inp = S.make_inputs(w)
+    L = U.make_layer(w, inp)
+    if w.partial:
+        L.route()
+        L.dispatch(gather=False)
+        torch.cuda.synchronize()
+        L.set_slices(*S.partial_slices(w, U.host(L.kept)))
+    U.fill_sentinels(L)
+    L.step()
+    torch.cuda.synchronize()
+    grads = ["dx", "dx_perm", "dW1", "dW2", "dWr", "d_logits", "d_topk_w"] + (["dW1b"] if w.act == S.ACT_SWIGLU else [])
+    keep = {n: getattr(L, n).clone() for n in grads + ["out", "y_perm", "row_of", "src_of", "x_perm"]}
+    saved = L.saved.clone()
+    assert not torch.equal(saved, torch.full_like(saved, 0))
+
+    # a checkpointed layer: the saved planes are gone (another layer used the buffer), the gate and
+    # the dispatch run again on the layer input, the planes are recomputed, then the usual backward
+    y = L.y_perm.clone()
+    U.fill_sentinels(L)
+    L.y_perm.copy_(y)                       # expert outputs are what a checkpointing caller keeps
+    L.route()
+    L.dispatch()
+    L.ffn_recompute()
+    torch.cuda.synchronize()
+    assert torch.equal(L.saved, saved), "recomputed activations differ from the forward's"
+    assert torch.equal(L.row_of, keep["row_of"]) and torch.equal(L.x_perm.view(torch.int16), keep["x_perm"].view(torch.int16))
+    L.backward()
+    torch.cuda.synchronize()
+    for n in grads:
+        a, b = getattr(L, n), keep[n]
+        assert torch.equal(a.view(torch.int16 if a.element_size() == 2 else torch.int32),
+                           b.view(torch.int16 if b.element_size() == 2 else torch.int32)), n
