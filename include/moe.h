@@ -179,11 +179,12 @@ MOE_API int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const vo
  * Gate backward (Section 5: the branch through the confidence scores to the gate weights and to
  * the block input, accumulated with the gradient that comes back through the experts).
  * g = sum_j w_j dw_j;  d_logits[t][e_j] = w_j (dw_j - g), 0 for unselected experts;
- * dWr = x^T d_logits (overwritten);  dx += d_logits Wr^T (dx may be NULL to skip that part).
+ * dWr = x^T d_logits (accumulate = 0: overwritten; 1: added to, for gradient accumulation over
+ * micro-batches);  dx += d_logits Wr^T (dx may be NULL to skip that part).
  */
 MOE_API int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx,
                   const float* topk_w, const float* d_topk_w,
-                  float* d_logits, float* dWr, void* dx, void* ws, void* stream);
+                  float* d_logits, float* dWr, void* dx, int32_t accumulate, void* ws, void* stream);
 
 /*
  * Planner of the asymmetric expert assignment (Section 4.2 of the paper, Algorithm 1 and the paragraph

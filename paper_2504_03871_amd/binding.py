@@ -60,7 +60,7 @@ def lib():
             "moe_combine": [cfgp] + [p] * 9 + [i32, p],
             "moe_combine_bwd": [cfgp] + [p] * 12,
             "moe_expert_ffn_bwd": [cfgp] + [p] * 14 + [i32, p, p],
-            "moe_route_bwd": [cfgp] + [p] * 10,
+            "moe_route_bwd": [cfgp] + [p] * 8 + [i32, p, p],
             "moe_asymea_plan": [i32] * 4 + [ctypes.c_double] * 3 + [i32, i32, ctypes.POINTER(i32)],
             "moe_asymea_shares": [i32] * 6 + [ctypes.POINTER(i32), ctypes.POINTER(i32)],
             "moe_profile_kernel": [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
@@ -161,9 +161,9 @@ def moe_expert_ffn_bwd(cfg, dy_perm, x_perm, saved, W1, W1b, W2, offsets, kept, 
                                                           _stream() if stream is None else stream))
 
 
-def moe_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, ws, stream=None):
+def moe_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, ws, accumulate=0, stream=None):
     _check("moe_route_bwd", lib().moe_route_bwd(ctypes.byref(cfg), _ptr(x), _ptr(Wr), _ptr(topk_idx), _ptr(topk_w),
-                                                _ptr(d_topk_w), _ptr(d_logits), _ptr(dWr), _ptr(dx), _ptr(ws),
+                                                _ptr(d_topk_w), _ptr(d_logits), _ptr(dWr), _ptr(dx), int(accumulate), _ptr(ws),
                                                 _stream() if stream is None else stream))
 
 

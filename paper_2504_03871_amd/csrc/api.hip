@@ -59,7 +59,7 @@ WsLayout ws_layout(const moe_cfg* c) {
 int launch_route(const moe_cfg*, const void*, const float*, const float*, const float*, float*, int32_t*, float*, void*,
                  hipStream_t);
 int launch_route_bwd(const moe_cfg*, const void*, const float*, const int32_t*, const float*, const float*, float*,
-                     float*, void*, float*, float*, hipStream_t);
+                     float*, void*, int, float*, float*, hipStream_t);
 int launch_dispatch(const moe_cfg*, const void*, const int32_t*, const int32_t*, const int32_t*, int32_t*, int32_t*,
                     int32_t*, int32_t*, int32_t*, void*, int32_t*, hipStream_t);
 int launch_combine(const moe_cfg*, const void*, const float*, const int32_t*, const int32_t*, const int32_t*,
@@ -332,7 +332,8 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
 }
 
 int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx, const float* topk_w,
-                  const float* d_topk_w, float* d_logits, float* dWr, void* dx, void* ws, void* stream) {
+                  const float* d_topk_w, float* d_logits, float* dWr, void* dx, int32_t accumulate, void* ws,
+                  void* stream) {
   CHECK(check_cfg(cfg));
   REQUIRE(x); REQUIRE(Wr); REQUIRE(topk_idx); REQUIRE(topk_w); REQUIRE(d_topk_w); REQUIRE(d_logits); REQUIRE(dWr);
   REQUIRE(ws);
@@ -340,6 +341,7 @@ int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int3
   ALIGNED(dx); ALIGNED(ws);
   hipStream_t s = (hipStream_t)stream;
   if (cfg->T == 0) {
+    if (accumulate) return MOE_OK;
     const int n = cfg->d_model * cfg->E;
     fill_zero_kernel<<<(n + 255) / 256, 256, 0, s>>>(dWr, n);   // a kernel, not a memset: safe under graph capture
     return launch_status();
@@ -347,7 +349,7 @@ int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int3
   const WsLayout w = ws_layout(cfg);
   float* partials = reinterpret_cast<float*>(static_cast<char*>(ws) + w.route_partials);
   float* wrt = reinterpret_cast<float*>(static_cast<char*>(ws) + w.route_wrt);
-  return launch_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, partials, wrt, s);
+  return launch_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, accumulate != 0, partials, wrt, s);
 }
 
 }  // extern "C"

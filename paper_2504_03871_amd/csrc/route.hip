@@ -503,7 +503,7 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_dense_kernel(
 // out [E][d] (the dense kernel) instead of [d][E] like dWr itself.
 template <bool EXPERT_MAJOR>
 __global__ __launch_bounds__(256) void route_bwd_reduce_kernel(const float* __restrict__ partials, float* __restrict__ dWr,
-                                                               int d, int E, int rows) {
+                                                               int d, int E, int rows, int accumulate) {
   __shared__ float s_part[4][64];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, n = d * E;
   const int i = blockIdx.x * 64 + lane;
@@ -516,8 +516,8 @@ __global__ __launch_bounds__(256) void route_bwd_reduce_kernel(const float* __re
   __syncthreads();
   if (w == 0 && i < n) {
     const float t = ((s_part[0][lane] + s_part[1][lane]) + s_part[2][lane]) + s_part[3][lane];
-    if (EXPERT_MAJOR) dWr[(size_t)(i % d) * E + i / d] = t;
-    else dWr[i] = t;
+    float* o = dWr + (EXPERT_MAJOR ? (size_t)(i % d) * E + i / d : (size_t)i);
+    *o = accumulate ? *o + t : t;
   }
 }
 
@@ -580,8 +580,8 @@ static int launch_dwr(const moe_cfg* c, const void* x, const int32_t* idx, const
 }
 
 int launch_route_bwd(const moe_cfg* c, const void* x, const float* Wr, const int32_t* idx, const float* w,
-                     const float* dw, float* d_logits, float* dWr, void* dx, float* partials, float* WrT,
-                     hipStream_t s) {
+                     const float* dw, float* d_logits, float* dWr, void* dx, int accumulate, float* partials,
+                     float* WrT, hipStream_t s) {
   const int n = c->d_model * c->E;
   const int chunks = (c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS;
   const bool bf = c->dtype == MOE_DTYPE_BF16;
@@ -605,7 +605,7 @@ int launch_route_bwd(const moe_cfg* c, const void* x, const float* Wr, const int
     else { if (eb == 4) MOE_DWR_DENSE(float, 4); else if (eb == 8) MOE_DWR_DENSE(float, 8); else MOE_DWR_DENSE(float, 16); }
 #undef MOE_DWR_DENSE
     if ((rc = launch_status()) != MOE_OK) return rc;
-    route_bwd_reduce_kernel<true><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, gm.partial_rows);
+    route_bwd_reduce_kernel<true><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, gm.partial_rows, accumulate);
     return launch_status();
   }
   // columns per thread: as many as 128 KiB of LDS allow for 4 waves x E experts (d is a multiple of 4)
@@ -614,7 +614,7 @@ int launch_route_bwd(const moe_cfg* c, const void* x, const float* Wr, const int
   else if (vec == 2) rc = bf ? launch_dwr<bf16, 2>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 2>(c, x, idx, d_logits, partials, chunks, s);
   else rc = bf ? launch_dwr<bf16, 1>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 1>(c, x, idx, d_logits, partials, chunks, s);
   if (rc != MOE_OK) return rc;
-  route_bwd_reduce_kernel<false><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, chunks);
+  route_bwd_reduce_kernel<false><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, chunks, accumulate);
   return launch_status();
 }
 

@@ -12,7 +12,10 @@ from . import binding as B
 
 
 class MoELayer:
-    def __init__(self, T, d_model, d_ff, E, k, dtype=B.DTYPE_BF16, act=B.ACT_GELU, capacity=0, device="cuda:0"):
+    def __init__(self, T, d_model, d_ff, E, k, dtype=B.DTYPE_BF16, act=B.ACT_GELU, capacity=0, device="cuda:0",
+                 params=None):
+        """`params`: another MoELayer whose weights and weight-gradient buffers this one aliases (one
+        layer seen by several micro-batches, each with activation buffers of its own)."""
         self.cfg = B.make_cfg(T, d_model, d_ff, E, k, dtype, act, capacity)
         self.T, self.d, self.f, self.E, self.k, self.act = T, d_model, d_ff, E, k, act
         self.tdtype = torch.bfloat16 if dtype == B.DTYPE_BF16 else torch.float32
@@ -24,11 +27,14 @@ class MoELayer:
         e = lambda *s, **kw: torch.empty(*s, **kw)
         # parameters and inputs (filled by the caller)
         self.x = e(T, d_model, dtype=td, device=dev)
-        self.Wr = e(d_model, E, **f32)
-        self.bias = None
-        self.W1 = e(E, d_model, d_ff, dtype=td, device=dev)
-        self.W1b = e(E, d_model, d_ff, dtype=td, device=dev) if act == B.ACT_SWIGLU else None
-        self.W2 = e(E, d_ff, d_model, dtype=td, device=dev)
+        if params is None:
+            self.Wr = e(d_model, E, **f32)
+            self.bias = None
+            self.W1 = e(E, d_model, d_ff, dtype=td, device=dev)
+            self.W1b = e(E, d_model, d_ff, dtype=td, device=dev) if act == B.ACT_SWIGLU else None
+            self.W2 = e(E, d_ff, d_model, dtype=td, device=dev)
+        else:
+            self.Wr, self.bias, self.W1, self.W1b, self.W2 = params.Wr, params.bias, params.W1, params.W1b, params.W2
         self.d_out = e(T, d_model, dtype=td, device=dev)
         # forward state
         self.logits = e(T, E, **f32)
@@ -46,11 +52,14 @@ class MoELayer:
         self.dy_perm = e(A, d_model, dtype=td, device=dev)
         self.d_topk_w = e(T, k, **f32)
         self.dx_perm = e(A, d_model, dtype=td, device=dev)
-        self.dW1 = e(E, d_model, d_ff, **f32)
-        self.dW1b = e(E, d_model, d_ff, **f32) if act == B.ACT_SWIGLU else None
-        self.dW2 = e(E, d_ff, d_model, **f32)
+        if params is None:
+            self.dW1 = e(E, d_model, d_ff, **f32)
+            self.dW1b = e(E, d_model, d_ff, **f32) if act == B.ACT_SWIGLU else None
+            self.dW2 = e(E, d_ff, d_model, **f32)
+            self.dWr = e(d_model, E, **f32)
+        else:
+            self.dW1, self.dW1b, self.dW2, self.dWr = params.dW1, params.dW1b, params.dW2, params.dWr
         self.d_logits = e(T, E, **f32)
-        self.dWr = e(d_model, E, **f32)
         self.dx = e(T, d_model, dtype=td, device=dev)
 
     def saved_plane(self, i):
@@ -102,9 +111,9 @@ class MoELayer:
         B.moe_combine(self.cfg, self.dx_perm, None, self.topk_idx, self.row_of, self.offsets, self.kept,
                       self.slice_lo, self.slice_hi, self.dx, 0)
 
-    def route_bwd(self):
+    def route_bwd(self, accumulate=0):
         B.moe_route_bwd(self.cfg, self.x, self.Wr, self.topk_idx, self.topk_w, self.d_topk_w, self.d_logits,
-                        self.dWr, self.dx, self.ws)
+                        self.dWr, self.dx, self.ws, accumulate)
 
     def forward(self, logits_in=None):
         self.route(logits_in)
@@ -112,11 +121,12 @@ class MoELayer:
         self.ffn_fwd()
         self.combine()
 
-    def backward(self):
+    def backward(self, accumulate=0):
+        """accumulate = 1 adds this batch's weight gradients (experts and gate) to the buffers."""
         self.combine_bwd()
-        self.ffn_bwd()
+        self.ffn_bwd(accumulate)
         self.dispatch_bwd()
-        self.route_bwd()
+        self.route_bwd(accumulate)
 
     def step(self):
         self.forward()

@@ -1,0 +1,84 @@
+"""Pins for the zebra timeline model (Section 4.1 of the paper: the two scheduling constraints, Theorem 1)
+and the check of the engine's task order against it."""
+import random
+
+import pytest
+
+from oracle import zebra_timeline as Z
+from paper_2504_03871_amd import zebra
+
+
+def fwd_only(L, R, t_a, t_e, t_comm=0.0):
+    dur = {"AF": t_a, "EF": t_e, "DF": t_comm, "CF": t_comm, "AB": 0.0, "EB": 0.0, "CB": 0.0, "DB": 0.0}
+    return Z.simulate(L, R, dur)
+
+
+def test_hand_computed_forward_timeline():
+    # attention 3, experts 4, free communication, three micro-batches, A1 E1 A2 E2 A3: worked by hand
+    times, _ = fwd_only(3, 3, 3.0, 4.0)
+    want = {("AF", 1, 1): 0, ("AF", 1, 2): 3, ("AF", 1, 3): 6,
+            ("EF", 1, 1): 3, ("EF", 1, 2): 7, ("EF", 1, 3): 11,
+            ("AF", 2, 1): 9, ("AF", 2, 2): 12, ("AF", 2, 3): 15,
+            ("EF", 2, 1): 15, ("EF", 2, 2): 19, ("EF", 2, 3): 23,
+            ("AF", 3, 1): 19, ("AF", 3, 2): 23, ("AF", 3, 3): 27}
+    for t, s in want.items():
+        assert times[t][0] == s, (t, times[t])
+
+
+def test_both_constraints_hold_for_random_durations():
+    rnd = random.Random(2)
+    for _ in range(50):
+        L, R = rnd.randint(2, 4), rnd.randint(1, 4)
+        dur = {k: float(rnd.randint(0, 6)) for k in ("AF", "AB", "EF", "EB", "DF", "CF", "CB", "DB")}
+        times, span = Z.simulate(L, R, dur)
+        assert span is not None and len(times) == len(Z.dependencies(L, R))
+        for t, d in Z.dependencies(L, R).items():
+            if d is not None:
+                assert times[t][0] >= times[d][1]            # data dependency
+        for s in ("attn", "exp", "a2e", "e2a"):
+            iv = sorted(v for t, v in times.items() if Z.STREAM_OF[t[0]] == s)
+            for a, b in zip(iv, iv[1:]):
+                assert b[0] >= a[1]                          # one task at a time per stream
+
+
+def test_steady_state_attention_share_is_three_quarters():
+    # the paper's Asym-EA figure: experts a third slower than attention -> attention GPUs compute 75 % of the time
+    L, R = 12, 3
+    times, _ = fwd_only(L, R, 3.0, 4.0)
+    for i in range(4, L - 1):
+        period = times[("AF", i + 1, 1)][0] - times[("AF", i, 1)][0]
+        busy = R * 3.0
+        assert busy / period == 0.75
+    # experts not slower: no bubbles on the attention stream once the pipeline is full
+    times, _ = fwd_only(8, 4, 4.0, 3.0)
+    ends = sorted(v for t, v in times.items() if t[0] == "AF")
+    assert all(b[0] == a[1] for a, b in zip(ends, ends[1:]))
+
+
+@pytest.mark.parametrize("L,R", [(2, 2), (3, 2), (2, 3)])
+def test_no_order_beats_theorem_one(L, R):
+    rnd = random.Random(7 + L * 10 + R)
+    attn = list(Z.chain_respecting_orders(Z.attention_chains(L, R)))
+    exp = list(Z.chain_respecting_orders(Z.expert_chains(L, R)))
+    assert Z.theorem1_attention_order(L, R) in attn and Z.theorem1_expert_order(L, R) in exp
+    for trial in range(3):
+        # communication faster than computation, as the paper assumes
+        dur = {"AF": rnd.randint(2, 6), "AB": rnd.randint(2, 9), "EF": rnd.randint(2, 7), "EB": rnd.randint(2, 10),
+               "DF": 1, "CF": 1, "CB": 1, "DB": 1}
+        dur = {k: float(v) for k, v in dur.items()}
+        _, best = Z.simulate(L, R, dur)
+        assert best is not None
+        if len(attn) * len(exp) <= 5000:
+            pairs = ((a, e) for a in attn for e in exp)
+        else:      # vary one stream at a time around the theorem's order
+            pairs = [(a, None) for a in rnd.sample(attn, min(len(attn), 3000))] + [(None, e) for e in exp]
+        for a, e in pairs:
+            _, span = Z.simulate(L, R, dur, a, e)
+            assert span is None or span >= best, (dur, a, e, span, best)
+
+
+def test_engine_uses_the_expert_order_of_theorem_one():
+    for L, R in ((1, 1), (2, 3), (4, 2)):
+        # the engine numbers expert blocks 0 .. L-1; the model's expert blocks are 1 .. (L+1)-1
+        want = [("F" if k == "EF" else "B", i - 1, j - 1) for k, i, j in Z.theorem1_expert_order(L + 1, R)]
+        assert zebra.expert_stream_order(L, R) == want
