@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap-gate-bwd", action="store_true",
+                    help="run the gate's weight gradient on a second stream next to the expert backward "
+                         "(measured: no gain; not the default)")
     ap.add_argument("--checkpoint", action="store_true",
                     help="time the step of an activation-checkpointed layer: gate, dispatch and the saved "
                          "activations are computed again before the backward (not the default metric)")
@@ -73,6 +76,8 @@ def main():
     bf = w.dtype == S.DT_BF16
     dev = "cuda:0"
     L = MoELayer(w.T, w.d, w.f, w.E, w.k, dtype=w.dtype, act=w.act, capacity=w.capacity, device=dev)
+    if args.overlap_gate_bwd:
+        L.enable_gate_overlap()
 
     def up(name):
         if bf:

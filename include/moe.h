@@ -180,7 +180,10 @@ MOE_API int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const vo
  * the block input, accumulated with the gradient that comes back through the experts).
  * g = sum_j w_j dw_j;  d_logits[t][e_j] = w_j (dw_j - g), 0 for unselected experts;
  * dWr = x^T d_logits (accumulate = 0: overwritten; 1: added to, for gradient accumulation over
- * micro-batches);  dx += d_logits Wr^T (dx may be NULL to skip that part).
+ * micro-batches);  dx += d_logits Wr^T.  dx may be NULL to skip that part, dWr may be NULL to skip the
+ * weight gradient (d_logits is always written): the two parts are independent, so a caller can run the
+ * weight-gradient part on a second stream next to the expert backward, with a workspace and a d_logits
+ * buffer of its own, and add to dx once the gradient through the experts has been written.
  */
 MOE_API int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx,
                   const float* topk_w, const float* d_topk_w,

@@ -335,13 +335,13 @@ int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int3
                   const float* d_topk_w, float* d_logits, float* dWr, void* dx, int32_t accumulate, void* ws,
                   void* stream) {
   CHECK(check_cfg(cfg));
-  REQUIRE(x); REQUIRE(Wr); REQUIRE(topk_idx); REQUIRE(topk_w); REQUIRE(d_topk_w); REQUIRE(d_logits); REQUIRE(dWr);
+  REQUIRE(x); REQUIRE(Wr); REQUIRE(topk_idx); REQUIRE(topk_w); REQUIRE(d_topk_w); REQUIRE(d_logits);
   REQUIRE(ws);
   ALIGNED(x); ALIGNED(Wr); ALIGNED(topk_idx); ALIGNED(topk_w); ALIGNED(d_topk_w); ALIGNED(d_logits); ALIGNED(dWr);
   ALIGNED(dx); ALIGNED(ws);
   hipStream_t s = (hipStream_t)stream;
   if (cfg->T == 0) {
-    if (accumulate) return MOE_OK;
+    if (accumulate || dWr == nullptr) return MOE_OK;
     const int n = cfg->d_model * cfg->E;
     fill_zero_kernel<<<(n + 255) / 256, 256, 0, s>>>(dWr, n);   // a kernel, not a memset: safe under graph capture
     return launch_status();

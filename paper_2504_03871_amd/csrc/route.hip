@@ -594,6 +594,7 @@ int launch_route_bwd(const moe_cfg* c, const void* x, const float* Wr, const int
   if (bf) route_bwd_dx_kernel<bf16><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (bf16*)dx, c->T, c->d_model, c->E, c->k);
   else route_bwd_dx_kernel<float><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (float*)dx, c->T, c->d_model, c->E, c->k);
   if ((rc = launch_status()) != MOE_OK) return rc;
+  if (dWr == nullptr) return MOE_OK;
   if (c->E <= ROUTE_BWD_DENSE_E) {
     const RouteBwdGeom gm = route_bwd_geom(c->T, c->d_model, bf ? 2 : 4);
     const dim3 grid(gm.col_blocks, gm.row_blocks);

@@ -43,6 +43,7 @@ class MoELayer:
         self.counts, self.kept, self.offsets = e(E, **i32), e(E, **i32), e(E + 1, **i32)
         self.row_of, self.src_of = e(A, **i32), e(A, **i32)
         self.slice_lo = self.slice_hi = None
+        self.side = None
         self.x_perm = e(A, d_model, dtype=td, device=dev)
         self.saved = torch.empty(B.moe_saved_bytes(self.cfg), dtype=torch.uint8, device=dev)
         self.y_perm = e(A, d_model, dtype=td, device=dev)
@@ -123,10 +124,36 @@ class MoELayer:
 
     def backward(self, accumulate=0):
         """accumulate = 1 adds this batch's weight gradients (experts and gate) to the buffers."""
+        if self.side is not None:
+            return self.backward_overlapped(accumulate)
         self.combine_bwd()
         self.ffn_bwd(accumulate)
         self.dispatch_bwd()
         self.route_bwd(accumulate)
+
+    def enable_gate_overlap(self):
+        """Run the gate's weight gradient on a second stream next to the expert backward (both need only
+        d_topk_w); it gets a workspace and a d_logits buffer of its own."""
+        self.side = torch.cuda.Stream(device=self.device)
+        self.side_ws = torch.empty_like(self.ws)
+        self.side_d_logits = torch.empty_like(self.d_logits)
+        self.ev_fork, self.ev_join = torch.cuda.Event(), torch.cuda.Event()
+
+    def backward_overlapped(self, accumulate=0):
+        main = torch.cuda.current_stream(self.device)
+        self.combine_bwd()
+        self.ev_fork.record(main)
+        self.side.wait_event(self.ev_fork)
+        with torch.cuda.stream(self.side):     # d_logits and dWr = x^T d_logits
+            B.moe_route_bwd(self.cfg, self.x, self.Wr, self.topk_idx, self.topk_w, self.d_topk_w, self.d_logits,
+                            self.dWr, None, self.side_ws, accumulate)
+            self.ev_join.record(self.side)
+        self.ffn_bwd(accumulate)
+        self.dispatch_bwd()
+        # dx += d_logits Wr^T once the gradient through the experts is in dx
+        B.moe_route_bwd(self.cfg, self.x, self.Wr, self.topk_idx, self.topk_w, self.d_topk_w, self.side_d_logits,
+                        None, self.dx, self.ws, 0)
+        main.wait_event(self.ev_join)
 
     def step(self):
         self.forward()

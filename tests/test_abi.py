@@ -98,3 +98,9 @@ def test_pointer_validation_happens_before_any_launch():
     with pytest.raises(B.MoeError) as ei:
         B.moe_route_bwd(cfg, P, P, P, P, P, P, P, Q, P, stream=s)
     assert ei.value.code == -5
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_route_bwd(cfg, P, P, P, P, P, None, P, P, P, stream=s)     # d_logits is always written
+    assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_route_bwd(cfg, P, P, P, P, P, P, None, None, None, stream=s)   # both parts skipped is fine, no workspace is not
+    assert ei.value.code == -1

@@ -194,3 +194,27 @@ def test_empty_token_batch():
     B.moe_dispatch(cfg, None, dummy, None, None, counts, kept, offsets, dummy, dummy, None, ws)
     torch.cuda.synchronize()
     assert counts.tolist() == [0] * 4 and kept.tolist() == [0] * 4 and offsets.tolist() == [0] * 5
+
+
+def test_gate_weight_gradient_on_a_second_stream():
+    """The two halves of the gate backward (weight gradient; input gradient) run as separate calls, the
+    first on a second stream next to the expert backward: same bits as the one-call, one-stream backward."""
+    import torch
+    for name in ("cfg2_small", "many_experts"):
+        w = CASES[name]
+        inp = S.make_inputs(w)
+        L = U.make_layer(w, inp)
+        L.step()
+        torch.cuda.synchronize()
+        names = ("dx", "dWr", "d_logits", "dW1", "dW2", "dx_perm")
+        first = {n: getattr(L, n).clone() for n in names}
+        U.fill_sentinels(L)
+        L.enable_gate_overlap()
+        L.step()
+        L.step()        # events and the side buffers are reused
+        torch.cuda.synchronize()
+        for n in names:
+            a, b = getattr(L, n), first[n]
+            view = torch.int16 if a.element_size() == 2 else torch.int32
+            assert torch.equal(a.view(view), b.view(view)), (name, n)
+        assert torch.equal(L.side_d_logits, L.d_logits)
