@@ -374,55 +374,83 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     // Fragments are read two K steps (one stage) ahead of the MFMAs that use them, into three register
     // slots, so a read has a whole K step of MFMAs to land before anything waits for it.
     static_assert(KS == 2, "the fragment slots rotate with two K steps per stage");
-    constexpr int RPS = WTM * (A_KC ? 1 : 2) + WTN * (B_KC ? 1 : 2) * (DUAL ? 2 : 1);   // LDS reads per K step
-    constexpr int NM = WTM * WTN * (DUAL ? 2 : 1);                                      // MFMAs per K step
-    constexpr int RPM = (RPS + NM / 2 - 1) / (NM / 2);
+    constexpr int NU = WTM + WTN * (DUAL ? 2 : 1);   // fragments read per K step
+    constexpr int NMI = WTM * WTN;                   // MFMAs per K step (DUAL: pairs)
+    constexpr int NR = NMI >= 4 ? 4 : NMI;           // scheduling regions per K step
+    constexpr int GM = NMI / NR;                     // MFMAs (pairs) per region
+    constexpr int L0 = (L + 1) / 2;                  // loads issued with K step 0
+    static_assert(NMI % NR == 0, "regions hold equal numbers of MFMAs");
     bf16x8 af[3][WTM], bfr[3][WTN], bfr2[3][DUAL ? WTN : 1];
 #define MOE_LOAD(kt_, buf_)                                                                                 \
+  do {                                                                                                      \
+    _Pragma("unroll") for (int q__ = 0; q__ < L; ++q__) MOE_LOAD1(kt_, buf_, q__);                          \
+  } while (0)
+// load q_ (0 .. L-1) of a stage: the A chunks, then the B chunks (DUAL: both weight matrices in turn)
+#define MOE_LOAD1(kt_, buf_, q_)                                                                            \
   do {                                                                                                      \
     const int kq__ = (kt_);                                                                                 \
     const bool sec__ = CHAIN && kq__ >= KT1;                                                                \
     const unsigned kl__ = (unsigned)(sec__ ? kq__ - KT1 : kq__);                                            \
     const unsigned st__ = smem_base + (buf_) + wbase;                                                       \
-    _Pragma("unroll") for (int i = 0; i < StA::CH; ++i)                                                     \
-      load_to_lds16(sec__ ? ra1 : ra, st__ + NT * 16 * i, a_vo[i] + kl__ * astep);                          \
-    _Pragma("unroll") for (int i = 0; i < StB::CH; ++i) {                                                   \
-      load_to_lds16(sec__ ? rb1 : rb, st__ + A_BYTES + NT * 16 * i, b_vo[i] + kl__ * bstep);                \
-      if constexpr (DUAL) load_to_lds16(rb1, st__ + A_BYTES + B_BYTES + NT * 16 * i, b_vo[i] + kl__ * bstep); \
+    if ((q_) < StA::CH) {                                                                                   \
+      load_to_lds16(sec__ ? ra1 : ra, st__ + NT * 16 * (q_), a_vo[(q_) < StA::CH ? (q_) : 0] + kl__ * astep); \
+    } else {                                                                                                \
+      const int c__ = ((q_) - StA::CH) / (DUAL ? 2 : 1) % StB::CH;                                          \
+      if (!DUAL || ((q_) - StA::CH) % 2 == 0)                                                               \
+        load_to_lds16(sec__ ? rb1 : rb, st__ + A_BYTES + NT * 16 * c__, b_vo[c__] + kl__ * bstep);          \
+      else                                                                                                  \
+        load_to_lds16(rb1, st__ + A_BYTES + B_BYTES + NT * 16 * c__, b_vo[c__] + kl__ * bstep);             \
     }                                                                                                       \
   } while (0)
-// fragments of K step ks_ of the stage at buf_ into slot slot_
-#define MOE_FRAGS(slot_, buf_, ks_)                                                                         \
+// read unit u_ (0 .. NU-1) of K step ks_ of the stage at buf_ into slot slot_: the A fragments, then the
+// B fragments (DUAL: then those of the second weight matrix)
+#define MOE_FRAG1(slot_, buf_, ks_, u_)                                                                     \
   do {                                                                                                      \
     const char* st__ = smem + (buf_);                                                                       \
-    _Pragma("unroll") for (int i = 0; i < WTM; ++i) {                                                       \
-      if constexpr (A_KC) af[slot_][i] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + i * WGM * 32 * BKT * 2); \
-      else af[slot_][i] = lds_read_ks2<BM>(st__ + a_fr[i] + (ks_) * 16 * BM * 2);                           \
-    }                                                                                                       \
-    _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                       \
-      if constexpr (B_KC) bfr[slot_][j] = *reinterpret_cast<const bf16x8*>(st__ + b_fr[ks_] + j * 32 * BKT * 2); \
-      else bfr[slot_][j] = lds_read_ks2<BN>(st__ + b_fr[j] + (ks_) * 16 * BN * 2);                          \
-      if constexpr (DUAL) bfr2[slot_][j] = lds_read_ks2<BN>(st__ + B_BYTES + b_fr[j] + (ks_) * 16 * BN * 2); \
+    if ((u_) < WTM) {                                                                                       \
+      const int i__ = (u_) < WTM ? (u_) : 0;                                                                \
+      if constexpr (A_KC) af[slot_][i__] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + i__ * WGM * 32 * BKT * 2); \
+      else af[slot_][i__] = lds_read_ks2<BM>(st__ + a_fr[i__] + (ks_) * 16 * BM * 2);                       \
+    } else if ((u_) < WTM + WTN) {                                                                          \
+      const int j__ = ((u_) - WTM) % WTN;                                                                   \
+      if constexpr (B_KC) bfr[slot_][j__] = *reinterpret_cast<const bf16x8*>(st__ + b_fr[ks_] + j__ * 32 * BKT * 2); \
+      else bfr[slot_][j__] = lds_read_ks2<BN>(st__ + b_fr[j__] + (ks_) * 16 * BN * 2);                      \
+    } else if constexpr (DUAL) {                                                                            \
+      const int j__ = ((u_) - WTM - WTN) % WTN;                                                             \
+      bfr2[slot_][j__] = lds_read_ks2<BN>(st__ + B_BYTES + b_fr[j__] + (ks_) * 16 * BN * 2);                \
     }                                                                                                       \
   } while (0)
-// One K step: the reads for the same K step of the next stage, then the MFMAs of this one.  The
-// scheduling groups ask for that order, with the reads spread over the first half of the MFMAs (RPM
-// per MFMA), so the LDS pipe sees a steady trickle and no read is sunk down to its first use.
-#define MOE_STEP(ks_, cur_, tgt_, DO_NEXT_, NI_)                                                            \
+#define MOE_FRAGS(slot_, buf_, ks_)                                                                         \
   do {                                                                                                      \
-    if (DO_NEXT_) MOE_FRAGS(tgt_, b1, ks_);                                                                 \
-    _Pragma("unroll") for (int i = 0; i < WTM; ++i) if (i < (NI_))                                          \
-      _Pragma("unroll") for (int j = 0; j < WTN; ++j) {                                                     \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i], bfr[cur_][j], acc[i][j], 0, 0, 0); \
-        if constexpr (DUAL)                                                                                 \
-          acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i], bfr2[cur_][j], acc2[i][j], 0, 0, 0); \
+    _Pragma("unroll") for (int u__ = 0; u__ < NU; ++u__) MOE_FRAG1(slot_, buf_, ks_, u__);                  \
+  } while (0)
+// One K step, cut into NR regions that nothing crosses (sched_barrier).  A region holds its share of the
+// MFMAs of this K step, of the fragment reads for the same K step of the next stage, and of the global
+// loads of the stage D ahead (the first half of a stage's loads go with K step 0, the rest with K step 1):
+// LDS reads and, above all, the global->LDS loads then arrive as a steady trickle.  Loads issued in one
+// burst fill the address FIFO of the memory pipe, and a wave that cannot issue a load cannot issue the
+// MFMAs behind it either.
+#define MOE_STEP(ks_, cur_, tgt_, DO_NEXT_, DO_LOAD_, kt_, NI_)                                             \
+  do {                                                                                                      \
+    _Pragma("unroll") for (int r__ = 0; r__ < NR; ++r__) {                                                  \
+      if (DO_NEXT_) {                                                                                       \
+        _Pragma("unroll") for (int u__ = 0; u__ < NU; ++u__)                                                \
+          if (u__ * NR / NU == r__) MOE_FRAG1(tgt_, b1, ks_, u__);                                          \
       }                                                                                                     \
-    if (DO_NEXT_) {                                                                                         \
-      _Pragma("unroll") for (int q = 0; q < NM / 2; ++q) {                                                  \
-        __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);                                                \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                  \
+      _Pragma("unroll") for (int m__ = r__ * GM; m__ < (r__ + 1) * GM; ++m__) {                             \
+        const int i__ = m__ / WTN, j__ = m__ % WTN;                                                         \
+        if (i__ < (NI_)) {                                                                                  \
+          acc[i__][j__] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i__], bfr[cur_][j__], acc[i__][j__], 0, 0, 0); \
+          if constexpr (DUAL)                                                                               \
+            acc2[i__][j__] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i__], bfr2[cur_][j__], acc2[i__][j__], 0, 0, 0); \
+        }                                                                                                   \
       }                                                                                                     \
-      __builtin_amdgcn_sched_group_barrier(0x008, NM - NM / 2, 0);                                          \
+      if (DO_LOAD_) {                                                                                       \
+        constexpr int lo__ = (ks_) == 0 ? 0 : L0, n__ = (ks_) == 0 ? L0 : L - L0;                           \
+        _Pragma("unroll") for (int q__ = 0; q__ < n__; ++q__)                                               \
+          if (q__ * NR / n__ == r__) MOE_LOAD1((kt_) + D, bload, lo__ + q__);                               \
+      }                                                                                                     \
+      __builtin_amdgcn_sched_barrier(0);                                                                    \
     }                                                                                                       \
   } while (0)
 // One iteration; S0_ is the fragment slot of its first K step (the second uses the next slot, the
@@ -431,9 +459,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
 // the run-time conditions.
 #define MOE_ITER(kt_, S0_, DO_LOAD_, DO_NEXT_, NI_)                                                         \
   do {                                                                                                      \
-    if (DO_LOAD_) MOE_LOAD((kt_) + D, bload);                                                               \
-    MOE_STEP(0, (S0_) % 3, ((S0_) + 2) % 3, DO_NEXT_, NI_);                                                 \
-    MOE_STEP(1, ((S0_) + 1) % 3, (S0_) % 3, DO_NEXT_, NI_);                                                 \
+    MOE_STEP(0, (S0_) % 3, ((S0_) + 2) % 3, DO_NEXT_, DO_LOAD_, kt_, NI_);                                  \
+    MOE_STEP(1, ((S0_) + 1) % 3, (S0_) % 3, DO_NEXT_, DO_LOAD_, kt_, NI_);                                  \
     if (DO_LOAD_) __builtin_amdgcn_s_waitcnt(WAIT_L); else __builtin_amdgcn_s_waitcnt(WAIT_0);              \
     asm volatile("" ::: "memory");                                                                          \
     __builtin_amdgcn_s_barrier();                                                                           \
@@ -484,6 +511,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
 #undef MOE_MAINLOOP
     }
 #undef MOE_LOAD
+#undef MOE_LOAD1
+#undef MOE_FRAG1
 #undef MOE_FRAGS
 #undef MOE_STEP
 #undef MOE_ITER
