@@ -66,3 +66,20 @@ def test_shares_of_a_group_add_up(name):
     for n, r in (("out", "out"), ("dx", "dx"), ("dW1", "dW1"), ("dW2", "dW2"), ("dWr", "dWr"),
                  ("d_logits", "dlogits"), ("d_topk_w", "dw")):
         U.assert_close(f"sum of shares: {n}", total[n], full[r], tol)
+
+
+def test_profiled_expert_times_drive_the_planner():
+    """The paper's profiler step with the library's own kernels: time an expert module at the batch a GPU
+    sees, feed Algorithm 1.  Expert time must grow with the tokens received, not with the experts held
+    (Section 4.2), which is what lets T_squeeze be written per expert."""
+    from paper_2504_03871_amd import profiler
+    d, f, n, tokens = 512, 1024, 8, 16384
+    t_all = profiler.expert_module_time_ms(tokens, d, f, n_experts=n)            # a layer's experts, all tokens
+    t_half_experts = profiler.expert_module_time_ms(tokens, d, f, n_experts=n // 2)
+    t_one = profiler.expert_module_time_ms(tokens // n, d, f, n_experts=1)       # one expert's share
+    assert t_all > 0 and t_one > 0
+    assert abs(t_all - t_half_experts) / t_all < 0.25, (t_all, t_half_experts)   # same tokens, half the experts
+    # an attention GPU (this GPU) against an expert GPU assumed a third slower, attention time made up
+    plan = B.moe_asymea_plan(n, 12, 1, 1, 0.9 * t_all, t_one, 4.0 / 3.0 * t_all)
+    assert len(plan) == 12 and all(0 <= o <= n for o in plan) and sum(plan) > 0
+    print(f"\nT_E {t_all:.3f} ms, one expert {t_one:.3f} ms, plan {plan}", flush=True)
