@@ -325,9 +325,9 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
     }
   }
   ProfScope ps(MOE_PROF_DX_BWD, s);
-  if (pair_x) return launch_gemm_bf16_pair(EPI_STORE, swiglu, gx, max_tiles, gw1, s);
-  if (bf && !swiglu && split_k_applies(cfg->E, f))   // a launch of its own: its smallest row tiles use split-K
+  if (bf && !swiglu && split_k_applies(cfg->E, f))   // the smallest row tiles of the GELU dx use split-K (gemm.h)
     gx.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ffn_split);
+  if (pair_x) return launch_gemm_bf16_pair(EPI_STORE, swiglu, gx, max_tiles, gw1, s);
   return launch_gemm(cfg, MODE_NT, EPI_STORE, false, swiglu, gx, max_tiles, s);
 }
 

@@ -53,12 +53,18 @@ static int launch_pair(const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hi
   }
   // the first GEMM's block count is a multiple of the XCD count, so that a tile number still tells the
   // XCD its block runs on for the second one (numbers past the last tile return at once)
-  const long long n1 = ((long long)((g1.N + T_BN - 1) / T_BN) * max_tiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+  // (a plain-store first GEMM may split its smallest row tiles along K: SPLIT_K blocks per column tile, see gemm.h)
+  const int ntn1 = (g1.N + T_BN - 1) / T_BN;
+  const bool split = EPI1 == EPI_STORE && !CHAIN1 && g1.split_ws != nullptr;
+  const long long t1 = (long long)ntn1 * max_tiles + (split ? (long long)g1.E * ntn1 * (SPLIT_K - 1) : 0);
+  const long long n1 = (t1 + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
   const long long p2 = (long long)((g2.N + T_BN - 1) / T_BN) * ((g2.M + T_BM - 1) / T_BM);
   const long long n2 = (p2 + NUM_XCD - 1) / NUM_XCD * NUM_XCD * g2.E;
   if (n1 + n2 > 0x7fffffffll) return MOE_ERR_BAD_SHAPE;
   kern<<<dim3(gemm_bf16_grid(n1 + n2)), T_WGM * T_WGN * 64, lds, s>>>(g1, g2, (int)n1);
-  return launch_status();
+  const int rc = launch_status();
+  if (rc != MOE_OK || !split) return rc;
+  return launch_split_reduce(g1, s);
 }
 
 int launch_gemm_bf16_pair(int epi1, bool chain1, const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s) {
