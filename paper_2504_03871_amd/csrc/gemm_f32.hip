@@ -104,7 +104,8 @@ int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* 
 }
 
 constexpr int SB = 64;   // tile edge
-constexpr int SK = 16;   // k step
+constexpr int SK = 32;   // k step
+constexpr int EPT = SB * SK / 256;   // operand elements a thread moves per k step
 
 // NN/NT: grid = (ceil(N/SB), max row tiles).  TN: grid = (ceil(N/SB), ceil(M/SB), E).
 template <int MODE, int EPI, bool DUAL, bool CHAIN>
@@ -134,59 +135,73 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
   }
   const int nvalid = min(SB, g.N - n0);
   float acc[4][4] = {}, acc2[DUAL ? 4 : 1][4] = {};
-  for (int pass = 0; pass < (CHAIN ? 2 : 1); ++pass) {
+  // The global loads of K step k0 + SK are issued before the arithmetic of step k0 (registers va/vb), so
+  // their latency hides behind it; a chained GEMM runs its two operand pairs back to back.
+  const int nsteps = (klen + SK - 1) / SK, total = nsteps * (CHAIN ? 2 : 1);
+  float va[EPT], vb[EPT], vb2[DUAL ? EPT : 1];
+  auto fetch = [&](int step) {
+    const int pass = step / max(nsteps, 1), k0 = (step - pass * nsteps) * SK;
     const float* A = reinterpret_cast<const float*>(pass == 0 ? g.A : g.A2);
     const float* B = reinterpret_cast<const float*>(pass == 0 ? g.B : g.B2);
     const float* B2 = reinterpret_cast<const float*>(g.B2);
-    for (int k0 = 0; k0 < klen; k0 += SK) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int id = tid + 256 * i;
-        {  // A element (m, kk)
-          int m, kk;
-          if constexpr (MODE == MODE_TN) { m = id % SB; kk = id / SB; } else { m = id / SK; kk = id % SK; }
-          float v = 0.f;
-          if (m < mvalid && k0 + kk < klen) {
-            if constexpr (MODE == MODE_TN) v = A[(size_t)(row0 + k0 + kk) * g.M + m0 + m];
-            else v = A[(size_t)(row0 + m) * g.K + k0 + kk];
-          }
-          As[kk][m] = v;
+    for (int i = 0; i < EPT; ++i) {
+      const int id = tid + 256 * i;
+      {  // A element (m, kk)
+        int m, kk;
+        if constexpr (MODE == MODE_TN) { m = id % SB; kk = id / SB; } else { m = id / SK; kk = id % SK; }
+        float v = 0.f;
+        if (m < mvalid && k0 + kk < klen) {
+          if constexpr (MODE == MODE_TN) v = A[(size_t)(row0 + k0 + kk) * g.M + m0 + m];
+          else v = A[(size_t)(row0 + m) * g.K + k0 + kk];
         }
-        {  // B element (kk, n)
-          int n, kk;
-          if constexpr (MODE == MODE_NT) { n = id / SK; kk = id % SK; } else { n = id % SB; kk = id / SB; }
-          float v = 0.f, v2 = 0.f;
-          if (n < nvalid && k0 + kk < klen) {
-            size_t off;
-            if constexpr (MODE == MODE_TN) off = (size_t)(row0 + k0 + kk) * g.N + n0 + n;
-            else if constexpr (MODE == MODE_NN) off = ((size_t)e * g.K + k0 + kk) * g.N + n0 + n;
-            else off = ((size_t)e * g.N + n0 + n) * g.K + k0 + kk;
-            v = B[off];
-            if constexpr (DUAL) v2 = B2[off];
-          }
-          Bs[kk][n] = v;
-          if constexpr (DUAL) Bs2[kk][n] = v2;
-        }
+        va[i] = v;
       }
-      __syncthreads();
+      {  // B element (kk, n)
+        int n, kk;
+        if constexpr (MODE == MODE_NT) { n = id / SK; kk = id % SK; } else { n = id % SB; kk = id / SB; }
+        float v = 0.f, v2 = 0.f;
+        if (n < nvalid && k0 + kk < klen) {
+          size_t off;
+          if constexpr (MODE == MODE_TN) off = (size_t)(row0 + k0 + kk) * g.N + n0 + n;
+          else if constexpr (MODE == MODE_NN) off = ((size_t)e * g.K + k0 + kk) * g.N + n0 + n;
+          else off = ((size_t)e * g.N + n0 + n) * g.K + k0 + kk;
+          v = B[off];
+          if constexpr (DUAL) v2 = B2[off];
+        }
+        vb[i] = v;
+        if constexpr (DUAL) vb2[i] = v2;
+      }
+    }
+  };
+  if (total > 0) fetch(0);
+  for (int step = 0; step < total; ++step) {
 #pragma unroll
-      for (int kk = 0; kk < SK; ++kk) {
-        float a[4], b[4];
+    for (int i = 0; i < EPT; ++i) {
+      const int id = tid + 256 * i;
+      if constexpr (MODE == MODE_TN) As[id / SB][id % SB] = va[i]; else As[id % SK][id / SK] = va[i];
+      if constexpr (MODE == MODE_NT) Bs[id % SK][id / SK] = vb[i]; else Bs[id / SB][id % SB] = vb[i];
+      if constexpr (DUAL) { if constexpr (MODE == MODE_NT) Bs2[id % SK][id / SK] = vb2[i]; else Bs2[id / SB][id % SB] = vb2[i]; }
+    }
+    __syncthreads();
+    if (step + 1 < total) fetch(step + 1);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+    for (int kk = 0; kk < SK; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+      if constexpr (DUAL) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
-        if constexpr (DUAL) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc2[i][j] = fmaf(a[i], Bs2[kk][tx * 4 + j], acc2[i][j]);
-        }
+          for (int j = 0; j < 4; ++j) acc2[i][j] = fmaf(a[i], Bs2[kk][tx * 4 + j], acc2[i][j]);
       }
-      __syncthreads();
     }
+    __syncthreads();
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i)
