@@ -32,7 +32,13 @@
  *     inverted range is empty.  Rows of permuted buffers outside the shares are never read for a
  *     result and never written.
  *   - Shapes: 1 <= k <= min(E, MOE_MAX_K), E <= MOE_MAX_E, T >= 0 (T = 0 is a no-op),
- *     T*k <= 2^30.  bf16: d_model and d_ff multiples of 64; fp32: multiples of 4.
+ *     T*k <= 2^30.  bf16: d_model and d_ff multiples of 64; fp32: multiples of 4.  The kernels address
+ *     one operand through 32-bit byte offsets, so T*k * max(d_model, d_ff) * (bytes per element) and
+ *     d_model * d_ff * 4 must both stay below 2^32 (MOE_ERR_BAD_SHAPE otherwise).
+ *   - `ws` is the caller's device workspace and `ws_bytes` its size; a call that uses it returns
+ *     MOE_ERR_WORKSPACE, before launching anything, when ws_bytes < moe_workspace_bytes(cfg).
+ *   - An expert id in topk_idx outside [0, E) is treated as a dropped assignment (row_of = -1, not
+ *     counted, contributes nothing); it never indexes memory.
  *   - Calls that use the same workspace or output buffers must not overlap in time.
  */
 #ifndef MOE_H_
@@ -60,8 +66,37 @@ enum {
   MOE_ERR_BAD_DTYPE = -3, /* dtype or act not one of the enumerators */
   MOE_ERR_BAD_SLICE = -4, /* exactly one of slice_lo / slice_hi is NULL */
   MOE_ERR_ALIGN = -5,     /* a device pointer is not 16-byte aligned */
-  MOE_ERR_HIP = -6        /* a launch failed; see moe_last_hip_error() */
+  MOE_ERR_HIP = -6,       /* a launch failed; see moe_last_hip_error() */
+  MOE_ERR_WORKSPACE = -7  /* ws_bytes is smaller than moe_workspace_bytes(cfg) */
 };
+
+/*
+ * Benchmark aid, not a step of the layer: timing brackets owned by the CALLER.  A moe_cfg whose `prof`
+ * points at one of these makes every launch of kernel `which` with n[which] > 0 record
+ * hipEventRecord(start[which][i]) / hipEventRecord(stop[which][i]) on the launch's stream around it,
+ * i = count[which]++ modulo n[which].  start/stop hold hipEvent_t handles created by the caller; the
+ * struct and the arrays are HOST memory that must stay valid during the call.  The library keeps no
+ * pointer to it after the call returns.  Do not use under graph capture.
+ */
+enum {
+  MOE_PROF_GEMM1_FWD = 0,   /* x_perm W1 (+ activation) */
+  MOE_PROF_GEMM2_FWD = 1,   /* H W2 */
+  MOE_PROF_DH_BWD = 2,      /* dy W2^T (+ activation derivative); bf16 with few tiles: the same launch also does H^T dy */
+  MOE_PROF_DW2_BWD = 3,     /* H^T dy, when it has a launch of its own */
+  MOE_PROF_DW1_BWD = 4,     /* x_perm^T dA (SwiGLU: both weight gradients), those with a launch of their own */
+  MOE_PROF_DX_BWD = 5,      /* dA W1^T; bf16 with few tiles: the same launch also does x_perm^T dA */
+  MOE_PROF_GATHER = 6,      /* row gather of moe_dispatch */
+  MOE_PROF_COMBINE = 7,     /* moe_combine kernel */
+  MOE_PROF_COMBINE_BWD = 8, /* moe_combine_bwd kernel */
+  MOE_PROF_ROUTE = 9,       /* moe_route kernel */
+  MOE_PROF_COUNT = 10
+};
+typedef struct moe_prof {
+  void** start[MOE_PROF_COUNT];
+  void** stop[MOE_PROF_COUNT];
+  int32_t n[MOE_PROF_COUNT];
+  int64_t count[MOE_PROF_COUNT];
+} moe_prof;
 
 typedef struct moe_cfg {
   int32_t T;        /* tokens */
@@ -72,6 +107,7 @@ typedef struct moe_cfg {
   int32_t dtype;    /* MOE_DTYPE_* : storage type of activations and expert weights */
   int32_t act;      /* MOE_ACT_GELU: gelu_erf(x W1) W2 ; MOE_ACT_SWIGLU: (silu(x W1) * (x W1b)) W2 */
   int32_t capacity; /* rows kept per expert; <= 0 = unlimited */
+  moe_prof* prof;   /* HOST pointer to caller-owned timing brackets, or NULL (the normal case) */
 } moe_cfg;
 
 /* Static text for a return code (never NULL). */
@@ -97,7 +133,7 @@ MOE_API int moe_saved_bytes(const moe_cfg* cfg, size_t* bytes);
  */
 MOE_API int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* bias,
               const float* logits_in, float* logits_out, int32_t* topk_idx, float* topk_w,
-              void* ws, void* stream);
+              void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Dispatch (Section 2.1: token embeddings go to their experts; locally a stable group-by-expert).
@@ -109,7 +145,7 @@ MOE_API int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const 
 MOE_API int moe_dispatch(const moe_cfg* cfg, const void* x, const int32_t* topk_idx,
                  const int32_t* slice_lo, const int32_t* slice_hi,
                  int32_t* counts, int32_t* kept, int32_t* offsets, int32_t* row_of, int32_t* src_of,
-                 void* x_perm, void* ws, void* stream);
+                 void* x_perm, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Expert FFN forward on the in-share rows (Section 2.1: experts are FFNs made of GEMMs).
@@ -120,7 +156,7 @@ MOE_API int moe_dispatch(const moe_cfg* cfg, const void* x, const int32_t* topk_
 MOE_API int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b,
                        const void* W2, const int32_t* offsets, const int32_t* kept,
                        const int32_t* slice_lo, const int32_t* slice_hi,
-                       void* saved, void* y_perm, void* ws, void* stream);
+                       void* saved, void* y_perm, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Activation checkpointing (the paper trains with it, Section 6.1): the first half of
@@ -134,7 +170,7 @@ MOE_API int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const voi
  */
 MOE_API int moe_expert_ffn_recompute(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b,
                              const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo,
-                             const int32_t* slice_hi, void* saved, void* ws, void* stream);
+                             const int32_t* slice_hi, void* saved, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Combine (Section 2.1: outputs weighted by the scores and summed).
@@ -173,7 +209,7 @@ MOE_API int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const vo
                        const int32_t* offsets, const int32_t* kept,
                        const int32_t* slice_lo, const int32_t* slice_hi,
                        void* dx_perm, float* dW1, float* dW1b, float* dW2, int32_t accumulate,
-                       void* ws, void* stream);
+                       void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Gate backward (Section 5: the branch through the confidence scores to the gate weights and to
@@ -187,7 +223,7 @@ MOE_API int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const vo
  */
 MOE_API int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx,
                   const float* topk_w, const float* d_topk_w,
-                  float* d_logits, float* dWr, void* dx, int32_t accumulate, void* ws, void* stream);
+                  float* d_logits, float* dWr, void* dx, int32_t accumulate, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Planner of the asymmetric expert assignment (Section 4.2 of the paper, Algorithm 1 and the paragraph
@@ -229,25 +265,12 @@ MOE_API int moe_asymea_shares(int32_t n, int32_t M, int32_t N, int32_t o_l, int3
                       int32_t* slice_lo, int32_t* slice_hi);
 
 /*
- * Benchmark aid, not a step of the layer: while armed, every launch of kernel `which` made by this
- * host thread is bracketed by hipEventRecord(start_events[i]) / hipEventRecord(stop_events[i]) on the
- * launch's stream, i = launch count modulo n.  The arrays hold n hipEvent_t handles created by the
- * caller (host memory, must stay valid while armed).  n = 0 disarms.  Do not arm under graph capture.
+ * Benchmark aid, not a step of the layer: a plain streaming kernel of this library over `bytes` bytes
+ * (a multiple of 16; dst and src are device pointers, 16-byte aligned).  mode 0: dst = src (the copy
+ * rate is the practical ceiling of the HBM-bound kernels on a given box); mode 1: dst is filled with
+ * zeros and src is ignored (used between timed iterations to push earlier data out of the caches).
  */
-enum {
-  MOE_PROF_GEMM1_FWD = 0,   /* x_perm W1 (+ activation) */
-  MOE_PROF_GEMM2_FWD = 1,   /* H W2 */
-  MOE_PROF_DH_BWD = 2,      /* dy W2^T (+ activation derivative); bf16 with few tiles: the same launch also does H^T dy */
-  MOE_PROF_DW2_BWD = 3,     /* H^T dy, when it has a launch of its own */
-  MOE_PROF_DW1_BWD = 4,     /* x_perm^T dA (SwiGLU: both weight gradients), those with a launch of their own */
-  MOE_PROF_DX_BWD = 5,      /* dA W1^T; bf16 with few tiles: the same launch also does x_perm^T dA */
-  MOE_PROF_GATHER = 6,      /* row gather of moe_dispatch */
-  MOE_PROF_COMBINE = 7,     /* moe_combine kernel */
-  MOE_PROF_COMBINE_BWD = 8, /* moe_combine_bwd kernel */
-  MOE_PROF_ROUTE = 9,       /* moe_route kernel */
-  MOE_PROF_COUNT = 10
-};
-MOE_API int moe_profile_kernel(int which, void** start_events, void** stop_events, int n);
+MOE_API int moe_bench_stream(void* dst, const void* src, size_t bytes, int32_t mode, void* stream);
 
 #ifdef __cplusplus
 }

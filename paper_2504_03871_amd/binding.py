@@ -19,14 +19,24 @@ MAX_E, MAX_K = 256, 8
 
 SYMBOLS = ("moe_error_string", "moe_last_hip_error", "moe_workspace_bytes", "moe_saved_bytes", "moe_route",
            "moe_dispatch", "moe_expert_ffn_fwd", "moe_expert_ffn_recompute", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
-           "moe_route_bwd", "moe_asymea_plan", "moe_asymea_shares", "moe_profile_kernel")
+           "moe_route_bwd", "moe_asymea_plan", "moe_asymea_shares", "moe_bench_stream")
 
 PROF = {"gemm1_fwd": 0, "gemm2_fwd": 1, "dh_bwd": 2, "dw2_bwd": 3, "dw1_bwd": 4, "dx_bwd": 5, "gather": 6,
         "combine": 7, "combine_bwd": 8, "route": 9}
 
 
+PROF_COUNT = 10
+
+
+class MoeProf(ctypes.Structure):
+    """Caller-owned timing brackets (moe_prof): per kernel, arrays of hipEvent_t handles and a launch counter."""
+    _fields_ = [("start", ctypes.POINTER(ctypes.c_void_p) * PROF_COUNT), ("stop", ctypes.POINTER(ctypes.c_void_p) * PROF_COUNT),
+                ("n", ctypes.c_int32 * PROF_COUNT), ("count", ctypes.c_int64 * PROF_COUNT)]
+
+
 class MoeCfg(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d_model", "d_ff", "E", "k", "dtype", "act", "capacity")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d_model", "d_ff", "E", "k", "dtype", "act", "capacity")] + \
+               [("prof", ctypes.POINTER(MoeProf))]
 
 
 class MoeError(RuntimeError):
@@ -48,23 +58,22 @@ def lib():
         l.moe_error_string.restype = ctypes.c_char_p
         l.moe_error_string.argtypes = [ctypes.c_int]
         l.moe_last_hip_error.restype = ctypes.c_int
-        p, i32 = ctypes.c_void_p, ctypes.c_int32
+        p, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         cfgp = ctypes.POINTER(MoeCfg)
         sig = {
             "moe_workspace_bytes": [cfgp, ctypes.POINTER(ctypes.c_size_t)],
             "moe_saved_bytes": [cfgp, ctypes.POINTER(ctypes.c_size_t)],
-            "moe_route": [cfgp] + [p] * 8,
-            "moe_dispatch": [cfgp] + [p] * 12,
-            "moe_expert_ffn_fwd": [cfgp] + [p] * 12,
-            "moe_expert_ffn_recompute": [cfgp] + [p] * 10,
+            "moe_route": [cfgp] + [p] * 8 + [sz, p],
+            "moe_dispatch": [cfgp] + [p] * 11 + [sz, p],
+            "moe_expert_ffn_fwd": [cfgp] + [p] * 11 + [sz, p],
+            "moe_expert_ffn_recompute": [cfgp] + [p] * 9 + [sz, p],
             "moe_combine": [cfgp] + [p] * 9 + [i32, p],
             "moe_combine_bwd": [cfgp] + [p] * 12,
-            "moe_expert_ffn_bwd": [cfgp] + [p] * 14 + [i32, p, p],
-            "moe_route_bwd": [cfgp] + [p] * 8 + [i32, p, p],
+            "moe_expert_ffn_bwd": [cfgp] + [p] * 14 + [i32, p, sz, p],
+            "moe_route_bwd": [cfgp] + [p] * 8 + [i32, p, sz, p],
             "moe_asymea_plan": [i32] * 4 + [ctypes.c_double] * 3 + [i32, i32, ctypes.POINTER(i32)],
             "moe_asymea_shares": [i32] * 6 + [ctypes.POINTER(i32), ctypes.POINTER(i32)],
-            "moe_profile_kernel": [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
-                                   ctypes.c_int],
+            "moe_bench_stream": [p, p, sz, i32, p],
         }
         for name, args in sig.items():
             fn = getattr(l, name)
@@ -86,6 +95,15 @@ def _ptr(t):
     if not t.is_contiguous():
         raise ValueError("tensor must be contiguous")
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _nbytes(t):
+    """Size of a workspace argument: a tensor's byte count; 0 for None; for a raw address the caller vouches."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return (1 << 62)
+    return t.numel() * t.element_size()
 
 
 def _stream():
@@ -111,30 +129,37 @@ def moe_saved_bytes(cfg) -> int:
     return n.value
 
 
-def moe_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, ws=None, stream=None):
+def moe_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, ws=None, stream=None, ws_bytes=None):
     _check("moe_route", lib().moe_route(ctypes.byref(cfg), _ptr(x), _ptr(Wr), _ptr(bias), _ptr(logits_in),
                                         _ptr(logits_out), _ptr(topk_idx), _ptr(topk_w), _ptr(ws),
+                                        _nbytes(ws) if ws_bytes is None else ws_bytes,
                                         _stream() if stream is None else stream))
 
 
 def moe_dispatch(cfg, x, topk_idx, slice_lo, slice_hi, counts, kept, offsets, row_of, src_of, x_perm, ws,
-                 stream=None):
+                 stream=None, ws_bytes=None):
     _check("moe_dispatch", lib().moe_dispatch(ctypes.byref(cfg), _ptr(x), _ptr(topk_idx), _ptr(slice_lo),
                                               _ptr(slice_hi), _ptr(counts), _ptr(kept), _ptr(offsets), _ptr(row_of),
-                                              _ptr(src_of), _ptr(x_perm), _ptr(ws), _stream() if stream is None else stream))
+                                              _ptr(src_of), _ptr(x_perm), _ptr(ws),
+                                              _nbytes(ws) if ws_bytes is None else ws_bytes,
+                                              _stream() if stream is None else stream))
 
 
-def moe_expert_ffn_fwd(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, saved, y_perm, ws, stream=None):
+def moe_expert_ffn_fwd(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, saved, y_perm, ws, stream=None,
+                       ws_bytes=None):
     _check("moe_expert_ffn_fwd", lib().moe_expert_ffn_fwd(ctypes.byref(cfg), _ptr(x_perm), _ptr(W1), _ptr(W1b),
                                                           _ptr(W2), _ptr(offsets), _ptr(kept), _ptr(slice_lo),
                                                           _ptr(slice_hi), _ptr(saved), _ptr(y_perm), _ptr(ws),
+                                                          _nbytes(ws) if ws_bytes is None else ws_bytes,
                                                           _stream() if stream is None else stream))
 
 
-def moe_expert_ffn_recompute(cfg, x_perm, W1, W1b, offsets, kept, slice_lo, slice_hi, saved, ws, stream=None):
+def moe_expert_ffn_recompute(cfg, x_perm, W1, W1b, offsets, kept, slice_lo, slice_hi, saved, ws, stream=None,
+                             ws_bytes=None):
     _check("moe_expert_ffn_recompute", lib().moe_expert_ffn_recompute(
         ctypes.byref(cfg), _ptr(x_perm), _ptr(W1), _ptr(W1b), _ptr(offsets), _ptr(kept), _ptr(slice_lo),
-        _ptr(slice_hi), _ptr(saved), _ptr(ws), _stream() if stream is None else stream))
+        _ptr(slice_hi), _ptr(saved), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+        _stream() if stream is None else stream))
 
 
 def moe_combine(cfg, y_perm, topk_w, topk_idx, row_of, offsets, kept, slice_lo, slice_hi, out, accumulate=0,
@@ -153,17 +178,20 @@ def moe_combine_bwd(cfg, d_out, y_perm, topk_w, topk_idx, row_of, offsets, kept,
 
 
 def moe_expert_ffn_bwd(cfg, dy_perm, x_perm, saved, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, dx_perm, dW1,
-                       dW1b, dW2, accumulate, ws, stream=None):
+                       dW1b, dW2, accumulate, ws, stream=None, ws_bytes=None):
     _check("moe_expert_ffn_bwd", lib().moe_expert_ffn_bwd(ctypes.byref(cfg), _ptr(dy_perm), _ptr(x_perm), _ptr(saved),
                                                           _ptr(W1), _ptr(W1b), _ptr(W2), _ptr(offsets), _ptr(kept),
                                                           _ptr(slice_lo), _ptr(slice_hi), _ptr(dx_perm), _ptr(dW1),
                                                           _ptr(dW1b), _ptr(dW2), int(accumulate), _ptr(ws),
+                                                          _nbytes(ws) if ws_bytes is None else ws_bytes,
                                                           _stream() if stream is None else stream))
 
 
-def moe_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, ws, accumulate=0, stream=None):
+def moe_route_bwd(cfg, x, Wr, topk_idx, topk_w, d_topk_w, d_logits, dWr, dx, ws, accumulate=0, stream=None,
+                  ws_bytes=None):
     _check("moe_route_bwd", lib().moe_route_bwd(ctypes.byref(cfg), _ptr(x), _ptr(Wr), _ptr(topk_idx), _ptr(topk_w),
                                                 _ptr(d_topk_w), _ptr(d_logits), _ptr(dWr), _ptr(dx), int(accumulate), _ptr(ws),
+                                                _nbytes(ws) if ws_bytes is None else ws_bytes,
                                                 _stream() if stream is None else stream))
 
 
@@ -183,6 +211,7 @@ def moe_asymea_shares(n, M, N, o_l, role, rank):
     return list(lo)[:int(n)], list(hi)[:int(n)]
 
 
-def moe_profile_kernel(which, start_events, stop_events, n):
-    """Arm (n > 0) or disarm (n = 0) HIP-event brackets around kernel `which`; arrays of hipEvent_t handles."""
-    _check("moe_profile_kernel", lib().moe_profile_kernel(int(which), start_events, stop_events, int(n)))
+def moe_bench_stream(dst, src, nbytes, mode=0, stream=None):
+    """Benchmark aid: the library's streaming copy (mode 0) or zero fill (mode 1) over nbytes bytes."""
+    _check("moe_bench_stream", lib().moe_bench_stream(_ptr(dst), _ptr(src), int(nbytes), int(mode),
+                                                      _stream() if stream is None else stream))

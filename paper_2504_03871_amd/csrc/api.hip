@@ -12,11 +12,6 @@ int set_hip_error(hipError_t e) {
   return MOE_ERR_HIP;
 }
 
-ProfSlot& prof_slot(int which) {
-  static thread_local ProfSlot slots[MOE_PROF_COUNT];
-  return slots[which];
-}
-
 int check_cfg(const moe_cfg* c) {
   if (c == nullptr) return MOE_ERR_NULL;
   if (c->dtype != MOE_DTYPE_F32 && c->dtype != MOE_DTYPE_BF16) return MOE_ERR_BAD_DTYPE;
@@ -27,6 +22,7 @@ int check_cfg(const moe_cfg* c) {
   const int mult = (c->dtype == MOE_DTYPE_BF16) ? 64 : 4;
   if (c->d_model % mult != 0 || c->d_ff % mult != 0) return MOE_ERR_BAD_SHAPE;
   if ((long long)c->T * c->k > (1ll << 30)) return MOE_ERR_BAD_SHAPE;
+  if (!offsets_fit_32_bits(c->T, c->k, c->d_model, c->d_ff, (int)elt_size(c))) return MOE_ERR_BAD_SHAPE;
   return MOE_OK;
 }
 
@@ -35,7 +31,7 @@ WsLayout ws_layout(const moe_cfg* c) {
   const size_t A = (size_t)c->T * c->k;
   size_t off = 0;
   w.dispatch_blk_cnt = off;
-  off += align_up(((A + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK) * (size_t)c->E * 4, 256);
+  off += align_up(((A + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK + 1) * (size_t)c->E * 4, 256);   // + a row of totals
   w.tile_map = off;
   off += align_up(tile_map_bytes(max_row_tiles((int)A, c->E, TILE_ROWS_MIN), c->E), 256);
   w.route_partials = off;
@@ -72,6 +68,28 @@ __global__ void fill_zero_kernel(float* p, int n) {
   if (i < n) p[i] = 0.f;
 }
 
+// Streaming copy / fill for the benchmark: 16-byte vectors, four per thread in flight, grid-stride.
+typedef unsigned bs_u32x4 __attribute__((ext_vector_type(4)));
+template <bool FILL>
+__global__ __launch_bounds__(256) void bench_stream_kernel(bs_u32x4* __restrict__ dst, const bs_u32x4* __restrict__ src, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256 * 4;
+  for (size_t i = (size_t)blockIdx.x * 256 * 4 + threadIdx.x; i < n16; i += stride) {
+    bs_u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      v[u] = bs_u32x4{0u, 0u, 0u, 0u};
+      if (!FILL && i + u * 256 < n16) v[u] = __builtin_nontemporal_load(src + i + u * 256);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i + u * 256 < n16) __builtin_nontemporal_store(v[u], dst + i + u * 256);
+  }
+}
+
+static int check_ws(const moe_cfg* c, const void* ws, size_t ws_bytes) {
+  return (ws != nullptr && ws_bytes < ws_layout(c).total) ? MOE_ERR_WORKSPACE : MOE_OK;
+}
+
 static int check_slices(const int32_t* lo, const int32_t* hi) {
   return ((lo == nullptr) != (hi == nullptr)) ? MOE_ERR_BAD_SLICE : MOE_OK;
 }
@@ -102,21 +120,26 @@ const char* moe_error_string(int code) {
     case MOE_ERR_BAD_SLICE: return "slice_lo and slice_hi must both be given or both be NULL";
     case MOE_ERR_ALIGN: return "device pointer not 16-byte aligned";
     case MOE_ERR_HIP: return "HIP launch failed (see moe_last_hip_error)";
+    case MOE_ERR_WORKSPACE: return "workspace smaller than moe_workspace_bytes(cfg)";
     default: return "unknown error code";
   }
 }
 
 int moe_last_hip_error(void) { return g_last_hip_error; }
 
-int moe_profile_kernel(int which, void** start_events, void** stop_events, int n) {
-  if (which < 0 || which >= MOE_PROF_COUNT || n < 0) return MOE_ERR_BAD_SHAPE;
-  if (n > 0 && (start_events == nullptr || stop_events == nullptr)) return MOE_ERR_NULL;
-  ProfSlot& p = prof_slot(which);
-  p.start = start_events;
-  p.stop = stop_events;
-  p.n = n;
-  p.count = 0;
-  return MOE_OK;
+int moe_bench_stream(void* dst, const void* src, size_t bytes, int32_t mode, void* stream) {
+  REQUIRE(dst);
+  if (mode != 0 && mode != 1) return MOE_ERR_BAD_DTYPE;
+  if (mode == 0) REQUIRE(src);
+  ALIGNED(dst); ALIGNED(src);
+  if (bytes % 16 != 0) return MOE_ERR_BAD_SHAPE;
+  if (bytes == 0) return MOE_OK;
+  const size_t n16 = bytes / 16;
+  const size_t want = (n16 + 1023) / 1024;
+  const unsigned grid = (unsigned)(want < 256 * 16 ? want : 256 * 16);
+  if (mode == 0) bench_stream_kernel<false><<<grid, 256, 0, (hipStream_t)stream>>>((bs_u32x4*)dst, (const bs_u32x4*)src, n16);
+  else bench_stream_kernel<true><<<grid, 256, 0, (hipStream_t)stream>>>((bs_u32x4*)dst, nullptr, n16);
+  return launch_status();
 }
 
 int moe_workspace_bytes(const moe_cfg* cfg, size_t* bytes) {
@@ -134,7 +157,7 @@ int moe_saved_bytes(const moe_cfg* cfg, size_t* bytes) {
 }
 
 int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* bias, const float* logits_in,
-              float* logits_out, int32_t* topk_idx, float* topk_w, void* ws, void* stream) {
+              float* logits_out, int32_t* topk_idx, float* topk_w, void* ws, size_t ws_bytes, void* stream) {
   CHECK(check_cfg(cfg));
   if (logits_in == nullptr) { REQUIRE(x); REQUIRE(Wr); REQUIRE(logits_out); }
   if (logits_in == nullptr && cfg->dtype == MOE_DTYPE_BF16) REQUIRE(ws);
@@ -142,21 +165,23 @@ int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* b
   REQUIRE(topk_w);
   ALIGNED(x); ALIGNED(Wr); ALIGNED(bias); ALIGNED(logits_in); ALIGNED(logits_out); ALIGNED(topk_idx); ALIGNED(topk_w);
   ALIGNED(ws);
+  CHECK(check_ws(cfg, ws, ws_bytes));
   if (cfg->T == 0) return MOE_OK;
   void* wfrag = ws != nullptr ? static_cast<char*>(ws) + ws_layout(cfg).route_wrt : nullptr;
-  ProfScope ps(MOE_PROF_ROUTE, (hipStream_t)stream);
+  ProfScope ps(cfg, MOE_PROF_ROUTE, (hipStream_t)stream);
   return launch_route(cfg, x, Wr, bias, logits_in, logits_out, topk_idx, topk_w, wfrag, (hipStream_t)stream);
 }
 
 int moe_dispatch(const moe_cfg* cfg, const void* x, const int32_t* topk_idx, const int32_t* slice_lo,
                  const int32_t* slice_hi, int32_t* counts, int32_t* kept, int32_t* offsets, int32_t* row_of,
-                 int32_t* src_of, void* x_perm, void* ws, void* stream) {
+                 int32_t* src_of, void* x_perm, void* ws, size_t ws_bytes, void* stream) {
   CHECK(check_cfg(cfg));
   CHECK(check_slices(slice_lo, slice_hi));
   REQUIRE(topk_idx); REQUIRE(counts); REQUIRE(kept); REQUIRE(offsets); REQUIRE(row_of); REQUIRE(src_of); REQUIRE(ws);
   if (x_perm != nullptr) REQUIRE(x);
   ALIGNED(x); ALIGNED(topk_idx); ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(counts); ALIGNED(kept);
   ALIGNED(offsets); ALIGNED(row_of); ALIGNED(src_of); ALIGNED(x_perm); ALIGNED(ws);
+  CHECK(check_ws(cfg, ws, ws_bytes));
   const WsLayout w = ws_layout(cfg);
   int32_t* blk_cnt = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + w.dispatch_blk_cnt);
   // T == 0 still has to produce zero counts and offsets: the kernels handle an empty assignment list
@@ -185,7 +210,7 @@ int ffn_fwd_impl(const moe_cfg* cfg, const void* x_perm, const void* W1, const v
   g.A = x_perm; g.B = W1; g.B2 = W1b; g.N = f; g.K = d;
   g.C = sv; g.C2 = sv + plane; g.C3 = sv + 2 * plane;
   {
-    ProfScope ps(MOE_PROF_GEMM1_FWD, s);
+    ProfScope ps(cfg, MOE_PROF_GEMM1_FWD, s);
     CHECK(launch_gemm(cfg, MODE_NN, swiglu ? EPI_SWIGLU_FWD : EPI_GELU_FWD, swiglu, false, g, max_tiles, s));
   }
   if (y_perm == nullptr) return MOE_OK;
@@ -194,14 +219,14 @@ int ffn_fwd_impl(const moe_cfg* cfg, const void* x_perm, const void* W1, const v
   g.C = y_perm; g.C2 = g.C3 = nullptr;
   if (cfg->dtype == MOE_DTYPE_BF16 && split_k_applies(cfg->E, f))   // smallest row tiles: split-K (gemm.h)
     g.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ffn_split);
-  ProfScope ps(MOE_PROF_GEMM2_FWD, s);
+  ProfScope ps(cfg, MOE_PROF_GEMM2_FWD, s);
   return launch_gemm(cfg, MODE_NN, EPI_STORE, false, false, g, max_tiles, s);
 }
 }  // namespace
 
 int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b, const void* W2,
                        const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo, const int32_t* slice_hi,
-                       void* saved, void* y_perm, void* ws, void* stream) {
+                       void* saved, void* y_perm, void* ws, size_t ws_bytes, void* stream) {
   CHECK(check_cfg(cfg));
   CHECK(check_slices(slice_lo, slice_hi));
   REQUIRE(x_perm); REQUIRE(W1); REQUIRE(W2); REQUIRE(offsets); REQUIRE(kept); REQUIRE(saved); REQUIRE(y_perm); REQUIRE(ws);
@@ -210,13 +235,14 @@ int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, c
   if (!swiglu && W1b != nullptr) return MOE_ERR_BAD_DTYPE;
   ALIGNED(x_perm); ALIGNED(W1); ALIGNED(W1b); ALIGNED(W2); ALIGNED(offsets); ALIGNED(kept); ALIGNED(slice_lo);
   ALIGNED(slice_hi); ALIGNED(saved); ALIGNED(y_perm); ALIGNED(ws);
+  CHECK(check_ws(cfg, ws, ws_bytes));
   if (cfg->T == 0) return MOE_OK;
   return ffn_fwd_impl(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, saved, y_perm, ws, (hipStream_t)stream);
 }
 
 int moe_expert_ffn_recompute(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b,
                              const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo,
-                             const int32_t* slice_hi, void* saved, void* ws, void* stream) {
+                             const int32_t* slice_hi, void* saved, void* ws, size_t ws_bytes, void* stream) {
   CHECK(check_cfg(cfg));
   CHECK(check_slices(slice_lo, slice_hi));
   REQUIRE(x_perm); REQUIRE(W1); REQUIRE(offsets); REQUIRE(kept); REQUIRE(saved); REQUIRE(ws);
@@ -225,6 +251,7 @@ int moe_expert_ffn_recompute(const moe_cfg* cfg, const void* x_perm, const void*
   if (!swiglu && W1b != nullptr) return MOE_ERR_BAD_DTYPE;
   ALIGNED(x_perm); ALIGNED(W1); ALIGNED(W1b); ALIGNED(offsets); ALIGNED(kept); ALIGNED(slice_lo); ALIGNED(slice_hi);
   ALIGNED(saved); ALIGNED(ws);
+  CHECK(check_ws(cfg, ws, ws_bytes));
   if (cfg->T == 0) return MOE_OK;
   return ffn_fwd_impl(cfg, x_perm, W1, W1b, nullptr, offsets, kept, slice_lo, slice_hi, saved, nullptr, ws,
                       (hipStream_t)stream);
@@ -239,7 +266,7 @@ int moe_combine(const moe_cfg* cfg, const void* y_perm, const float* topk_w, con
   ALIGNED(y_perm); ALIGNED(topk_w); ALIGNED(topk_idx); ALIGNED(row_of); ALIGNED(offsets); ALIGNED(kept);
   ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(out);
   if (cfg->T == 0) return MOE_OK;
-  ProfScope ps(MOE_PROF_COMBINE, (hipStream_t)stream);
+  ProfScope ps(cfg, MOE_PROF_COMBINE, (hipStream_t)stream);
   return launch_combine(cfg, y_perm, topk_w, topk_idx, row_of, offsets, kept, slice_lo, slice_hi, out, accumulate,
                         (hipStream_t)stream);
 }
@@ -254,7 +281,7 @@ int moe_combine_bwd(const moe_cfg* cfg, const void* d_out, const void* y_perm, c
   ALIGNED(d_out); ALIGNED(y_perm); ALIGNED(topk_w); ALIGNED(topk_idx); ALIGNED(row_of); ALIGNED(offsets);
   ALIGNED(kept); ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(dy_perm); ALIGNED(d_topk_w);
   if (cfg->T == 0) return MOE_OK;
-  ProfScope ps(MOE_PROF_COMBINE_BWD, (hipStream_t)stream);
+  ProfScope ps(cfg, MOE_PROF_COMBINE_BWD, (hipStream_t)stream);
   return launch_combine_bwd(cfg, d_out, y_perm, topk_w, topk_idx, row_of, offsets, kept, slice_lo, slice_hi, dy_perm,
                             d_topk_w, (hipStream_t)stream);
 }
@@ -262,7 +289,7 @@ int moe_combine_bwd(const moe_cfg* cfg, const void* d_out, const void* y_perm, c
 int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_perm, const void* saved, const void* W1,
                        const void* W1b, const void* W2, const int32_t* offsets, const int32_t* kept,
                        const int32_t* slice_lo, const int32_t* slice_hi, void* dx_perm, float* dW1, float* dW1b,
-                       float* dW2, int32_t accumulate, void* ws, void* stream) {
+                       float* dW2, int32_t accumulate, void* ws, size_t ws_bytes, void* stream) {
   CHECK(check_cfg(cfg));
   CHECK(check_slices(slice_lo, slice_hi));
   REQUIRE(dy_perm); REQUIRE(x_perm); REQUIRE(saved); REQUIRE(W1); REQUIRE(W2); REQUIRE(offsets); REQUIRE(kept);
@@ -273,6 +300,7 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
   ALIGNED(dy_perm); ALIGNED(x_perm); ALIGNED(saved); ALIGNED(W1); ALIGNED(W1b); ALIGNED(W2); ALIGNED(offsets);
   ALIGNED(kept); ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(dx_perm); ALIGNED(dW1); ALIGNED(dW1b); ALIGNED(dW2);
   ALIGNED(ws);
+  CHECK(check_ws(cfg, ws, ws_bytes));
   if (cfg->T == 0) return MOE_OK;
   hipStream_t s = (hipStream_t)stream;
   const WsLayout w = ws_layout(cfg);
@@ -307,16 +335,16 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
   const bool pair_h = bf && (long long)((f + tr - 1) / tr) * max_tiles <= few;
   const bool pair_x = bf && (long long)((d + tr - 1) / tr) * max_tiles <= few;
   {
-    ProfScope ps(MOE_PROF_DH_BWD, s);
+    ProfScope ps(cfg, MOE_PROF_DH_BWD, s);
     if (pair_h) CHECK(launch_gemm_bf16_pair(epi_h, false, gh, max_tiles, gw2, s));
     else CHECK(launch_gemm(cfg, MODE_NT, epi_h, false, false, gh, max_tiles, s));
   }
   if (!pair_h) {
-    ProfScope ps(MOE_PROF_DW2_BWD, s);
+    ProfScope ps(cfg, MOE_PROF_DW2_BWD, s);
     CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, gw2, 0, s));
   }
   if (!pair_x || swiglu) {
-    ProfScope ps(MOE_PROF_DW1_BWD, s);
+    ProfScope ps(cfg, MOE_PROF_DW1_BWD, s);
     if (!pair_x) CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, gw1, 0, s));
     if (swiglu) {
       GemmArgs gw1b = gw1;
@@ -324,7 +352,7 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
       CHECK(launch_gemm(cfg, MODE_TN, EPI_DW, false, false, gw1b, 0, s));
     }
   }
-  ProfScope ps(MOE_PROF_DX_BWD, s);
+  ProfScope ps(cfg, MOE_PROF_DX_BWD, s);
   if (bf && !swiglu && split_k_applies(cfg->E, f))   // the smallest row tiles of the GELU dx use split-K (gemm.h)
     gx.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ffn_split);
   if (pair_x) return launch_gemm_bf16_pair(EPI_STORE, swiglu, gx, max_tiles, gw1, s);
@@ -333,12 +361,13 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
 
 int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx, const float* topk_w,
                   const float* d_topk_w, float* d_logits, float* dWr, void* dx, int32_t accumulate, void* ws,
-                  void* stream) {
+                  size_t ws_bytes, void* stream) {
   CHECK(check_cfg(cfg));
   REQUIRE(x); REQUIRE(Wr); REQUIRE(topk_idx); REQUIRE(topk_w); REQUIRE(d_topk_w); REQUIRE(d_logits);
   REQUIRE(ws);
   ALIGNED(x); ALIGNED(Wr); ALIGNED(topk_idx); ALIGNED(topk_w); ALIGNED(d_topk_w); ALIGNED(d_logits); ALIGNED(dWr);
   ALIGNED(dx); ALIGNED(ws);
+  CHECK(check_ws(cfg, ws, ws_bytes));
   hipStream_t s = (hipStream_t)stream;
   if (cfg->T == 0) {
     if (accumulate || dWr == nullptr) return MOE_OK;

@@ -19,10 +19,17 @@ inline int launch_status() {
 }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t elt_size(const moe_cfg* c) { return c->dtype == MOE_DTYPE_BF16 ? 2 : 4; }
+// The grouped GEMMs reach an operand through one buffer descriptor and a 32-bit byte offset per lane.  The
+// longest walks are an expert's whole share in the weight-gradient GEMM (rows x max(d, f) elements; one expert
+// may hold every assignment) and one expert's weight matrix (d x f elements; fp32 gradients are 4 bytes wide).
+inline bool offsets_fit_32_bits(long long T, long long k, long long d, long long f, int elt_bytes) {
+  const long long lim = 1ll << 32;
+  return T * k * (d > f ? d : f) * elt_bytes < lim && d * f * 4 < lim;
+}
 
 // Workspace layout (bytes from the start of `ws`), one region per user; see api.hip.
 struct WsLayout {
-  size_t dispatch_blk_cnt;  // int32 [nblk][E]
+  size_t dispatch_blk_cnt;  // int32 [nblk + 1][E]: per-block counts (or their prefixes) and a row of totals
   size_t tile_map;          // int32 header + int4 entries (grouped GEMM row tiles)
   size_t route_partials;    // fp32 [nchunk][d][E]
   size_t route_wrt;         // fp32 [E][d]: transposed router weight

@@ -24,12 +24,33 @@ __global__ __launch_bounds__(DP_THREADS) void dispatch_hist_kernel(const int32_t
 #pragma unroll
   for (int r = 0; r < DP_ROUNDS; ++r) {
     const int a = base + r * DP_THREADS + threadIdx.x;
-    if (a < A) atomicAdd(&s_cnt[topk_idx[a]], 1);
+    if (a < A) {
+      const int e = topk_idx[a];
+      if (e >= 0 && e < E) atomicAdd(&s_cnt[e], 1);   // an id outside [0, E) is a dropped assignment
+    }
   }
   __syncthreads();
   for (int e = threadIdx.x; e < E; e += DP_THREADS) blk_cnt[(size_t)blockIdx.x * E + e] = s_cnt[e];
 }
 
+// Many blocks (more than DP_INLINE_SCAN): the per-block counts are turned into exclusive prefixes over the
+// blocks once, in place, one thread per expert, and row nblk receives the totals; the rank kernel then reads
+// two rows instead of scanning all of them (which would make the work quadratic in the number of blocks).
+constexpr int DP_INLINE_SCAN = 64;
+__global__ __launch_bounds__(DP_THREADS) void dispatch_scan_kernel(int32_t* __restrict__ blk_cnt, int E, int nblk) {
+  const int e = blockIdx.x * DP_THREADS + threadIdx.x;
+  if (e >= E) return;
+  int run = 0;
+  for (int b = 0; b < nblk; ++b) {
+    const int c = blk_cnt[(size_t)b * E + e];
+    blk_cnt[(size_t)b * E + e] = run;
+    run += c;
+  }
+  blk_cnt[(size_t)nblk * E + e] = run;
+}
+
+// SCANNED: blk_cnt holds exclusive prefixes and a row of totals (dispatch_scan_kernel) instead of counts.
+template <bool SCANNED>
 __global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
     const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ blk_cnt, int A, int E, int capacity, int nblk,
     int32_t* __restrict__ counts, int32_t* __restrict__ kept, int32_t* __restrict__ offsets,
@@ -40,14 +61,18 @@ __global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
   __shared__ int s_sub[DP_SUB][MOE_MAX_E];       // per sub-chunk counts, then exclusive offsets
   const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
 
-  // scan over blocks (each block redoes it: nblk*E is tiny) and over experts
+  // scan over blocks (few blocks: each block redoes it, nblk*E is tiny) and over experts
   for (int e = tid; e < MOE_MAX_E; e += DP_THREADS) {
     int before = 0, total = 0;
     if (e < E) {
-      for (int b = 0; b < nblk; ++b) {
-        const int c = blk_cnt[(size_t)b * E + e];
-        before += (b < (int)blockIdx.x) ? c : 0;
-        total += c;
+      if constexpr (SCANNED) {
+        if (nblk > 0) { before = blk_cnt[(size_t)blockIdx.x * E + e]; total = blk_cnt[(size_t)nblk * E + e]; }
+      } else {
+        for (int b = 0; b < nblk; ++b) {
+          const int c = blk_cnt[(size_t)b * E + e];
+          before += (b < (int)blockIdx.x) ? c : 0;
+          total += c;
+        }
       }
     }
     const int m = (capacity > 0) ? min(total, capacity) : total;
@@ -71,8 +96,9 @@ __global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
 #pragma unroll
   for (int r = 0; r < DP_ROUNDS; ++r) {
     const int a = base + r * DP_THREADS + tid;
-    const bool valid = a < A;
-    const int e = valid ? topk_idx[a] : -1;
+    int e = (a < A) ? topk_idx[a] : -1;
+    if (e < 0 || e >= E) e = -1;        // past the end, or an id outside [0, E): dropped, never an index
+    const bool valid = e >= 0;
     my_e[r] = e;
     // rank among the lanes of this wave with the same expert; one pass per distinct expert present
     unsigned long long todo = __ballot(valid);
@@ -101,9 +127,11 @@ __global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
     const int a = base + r * DP_THREADS + tid;
     if (a >= A) continue;
     const int e = my_e[r];
-    const int rank = s_sub[r * DP_WAVES + wave][e] + my_rank[r];
     int row = -1;
-    if (rank < s_kept[e]) { row = s_off[e] + rank; src_of[row] = a; }
+    if (e >= 0) {
+      const int rank = s_sub[r * DP_WAVES + wave][e] + my_rank[r];
+      if (rank < s_kept[e]) { row = s_off[e] + rank; src_of[row] = a; }
+    }
     row_of[a] = row;
     if (a >= R) src_of[a] = -1;   // rows past the end of the kept lists
   }
@@ -165,10 +193,17 @@ int launch_dispatch(const moe_cfg* c, const void* x, const int32_t* idx, const i
     if (rc != MOE_OK) return rc;
   }
   // with no assignments one block still writes the (all-zero) counts, kept and offsets
-  dispatch_rank_kernel<<<nblk > 0 ? nblk : 1, DP_THREADS, 0, s>>>(idx, blk_cnt, A, c->E, c->capacity, nblk, counts, kept, offsets, row_of, src_of);
+  if (nblk > DP_INLINE_SCAN) {
+    dispatch_scan_kernel<<<(c->E + DP_THREADS - 1) / DP_THREADS, DP_THREADS, 0, s>>>(blk_cnt, c->E, nblk);
+    rc = launch_status();
+    if (rc != MOE_OK) return rc;
+    dispatch_rank_kernel<true><<<nblk, DP_THREADS, 0, s>>>(idx, blk_cnt, A, c->E, c->capacity, nblk, counts, kept, offsets, row_of, src_of);
+  } else {
+    dispatch_rank_kernel<false><<<nblk > 0 ? nblk : 1, DP_THREADS, 0, s>>>(idx, blk_cnt, A, c->E, c->capacity, nblk, counts, kept, offsets, row_of, src_of);
+  }
   rc = launch_status();
   if (rc != MOE_OK || x_perm == nullptr || A == 0) return rc;
-  ProfScope ps(MOE_PROF_GATHER, s);
+  ProfScope ps(c, MOE_PROF_GATHER, s);
   const int waves_per_block = 256 / WAVE;
   const int grid = min((A + waves_per_block * GR - 1) / (waves_per_block * GR), 256 * 32);
   if (c->dtype == MOE_DTYPE_BF16)

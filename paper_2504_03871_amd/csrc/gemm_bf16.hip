@@ -14,11 +14,11 @@ static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
   constexpr int BN = DUAL ? T_BN_DUAL : T_BN;
   constexpr int lds = gemm_bf16_lds_bytes<T_BM, BN, T_BK, DUAL, T_WGM, T_WGN, NBUF, EPI == EPI_GELU_BWD || EPI == EPI_GELU_FWD>();
   auto kern = gemm_bf16_kernel<MODE, EPI, DUAL, CHAIN, T_BM, BN, T_BK, T_WGM, T_WGN>;
-  static bool attr_done = false;   // benign race: the attribute call is idempotent
-  if (!attr_done) {
+  // more than 64 KB of dynamic LDS needs the attribute on the current device; set on every launch (a cheap
+  // host-side call) rather than remembered, so the library keeps no per-process or per-device state
+  {
     hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (err != hipSuccess) return set_hip_error(err);
-    attr_done = true;
   }
   const int ntn = (g.N + BN - 1) / BN;
   long long tiles;
@@ -45,11 +45,11 @@ static int launch_pair(const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hi
   constexpr int lds2 = gemm_bf16_lds_bytes<T_BM, T_BN, T_BK, false, T_WGM, T_WGN>();
   constexpr int lds = lds1 > lds2 ? lds1 : lds2;
   auto kern = gemm_bf16_pair_kernel<MODE_NT, EPI1, CHAIN1, MODE_TN, EPI_DW, T_BM, T_BN, T_BK, T_WGM, T_WGN>;
-  static bool attr_done = false;   // benign race: the attribute call is idempotent
-  if (!attr_done) {
+  // more than 64 KB of dynamic LDS needs the attribute on the current device; set on every launch (a cheap
+  // host-side call) rather than remembered, so the library keeps no per-process or per-device state
+  {
     hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (err != hipSuccess) return set_hip_error(err);
-    attr_done = true;
   }
   // the first GEMM's block count is a multiple of the XCD count, so that a tile number still tells the
   // XCD its block runs on for the second one (numbers past the last tile return at once)

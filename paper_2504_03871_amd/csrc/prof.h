@@ -1,4 +1,5 @@
-// Benchmark aid: optional HIP-event brackets around individual kernel launches (see moe_profile_kernel).
+// Benchmark aid: optional HIP-event brackets around individual kernel launches, driven by the caller-owned
+// moe_prof that a moe_cfg may point at (moe.h).  The library itself holds no profiling state.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -6,27 +7,20 @@
 
 namespace moe {
 
-struct ProfSlot {
-  void** start = nullptr;
-  void** stop = nullptr;
-  int n = 0;
-  long long count = 0;
-};
-ProfSlot& prof_slot(int which);   // per host thread
-
 // Records the armed events of kernel `which` on `s` at construction and destruction.
 struct ProfScope {
-  ProfSlot& slot;
+  moe_prof* p;
   hipStream_t s;
+  int which;
   int i = -1;
-  ProfScope(int which, hipStream_t stream) : slot(prof_slot(which)), s(stream) {
-    if (slot.n > 0) {
-      i = (int)(slot.count++ % slot.n);
-      (void)hipEventRecord((hipEvent_t)slot.start[i], s);
+  ProfScope(const moe_cfg* c, int which_, hipStream_t stream) : p(c->prof), s(stream), which(which_) {
+    if (p != nullptr && p->n[which] > 0) {
+      i = (int)(p->count[which]++ % p->n[which]);
+      (void)hipEventRecord((hipEvent_t)p->start[which][i], s);
     }
   }
   ~ProfScope() {
-    if (i >= 0) (void)hipEventRecord((hipEvent_t)slot.stop[i], s);
+    if (i >= 0) (void)hipEventRecord((hipEvent_t)p->stop[which][i], s);
   }
 };
 

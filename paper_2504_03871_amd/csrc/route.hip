@@ -346,6 +346,7 @@ __global__ __launch_bounds__(256) void route_bwd_dx_kernel(
     if (j < k) {
       ds[j] = topk_w[(size_t)t * k + j] * (d_topk_w[(size_t)t * k + j] - gsum);
       ej[j] = topk_idx[(size_t)t * k + j];
+      if (ej[j] < 0 || ej[j] >= E) { ej[j] = -1; ds[j] = 0.f; }   // an id outside [0, E) contributes nothing
     }
   }
   for (int e = lane; e < E; e += WAVE) {
@@ -363,7 +364,7 @@ __global__ __launch_bounds__(256) void route_bwd_dx_kernel(
 #pragma unroll
     for (int j = 0; j < MOE_MAX_K; ++j)
       if (j < k) {
-        const float* wr = WrT + (size_t)ej[j] * d + c;
+        const float* wr = WrT + (size_t)max(ej[j], 0) * d + c;
 #pragma unroll
         for (int i = 0; i < VN; i += 4) {
           const float4 w4 = *reinterpret_cast<const float4*>(wr + i);
@@ -398,8 +399,9 @@ __global__ __launch_bounds__(RB_MAX_WAVES* WAVE) void route_bwd_dwr_kernel(
   for (int i = lane; i < E * COLS; i += WAVE) acc[i] = 0.f;
   for (int i = threadIdx.x; i < nt * k; i += blockDim.x) {
     const int e = topk_idx[(size_t)t0 * k + i];
-    s_e[i] = e;
-    s_ds[i] = d_logits[(size_t)(t0 + i / k) * E + e];
+    const bool ok = e >= 0 && e < E;   // an id outside [0, E) contributes nothing
+    s_e[i] = ok ? e : 0;
+    s_ds[i] = ok ? d_logits[(size_t)(t0 + i / k) * E + e] : 0.f;
   }
   __syncthreads();
   const bool live = c0 < d;   // d is a multiple of VEC

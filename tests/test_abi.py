@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 def test_error_strings():
     lib = B.lib()
     assert lib.moe_error_string(0) == b"ok"
-    for code in range(-6, 0):
+    for code in range(-7, 0):
         assert len(lib.moe_error_string(code)) > 3
     assert b"unknown" in lib.moe_error_string(-99)
     assert lib.moe_last_hip_error() == 0
@@ -104,3 +104,54 @@ def test_pointer_validation_happens_before_any_launch():
     with pytest.raises(B.MoeError) as ei:
         B.moe_route_bwd(cfg, P, P, P, P, P, P, None, None, None, stream=s)   # both parts skipped is fine, no workspace is not
     assert ei.value.code == -1
+
+
+def test_too_small_workspace_is_rejected_before_any_launch():
+    """Every call that takes the workspace also takes its size: one byte short is MOE_ERR_WORKSPACE."""
+    cfg = B.make_cfg(8, 64, 128, 4, 2)
+    need = B.moe_workspace_bytes(cfg)
+    P = 0x10000
+    s = ctypes.c_void_p(0)
+    calls = [
+        lambda n: B.moe_route(cfg, P, P, None, None, P, P, P, ws=P, stream=s, ws_bytes=n),
+        lambda n: B.moe_dispatch(cfg, P, P, None, None, P, P, P, P, P, P, P, stream=s, ws_bytes=n),
+        lambda n: B.moe_expert_ffn_fwd(cfg, P, P, None, P, P, P, None, None, P, P, P, stream=s, ws_bytes=n),
+        lambda n: B.moe_expert_ffn_recompute(cfg, P, P, None, P, P, None, None, P, P, stream=s, ws_bytes=n),
+        lambda n: B.moe_expert_ffn_bwd(cfg, P, P, P, P, None, P, P, P, None, None, P, P, None, P, 0, P, stream=s, ws_bytes=n),
+        lambda n: B.moe_route_bwd(cfg, P, P, P, P, P, P, P, P, P, stream=s, ws_bytes=n),
+    ]
+    for call in calls:
+        for n in (0, need - 1):
+            with pytest.raises(B.MoeError) as ei:
+                call(n)
+            assert ei.value.code == -7
+    assert b"workspace" in B.lib().moe_error_string(-7)
+
+
+def test_shapes_whose_byte_offsets_pass_32_bits_are_rejected():
+    """The grouped GEMMs use 32-bit byte offsets into one expert's share and one expert's weights."""
+    ok = dict(T=32768, d_model=4096, d_ff=14336, E=8, k=2, dtype=B.DTYPE_BF16, act=B.ACT_SWIGLU)
+    assert B.moe_workspace_bytes(B.make_cfg(**ok)) > 0
+    # T*k*max(d, f)*2 bytes: 2^16 * 2 * 2^14 * 2 = 2^32 exactly is out, one row tile less is in
+    edge = dict(T=1 << 16, d_model=64, d_ff=1 << 14, E=8, k=2, dtype=B.DTYPE_BF16, act=B.ACT_GELU)
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_workspace_bytes(B.make_cfg(**edge))
+    assert ei.value.code == -2
+    assert B.moe_workspace_bytes(B.make_cfg(**{**edge, "T": (1 << 16) - 1})) > 0
+    with pytest.raises(B.MoeError) as ei:       # the same element count in fp32 is twice the bytes
+        B.moe_workspace_bytes(B.make_cfg(**{**edge, "T": 1 << 15, "dtype": B.DTYPE_F32}))
+    assert ei.value.code == -2
+    with pytest.raises(B.MoeError) as ei:       # d * f * 4 bytes of one expert's fp32 weight gradient
+        B.moe_workspace_bytes(B.make_cfg(T=8, d_model=1 << 15, d_ff=1 << 15, E=2, k=1))
+    assert ei.value.code == -2
+
+
+def test_bench_stream_validation():
+    s = ctypes.c_void_p(0)
+    lib = B.lib()
+    assert lib.moe_bench_stream(None, 0x10000, 1024, 0, s) == -1
+    assert lib.moe_bench_stream(0x10000, None, 1024, 0, s) == -1
+    assert lib.moe_bench_stream(0x10000, 0x20008, 1024, 0, s) == -5
+    assert lib.moe_bench_stream(0x10000, 0x20000, 1000, 0, s) == -2
+    assert lib.moe_bench_stream(0x10000, 0x20000, 1024, 2, s) == -3
+    assert lib.moe_bench_stream(0x10000, None, 0, 1, s) == 0

@@ -48,6 +48,14 @@ def test_recomputed_activations_and_gradients_are_bit_identical(name):
     L.ffn_recompute()
     torch.cuda.synchronize()
     assert torch.equal(L.saved, saved), "recomputed activations differ from the forward's"
+    # the recomputed planes against the oracle's forward intermediates (routing replayed from the GPU's logits)
+    kept = U.host(L.kept)
+    lo, hi = S.partial_slices(w, kept) if w.partial else (None, None)
+    ref = U.run_oracle(w, inp, gpu_logits=L.logits.cpu().numpy(), lo=lo, hi=hi)
+    assert (U.host(L.row_of) == ref["row_of"]).all()
+    planes = ("A", "H") if w.act == S.ACT_GELU else ("G", "U", "H")
+    for i, p in enumerate(planes):
+        U.assert_close("recomputed " + p, U.host(L.saved_plane(i)), ref["fw"][p], U.TOL[w.dtype])
     assert torch.equal(L.row_of, keep["row_of"]) and torch.equal(L.x_perm.view(torch.int16), keep["x_perm"].view(torch.int16))
     L.backward()
     torch.cuda.synchronize()
@@ -55,3 +63,7 @@ def test_recomputed_activations_and_gradients_are_bit_identical(name):
         a, b = getattr(L, n), keep[n]
         assert torch.equal(a.view(torch.int16 if a.element_size() == 2 else torch.int32),
                            b.view(torch.int16 if b.element_size() == 2 else torch.int32)), n
+    # and the gradients of the checkpointed backward against the oracle
+    for n, key in (("dx", "dx"), ("dW1", "dW1"), ("dW2", "dW2"), ("dWr", "dWr")) + \
+            ((("dW1b", "dW1b"),) if w.act == S.ACT_SWIGLU else ()):
+        U.assert_close("checkpointed " + n, U.host(getattr(L, n)), ref[key], U.TOL[w.dtype])

@@ -45,6 +45,17 @@ def test_micro_batched_streams_equal_the_whole_batch(name):
             full[i].d_out.copy_(full[i + 1].dx)
         full[i].backward()
     torch.cuda.synchronize()
+    # the reference the engine is compared with is itself checked against the oracle: every layer on the
+    # input and the upstream gradient it actually received (its GPU-side values, as stored)
+    for i in range(L):
+        li = dict(inps[i])
+        li["x"] = full[i].x.float().cpu().numpy()
+        li["d_out"] = full[i].d_out.float().cpu().numpy()
+        ref = U.run_oracle(w, li, gpu_logits=full[i].logits.cpu().numpy())
+        assert (U.host(full[i].topk_idx) == ref["idx"]).all()
+        for n, key in (("out", "out"), ("dx", "dx"), ("dW1", "dW1"), ("dW2", "dW2"), ("dWr", "dWr")) + \
+                ((("dW1b", "dW1b"),) if w.act == S.ACT_SWIGLU else ()):
+            U.assert_close(f"layer {i} {n} vs oracle", U.host(getattr(full[i], n)), ref[key], U.TOL[w.dtype])
 
     eng = ZebraExpertEngine(L, R, T_mb, w.d, w.f, w.E, w.k, dtype=w.dtype, act=w.act)
     for i in range(L):
@@ -66,3 +77,11 @@ def test_micro_batched_streams_equal_the_whole_batch(name):
         for i in range(L):
             for n in ("dW1", "dW2", "dWr") + (("dW1b",) if w.act == S.ACT_SWIGLU else ()):
                 U.assert_close(f"layer {i} {n}", U.host(getattr(eng.params[i], n)), U.host(getattr(full[i], n)), 1e-4)
+    # the engine's own results against the oracle (layer 0: its input is an input of the test)
+    li = dict(inps[0])
+    li["d_out"] = full[0].d_out.float().cpu().numpy()
+    ref = U.run_oracle(w, li, gpu_logits=full[0].logits.cpu().numpy())
+    g0 = torch.cat([eng.grad[0][j] for j in range(R)])
+    U.assert_close("engine input gradient vs oracle", U.host(g0), ref["dx"], U.TOL[w.dtype])
+    for n, key in (("dW1", "dW1"), ("dW2", "dW2"), ("dWr", "dWr")) + ((("dW1b", "dW1b"),) if w.act == S.ACT_SWIGLU else ()):
+        U.assert_close(f"engine layer 0 {n} vs oracle", U.host(getattr(eng.params[0], n)), ref[key], U.TOL[w.dtype])
