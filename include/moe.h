@@ -148,6 +148,23 @@ MOE_API int moe_dispatch(const moe_cfg* cfg, const void* x, const int32_t* topk_
                  void* x_perm, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * moe_dispatch for callers that cannot allocate or carry a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as moe_dispatch
+ * minus `ws`: the per-block histograms live in a device array that is part of the library's code object
+ * (MOE_DISPATCH_STATIC_BYTES per GPU, held until the process ends; its address is looked up once per
+ * device on the first call there).  Allocates nothing.  Limit: (ceil(T*k / 1024) + 1) * E * 4 bytes must fit
+ * the array, else MOE_ERR_WORKSPACE before anything is launched.  All calls on one GPU share the array, so
+ * two calls that overlap in time on one GPU (different streams or host threads) race; calls in stream order
+ * are fine, and nothing in the array has to be cleared between calls (every entry a call reads, it has
+ * written first).
+ */
+#define MOE_DISPATCH_STATIC_BYTES (1 << 20)
+MOE_API int moe_dispatch_static(const moe_cfg* cfg, const void* x, const int32_t* topk_idx,
+                        const int32_t* slice_lo, const int32_t* slice_hi,
+                        int32_t* counts, int32_t* kept, int32_t* offsets, int32_t* row_of, int32_t* src_of,
+                        void* x_perm, void* stream);
+
+/*
  * Expert FFN forward on the in-share rows (Section 2.1: experts are FFNs made of GEMMs).
  * GELU:   A = x_perm W1[e], H = gelu_erf(A), y_perm = H W2[e];          saved = [A | H]
  * SwiGLU: G = x_perm W1[e], U = x_perm W1b[e], H = silu(G) * U, y_perm = H W2[e];  saved = [G | U | H]

@@ -18,7 +18,7 @@ ACT_GELU, ACT_SWIGLU = 0, 1
 MAX_E, MAX_K = 256, 8
 
 SYMBOLS = ("moe_error_string", "moe_last_hip_error", "moe_workspace_bytes", "moe_saved_bytes", "moe_route",
-           "moe_dispatch", "moe_expert_ffn_fwd", "moe_expert_ffn_recompute", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
+           "moe_dispatch", "moe_dispatch_static", "moe_expert_ffn_fwd", "moe_expert_ffn_recompute", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
            "moe_route_bwd", "moe_asymea_plan", "moe_asymea_shares", "moe_bench_stream")
 
 PROF = {"gemm1_fwd": 0, "gemm2_fwd": 1, "dh_bwd": 2, "dw2_bwd": 3, "dw1_bwd": 4, "dx_bwd": 5, "gather": 6,
@@ -65,6 +65,7 @@ def lib():
             "moe_saved_bytes": [cfgp, ctypes.POINTER(ctypes.c_size_t)],
             "moe_route": [cfgp] + [p] * 8 + [sz, p],
             "moe_dispatch": [cfgp] + [p] * 11 + [sz, p],
+            "moe_dispatch_static": [cfgp] + [p] * 11,
             "moe_expert_ffn_fwd": [cfgp] + [p] * 11 + [sz, p],
             "moe_expert_ffn_recompute": [cfgp] + [p] * 9 + [sz, p],
             "moe_combine": [cfgp] + [p] * 9 + [i32, p],
@@ -143,6 +144,13 @@ def moe_dispatch(cfg, x, topk_idx, slice_lo, slice_hi, counts, kept, offsets, ro
                                               _ptr(src_of), _ptr(x_perm), _ptr(ws),
                                               _nbytes(ws) if ws_bytes is None else ws_bytes,
                                               _stream() if stream is None else stream))
+
+
+def moe_dispatch_static(cfg, x, topk_idx, slice_lo, slice_hi, counts, kept, offsets, row_of, src_of, x_perm, stream=None):
+    _check("moe_dispatch_static", lib().moe_dispatch_static(ctypes.byref(cfg), _ptr(x), _ptr(topk_idx), _ptr(slice_lo),
+                                                            _ptr(slice_hi), _ptr(counts), _ptr(kept), _ptr(offsets),
+                                                            _ptr(row_of), _ptr(src_of), _ptr(x_perm),
+                                                            _stream() if stream is None else stream))
 
 
 def moe_expert_ffn_fwd(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, saved, y_perm, ws, stream=None,

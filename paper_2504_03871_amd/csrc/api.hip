@@ -58,6 +58,7 @@ int launch_route_bwd(const moe_cfg*, const void*, const float*, const int32_t*, 
                      float*, void*, int, float*, float*, hipStream_t);
 int launch_dispatch(const moe_cfg*, const void*, const int32_t*, const int32_t*, const int32_t*, int32_t*, int32_t*,
                     int32_t*, int32_t*, int32_t*, void*, int32_t*, hipStream_t);
+int dispatch_static_scratch(int32_t** out);
 int launch_combine(const moe_cfg*, const void*, const float*, const int32_t*, const int32_t*, const int32_t*,
                    const int32_t*, const int32_t*, const int32_t*, void*, int, hipStream_t);
 int launch_combine_bwd(const moe_cfg*, const void*, const void*, const float*, const int32_t*, const int32_t*,
@@ -120,7 +121,7 @@ const char* moe_error_string(int code) {
     case MOE_ERR_BAD_SLICE: return "slice_lo and slice_hi must both be given or both be NULL";
     case MOE_ERR_ALIGN: return "device pointer not 16-byte aligned";
     case MOE_ERR_HIP: return "HIP launch failed (see moe_last_hip_error)";
-    case MOE_ERR_WORKSPACE: return "workspace smaller than moe_workspace_bytes(cfg)";
+    case MOE_ERR_WORKSPACE: return "workspace smaller than moe_workspace_bytes(cfg), or problem too large for the static scratch";
     default: return "unknown error code";
   }
 }
@@ -185,6 +186,25 @@ int moe_dispatch(const moe_cfg* cfg, const void* x, const int32_t* topk_idx, con
   const WsLayout w = ws_layout(cfg);
   int32_t* blk_cnt = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + w.dispatch_blk_cnt);
   // T == 0 still has to produce zero counts and offsets: the kernels handle an empty assignment list
+  return launch_dispatch(cfg, x, topk_idx, slice_lo, slice_hi, counts, kept, offsets, row_of, src_of, x_perm, blk_cnt,
+                         (hipStream_t)stream);
+}
+
+int moe_dispatch_static(const moe_cfg* cfg, const void* x, const int32_t* topk_idx, const int32_t* slice_lo,
+                        const int32_t* slice_hi, int32_t* counts, int32_t* kept, int32_t* offsets, int32_t* row_of,
+                        int32_t* src_of, void* x_perm, void* stream) {
+  CHECK(check_cfg(cfg));
+  CHECK(check_slices(slice_lo, slice_hi));
+  REQUIRE(topk_idx); REQUIRE(counts); REQUIRE(kept); REQUIRE(offsets); REQUIRE(row_of); REQUIRE(src_of);
+  if (x_perm != nullptr) REQUIRE(x);
+  ALIGNED(x); ALIGNED(topk_idx); ALIGNED(slice_lo); ALIGNED(slice_hi); ALIGNED(counts); ALIGNED(kept);
+  ALIGNED(offsets); ALIGNED(row_of); ALIGNED(src_of); ALIGNED(x_perm);
+  // the same per-block histogram region as the workspace version, held to the size of the static array
+  const size_t A = (size_t)cfg->T * cfg->k;
+  const size_t need = ((A + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK + 1) * (size_t)cfg->E * 4;
+  if (need > MOE_DISPATCH_STATIC_BYTES) return MOE_ERR_WORKSPACE;
+  int32_t* blk_cnt = nullptr;
+  CHECK(dispatch_static_scratch(&blk_cnt));
   return launch_dispatch(cfg, x, topk_idx, slice_lo, slice_hi, counts, kept, offsets, row_of, src_of, x_perm, blk_cnt,
                          (hipStream_t)stream);
 }

@@ -7,6 +7,7 @@
 // a scan over blocks, and an in-block stable rank built from wave ballots.
 #include "common.h"
 #include "prof.h"
+#include <mutex>
 
 namespace moe {
 
@@ -179,6 +180,35 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(
         if (tok[u] >= 0) v[u].store(x_perm + (size_t)(base + u) * d + c);
     }
   }
+}
+
+// ---------------------------------------------------------------- dispatch without a caller workspace
+// The per-block histograms of moe_dispatch_static live in this file-scope device array instead of the
+// caller's workspace.  Every GPU the library runs on holds its own copy until the process ends.  In host
+// code the array's name is only a handle: its device address is asked for once per device
+// (hipGetSymbolAddress, with that device current) and kept; kernels and everything else get that pointer.
+static __device__ __align__(256) int32_t scratch[MOE_DISPATCH_STATIC_BYTES / 4];
+
+constexpr int MAX_DEVICES = 64;
+static int32_t* g_scratch_ptr[MAX_DEVICES] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (MOE_ERR_HIP on failure).
+int dispatch_static_scratch(int32_t** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return set_hip_error(e);
+  if (dev < 0 || dev >= MAX_DEVICES) return MOE_ERR_BAD_SHAPE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return set_hip_error(e);
+    if (p == nullptr) return set_hip_error(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return MOE_OK;
 }
 
 int launch_dispatch(const moe_cfg* c, const void* x, const int32_t* idx, const int32_t* lo, const int32_t* hi,

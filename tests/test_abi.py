@@ -155,3 +155,15 @@ def test_bench_stream_validation():
     assert lib.moe_bench_stream(0x10000, 0x20000, 1000, 0, s) == -2
     assert lib.moe_bench_stream(0x10000, 0x20000, 1024, 2, s) == -3
     assert lib.moe_bench_stream(0x10000, None, 0, 1, s) == 0
+
+
+def test_static_scratch_limit_is_checked_before_any_launch():
+    P = 0x10000
+    s = ctypes.c_void_p(0)
+    big = B.make_cfg(1 << 20, 64, 64, 256, 1)       # (1024 + 1) * 256 * 4 bytes > 1 MiB
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_dispatch_static(big, P, P, None, None, P, P, P, P, P, P, stream=s)
+    assert ei.value.code == -7
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_dispatch_static(B.make_cfg(8, 64, 64, 4, 2), P, None, None, None, P, P, P, P, P, P, stream=s)
+    assert ei.value.code == -1
