@@ -393,7 +393,7 @@ def main():
             cores = os.cpu_count()
         # bounded sample: the first Ts tokens of the same workload (all experts, same weights)
         per = 18 if w.act == S.ACT_SWIGLU else 12
-        target_flops = 4.0e12
+        target_flops = 1.2e13
         Ts = int(min(w.T, max(256, target_flops // (per * w.k * w.d * w.f))))
         tc = time.perf_counter()
         O.moe_layer(inp["x"][:Ts], inp["Wr"], inp["bias"], inp["W1"], inp.get("W1b"), inp["W2"], inp["d_out"][:Ts],
