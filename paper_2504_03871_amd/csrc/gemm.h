@@ -35,7 +35,8 @@ constexpr int SPLIT_ROWS = 64;
 constexpr int SPLIT_K = 8;
 constexpr int SPLIT_MAX_E = 32;
 constexpr int SPLIT_MIN_K = 2048;
-inline bool split_k_applies(int E, int K) { return E <= SPLIT_MAX_E && K >= SPLIT_MIN_K && K % (SPLIT_K * 32) == 0; }
+// (each K part must be whole 64-wide stages of the row-tile GEMMs)
+inline bool split_k_applies(int E, int K) { return E <= SPLIT_MAX_E && K >= SPLIT_MIN_K && K % (SPLIT_K * 64) == 0; }
 inline size_t split_ws_bytes(int E, int N) { return (size_t)E * SPLIT_K * SPLIT_ROWS * N * 4; }
 
 constexpr int GELU_TAB_EXP0 = 111;                 // biased exponent of 2^-16

@@ -9,6 +9,10 @@
 // stage kt while reading the fragments of stage kt+1 into a third register slot, then waits for its
 // own loads of stage kt+2 and joins the block barrier.  A global load has one to two iterations of
 // MFMA work to land, an LDS read a whole K step, and the barrier only guards buffer reuse.
+// Operands whose K index is contiguous (both of dy W^T, the activations of x W) use a second pipeline with
+// two 64-wide stages instead: a 32-wide stage fetches such an operand as 64-byte pieces of 128-byte lines,
+// which fills the address FIFO of the memory pipe (counters: full thirteen times as often) and holds the
+// matrix cores to 0.64 of their cycles against 0.72 with whole lines.
 // The direct loads are raw instructions: if the compiler knew that they write LDS it would wait for
 // every outstanding load before each LDS read it cannot prove disjoint.  The pipeline orders loads and
 // reads itself (explicit vmcnt waits, block barriers); the LDS reads stay compiler-tracked.
@@ -222,8 +226,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
   constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2;
   constexpr int STAGE = gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
   static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of K steps per stage");
-  static_assert(NB >= 4, "loads run at least three stages ahead");
-  constexpr int D = NB - 1;   // loads run D stages ahead of the MFMAs
+  static_assert(NB >= 4 || (NB == 2 && KS == 4), "a ring of four or more 32-wide stages, or two 64-wide stages");
+  constexpr int D = NB - 1;   // ring pipeline: loads run D stages ahead of the MFMAs
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps wave-dependent values scalar
@@ -360,7 +364,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     // stages) and joins the block barrier, after which stage kt+2 is visible to every wave and stage
     // kt's buffer may be overwritten.
     constexpr int L = StA::CH + StB::CH * (DUAL ? 2 : 1);   // loads per thread per stage
-    constexpr int PEND = L * (D - 2);                        // loads that may stay in flight at the barrier
+    constexpr int PEND = NB == 2 ? L : L * (D - 2);          // loads that may stay in flight at the barrier (two stages: after the prologue)
     static_assert(PEND < 64, "the wait counter has six bits");
     constexpr int WAIT_L = (PEND & 15) | ((PEND >> 4) << 14) | 0x70 | (15 << 8);   // s_waitcnt vmcnt(PEND) only
     constexpr int WAIT_0 = 0x70 | (15 << 8);                                       // s_waitcnt vmcnt(0) only
@@ -373,7 +377,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     const unsigned smem_base = lds_addr(smem);
     // Fragments are read two K steps (one stage) ahead of the MFMAs that use them, into three register
     // slots, so a read has a whole K step of MFMAs to land before anything waits for it.
-    static_assert(KS == 2, "the fragment slots rotate with two K steps per stage");
+    static_assert(KS == 2 || NB == 2, "ring pipeline: the fragment slots rotate with two K steps per stage");
     constexpr int NU = WTM + WTN * (DUAL ? 2 : 1);   // fragments read per K step
     constexpr int NMI = WTM * WTN;                   // MFMAs per K step (DUAL: pairs)
     constexpr int NR = NMI >= 4 ? 4 : NMI;           // scheduling regions per K step
@@ -476,7 +480,90 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
       for (int i = 0; i < GELU_TAB_FLOATS * 4 / (NT * 16); ++i)
         load_to_lds16(rt, smem_base + NB * STAGE + i * NT * 16 + wbase, (unsigned)(i * NT + tid) * 16u);
     }
-    if (KTT > 0) {
+    if constexpr (NB == 2) {
+      // ---- two 64-wide stages --------------------------------------------------------------------------
+      // Iteration S multiplies stage S (four K steps) out of buffer S % 2.  Fragments are still read two K
+      // steps ahead: K steps 0 and 1 read steps 2 and 3 of the same stage; then every wave waits for its own
+      // loads of stage S+1 and for its fragment reads and joins the one block barrier of the iteration, after
+      // which stage S+1 is visible to all and nobody reads buffer S % 2 again; K steps 2 and 3 read steps 0
+      // and 1 of stage S+1, and K step 2 also issues the loads of stage S+2 into buffer S % 2 (all of them:
+      // they have three to four K steps to land).  Unrolled three times for compile-time fragment slots.
+#define P2_STEP(cur_, tgt_, rbuf_, rks_, DO_NEXT_, DO_LOAD_, lkt_, lbuf_, NI_)                              \
+  do {                                                                                                      \
+    _Pragma("unroll") for (int r__ = 0; r__ < NR; ++r__) {                                                  \
+      if (DO_NEXT_) {                                                                                       \
+        _Pragma("unroll") for (int u__ = 0; u__ < NU; ++u__)                                                \
+          if (u__ * NR / NU == r__) MOE_FRAG1(tgt_, rbuf_, rks_, u__);                                      \
+      }                                                                                                     \
+      _Pragma("unroll") for (int m__ = r__ * GM; m__ < (r__ + 1) * GM; ++m__) {                             \
+        const int i__ = m__ / WTN, j__ = m__ % WTN;                                                         \
+        if (i__ < (NI_)) {                                                                                  \
+          acc[i__][j__] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i__], bfr[cur_][j__], acc[i__][j__], 0, 0, 0); \
+          if constexpr (DUAL)                                                                               \
+            acc2[i__][j__] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i__], bfr2[cur_][j__], acc2[i__][j__], 0, 0, 0); \
+        }                                                                                                   \
+      }                                                                                                     \
+      if (DO_LOAD_) {                                                                                       \
+        _Pragma("unroll") for (int q__ = 0; q__ < L; ++q__)                                                 \
+          if (q__ * NR / L == r__) MOE_LOAD1(lkt_, lbuf_, q__);                                             \
+      }                                                                                                     \
+      __builtin_amdgcn_sched_barrier(0);                                                                    \
+    }                                                                                                       \
+  } while (0)
+#define P2_ITER(S_, S0_, DO_NEXT_, DO_LOAD_, NI_)                                                           \
+  do {                                                                                                      \
+    P2_STEP((S0_) % 3, ((S0_) + 2) % 3, b0, 2, true, false, 0, 0, NI_);                                     \
+    P2_STEP(((S0_) + 1) % 3, (S0_) % 3, b0, 3, true, false, 0, 0, NI_);                                     \
+    if (DO_NEXT_) {                                                                                         \
+      __builtin_amdgcn_s_waitcnt(0);   /* vmcnt(0) lgkmcnt(0): own loads of stage S+1, own reads of stage S */ \
+      asm volatile("" ::: "memory");                                                                        \
+      __builtin_amdgcn_s_barrier();                                                                         \
+      asm volatile("" ::: "memory");                                                                        \
+    }                                                                                                       \
+    P2_STEP(((S0_) + 2) % 3, ((S0_) + 1) % 3, b1, 0, DO_NEXT_, DO_LOAD_, (S_) + 2, b0, NI_);                \
+    P2_STEP((S0_) % 3, ((S0_) + 2) % 3, b1, 1, DO_NEXT_, false, 0, 0, NI_);                                 \
+    { const int t__ = b0; b0 = b1; b1 = t__; }                                                              \
+  } while (0)
+      if (KTT > 0) {
+        int b0 = 0, b1 = STAGE;
+        MOE_LOAD(0, 0);
+        if (KTT > 1) {
+          MOE_LOAD(1, STAGE);
+          __builtin_amdgcn_s_waitcnt(WAIT_L);   // stage 0 (and the table) have landed, stage 1 may be in flight
+        } else {
+          __builtin_amdgcn_s_waitcnt(WAIT_0);
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+#define P2_MAINLOOP(NI_)                                                                        \
+  do {                                                                                          \
+    MOE_FRAGS(0, b0, 0);                                                                        \
+    MOE_FRAGS(1, b0, 1);                                                                        \
+    int S = 0;                                                                                  \
+    _Pragma("unroll 1") for (; S + 4 < KTT; S += 3) {                                           \
+      P2_ITER(S, 0, true, true, NI_);                                                           \
+      P2_ITER(S + 1, 1, true, true, NI_);                                                       \
+      P2_ITER(S + 2, 2, true, true, NI_);                                                       \
+    }                                                                                           \
+    _Pragma("unroll 1") for (; S < KTT; S += 3) {                                               \
+      P2_ITER(S, 0, S + 1 < KTT, S + 2 < KTT, NI_);                                             \
+      if (S + 1 < KTT) P2_ITER(S + 1, 1, S + 2 < KTT, S + 3 < KTT, NI_);                        \
+      if (S + 2 < KTT) P2_ITER(S + 2, 2, S + 3 < KTT, S + 4 < KTT, NI_);                        \
+    }                                                                                           \
+  } while (0)
+        if (ni == WTM) P2_MAINLOOP(WTM);
+        else P2_MAINLOOP(ni);
+#undef P2_MAINLOOP
+        // the epilogue's slabs reuse the ring: every wave must be done reading fragments first
+        __builtin_amdgcn_s_waitcnt(0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+#undef P2_STEP
+#undef P2_ITER
+    } else if (KTT > 0) {
       // ring offsets: stage kt, stage kt+1, and the buffer the loads of stage kt+D go to (the one before b0)
       int b0 = 0, b1 = STAGE, bload = D * STAGE;
 #pragma unroll
@@ -612,13 +699,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g)
 // tile of the second.  Blocks are dispatched in order, so the second GEMM's tiles start on the compute
 // units that the first one's last, partly filled round leaves idle (no stream or event in between,
 // and the two never compete for the cache from the start as two concurrent kernels would).
-template <int MODE1, int EPI1, bool CHAIN1, int MODE2, int EPI2, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>
+template <int MODE1, int EPI1, bool CHAIN1, int BK1, int NB1, int MODE2, int EPI2, int BK2, int NB2, int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_pair_kernel(GemmArgs g1, GemmArgs g2, int first_blocks) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   if ((int)blockIdx.x < first_blocks)
-    gemm_bf16_tile<MODE1, EPI1, false, CHAIN1, BM, BN, BKT, WGM, WGN, NB>(g1, blockIdx.x, smem);
+    gemm_bf16_tile<MODE1, EPI1, false, CHAIN1, BM, BN, BK1, WGM, WGN, NB1>(g1, blockIdx.x, smem);
   else
-    gemm_bf16_tile<MODE2, EPI2, false, false, BM, BN, BKT, WGM, WGN, NB>(g2, blockIdx.x - first_blocks, smem);
+    gemm_bf16_tile<MODE2, EPI2, false, false, BM, BN, BK2, WGM, WGN, NB2>(g2, blockIdx.x - first_blocks, smem);
 }
 
 inline unsigned gemm_bf16_grid(long long tiles) { return (unsigned)(tiles > 0 ? tiles : 1); }

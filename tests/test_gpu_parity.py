@@ -41,7 +41,7 @@ CASES = {
     "e100_k6": W["cfg1"].scaled(T=77, d=128, f=64, E=100, k=6),
     # d_ff long enough for split-K of the smallest row tiles: only such tiles / a full tile plus a small rest
     "split_k_tiny": W["cfg1"].scaled(T=40, d=128, f=2048, E=4, k=2),
-    "split_k_mixed": W["cfg1"].scaled(T=620, d=128, f=2304, E=4, k=2),
+    "split_k_mixed": W["cfg1"].scaled(T=620, d=128, f=2560, E=4, k=2),
 }
 
 
