@@ -24,7 +24,9 @@ __device__ __forceinline__ int live_row(int a, const int32_t* __restrict__ topk_
   return (pos >= l && pos < h) ? row : -1;
 }
 
-template <typename T>
+// KMAX: compile-time bound on k (2, 4 or 8); CU: column chunks of 16 bytes per lane kept in flight
+// (k * CU loads are issued before anything is used).  y_perm is read once: non-temporal loads.
+template <typename T, int KMAX, int CU>
 __global__ __launch_bounds__(CB_THREADS) void combine_kernel(
     const T* __restrict__ y_perm, const float* __restrict__ topk_w, const int32_t* __restrict__ topk_idx,
     const int32_t* __restrict__ row_of, const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept,
@@ -34,10 +36,10 @@ __global__ __launch_bounds__(CB_THREADS) void combine_kernel(
   const int lane = threadIdx.x & (WAVE - 1);
   const int t = (blockIdx.x * CB_THREADS + threadIdx.x) / WAVE;
   if (t >= Tn) return;
-  int rows[MOE_MAX_K];
-  float wj[MOE_MAX_K];
+  int rows[KMAX];
+  float wj[KMAX];
 #pragma unroll
-  for (int j = 0; j < MOE_MAX_K; ++j) {
+  for (int j = 0; j < KMAX; ++j) {
     rows[j] = -1;
     wj[j] = 0.f;
     if (j < k) {
@@ -45,35 +47,44 @@ __global__ __launch_bounds__(CB_THREADS) void combine_kernel(
       wj[j] = (topk_w != nullptr) ? topk_w[(size_t)t * k + j] : 1.f;
     }
   }
-  for (int c = lane * VN; c < d; c += WAVE * VN) {
-    Vec16<T> v[MOE_MAX_K];
+  for (int c0 = lane * VN; c0 < d; c0 += WAVE * VN * CU) {
+    Vec16<T> v[KMAX][CU];
 #pragma unroll
-    for (int j = 0; j < MOE_MAX_K; ++j)
-      if (rows[j] >= 0) v[j].load(y_perm + (size_t)rows[j] * d + c);
-    float acc[VN];
-    if (accumulate) {
-      Vec16<T> o;
-      o.load(out + (size_t)t * d + c);
-      o.unpack(acc);
-    } else {
-#pragma unroll
-      for (int i = 0; i < VN; ++i) acc[i] = 0.f;
-    }
-#pragma unroll
-    for (int j = 0; j < MOE_MAX_K; ++j)
+    for (int j = 0; j < KMAX; ++j)
       if (rows[j] >= 0) {
-        float f[VN];
-        v[j].unpack(f);
 #pragma unroll
-        for (int i = 0; i < VN; ++i) acc[i] = fmaf(wj[j], f[i], acc[i]);
+        for (int u = 0; u < CU; ++u)
+          if (c0 + u * WAVE * VN < d) v[j][u].load_nt(y_perm + (size_t)rows[j] * d + c0 + u * WAVE * VN);
       }
-    Vec16<T> o;
-    o.pack(acc);
-    o.store(out + (size_t)t * d + c);
+#pragma unroll
+    for (int u = 0; u < CU; ++u) {
+      const int c = c0 + u * WAVE * VN;
+      if (c >= d) break;
+      float acc[VN];
+      if (accumulate) {
+        Vec16<T> o;
+        o.load(out + (size_t)t * d + c);
+        o.unpack(acc);
+      } else {
+#pragma unroll
+        for (int i = 0; i < VN; ++i) acc[i] = 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < KMAX; ++j)     // fixed slot order: the sum is deterministic
+        if (rows[j] >= 0) {
+          float f[VN];
+          v[j][u].unpack(f);
+#pragma unroll
+          for (int i = 0; i < VN; ++i) acc[i] = fmaf(wj[j], f[i], acc[i]);
+        }
+      Vec16<T> o;
+      o.pack(acc);
+      o.store(out + (size_t)t * d + c);
+    }
   }
 }
 
-template <typename T>
+template <typename T, int KMAX, int CU>
 __global__ __launch_bounds__(CB_THREADS) void combine_bwd_kernel(
     const T* __restrict__ d_out, const T* __restrict__ y_perm, const float* __restrict__ topk_w,
     const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ row_of, const int32_t* __restrict__ offsets,
@@ -83,10 +94,10 @@ __global__ __launch_bounds__(CB_THREADS) void combine_bwd_kernel(
   const int lane = threadIdx.x & (WAVE - 1);
   const int t = (blockIdx.x * CB_THREADS + threadIdx.x) / WAVE;
   if (t >= Tn) return;
-  int rows[MOE_MAX_K];
-  float wj[MOE_MAX_K], dot[MOE_MAX_K];
+  int rows[KMAX];
+  float wj[KMAX], dot[KMAX];
 #pragma unroll
-  for (int j = 0; j < MOE_MAX_K; ++j) {
+  for (int j = 0; j < KMAX; ++j) {
     rows[j] = -1;
     wj[j] = 0.f;
     dot[j] = 0.f;
@@ -95,28 +106,39 @@ __global__ __launch_bounds__(CB_THREADS) void combine_bwd_kernel(
       wj[j] = topk_w[(size_t)t * k + j];
     }
   }
-  for (int c = lane * VN; c < d; c += WAVE * VN) {
-    Vec16<T> g, v[MOE_MAX_K];
-    g.load(d_out + (size_t)t * d + c);
+  for (int c0 = lane * VN; c0 < d; c0 += WAVE * VN * CU) {
+    Vec16<T> g[CU], v[KMAX][CU];
 #pragma unroll
-    for (int j = 0; j < MOE_MAX_K; ++j)
-      if (rows[j] >= 0) v[j].load(y_perm + (size_t)rows[j] * d + c);
-    float gf[VN];
-    g.unpack(gf);
+    for (int u = 0; u < CU; ++u)
+      if (c0 + u * WAVE * VN < d) g[u].load_nt(d_out + (size_t)t * d + c0 + u * WAVE * VN);
 #pragma unroll
-    for (int j = 0; j < MOE_MAX_K; ++j)
+    for (int j = 0; j < KMAX; ++j)
       if (rows[j] >= 0) {
-        float f[VN], o[VN];
-        v[j].unpack(f);
 #pragma unroll
-        for (int i = 0; i < VN; ++i) { dot[j] = fmaf(gf[i], f[i], dot[j]); o[i] = wj[j] * gf[i]; }
-        Vec16<T> ov;
-        ov.pack(o);
-        ov.store(dy_perm + (size_t)rows[j] * d + c);
+        for (int u = 0; u < CU; ++u)
+          if (c0 + u * WAVE * VN < d) v[j][u].load_nt(y_perm + (size_t)rows[j] * d + c0 + u * WAVE * VN);
       }
+#pragma unroll
+    for (int u = 0; u < CU; ++u) {
+      const int c = c0 + u * WAVE * VN;
+      if (c >= d) break;
+      float gf[VN];
+      g[u].unpack(gf);
+#pragma unroll
+      for (int j = 0; j < KMAX; ++j)
+        if (rows[j] >= 0) {
+          float f[VN], o[VN];
+          v[j][u].unpack(f);
+#pragma unroll
+          for (int i = 0; i < VN; ++i) { dot[j] = fmaf(gf[i], f[i], dot[j]); o[i] = wj[j] * gf[i]; }
+          Vec16<T> ov;
+          ov.pack(o);
+          ov.store_nt(dy_perm + (size_t)rows[j] * d + c);
+        }
+    }
   }
 #pragma unroll
-  for (int j = 0; j < MOE_MAX_K; ++j)
+  for (int j = 0; j < KMAX; ++j)
     if (j < k) {
       const float s = wave_sum(dot[j]);
       if (lane == 0) d_topk_w[(size_t)t * k + j] = (rows[j] >= 0) ? s : 0.f;
@@ -127,10 +149,11 @@ int launch_combine(const moe_cfg* c, const void* y_perm, const float* w, const i
                    const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, void* out,
                    int accumulate, hipStream_t s) {
   const int grid = (c->T + CB_THREADS / WAVE - 1) / (CB_THREADS / WAVE);
-  if (c->dtype == MOE_DTYPE_BF16)
-    combine_kernel<bf16><<<grid, CB_THREADS, 0, s>>>((const bf16*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (bf16*)out, c->T, c->d_model, c->k, accumulate);
-  else
-    combine_kernel<float><<<grid, CB_THREADS, 0, s>>>((const float*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (float*)out, c->T, c->d_model, c->k, accumulate);
+#define MOE_COMBINE(TY, KM, CU) \
+  combine_kernel<TY, KM, CU><<<grid, CB_THREADS, 0, s>>>((const TY*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (TY*)out, c->T, c->d_model, c->k, accumulate)
+  if (c->dtype == MOE_DTYPE_BF16) { if (c->k <= 2) MOE_COMBINE(bf16, 2, 4); else if (c->k <= 4) MOE_COMBINE(bf16, 4, 2); else MOE_COMBINE(bf16, 8, 1); }
+  else { if (c->k <= 2) MOE_COMBINE(float, 2, 4); else if (c->k <= 4) MOE_COMBINE(float, 4, 2); else MOE_COMBINE(float, 8, 1); }
+#undef MOE_COMBINE
   return launch_status();
 }
 
@@ -138,10 +161,11 @@ int launch_combine_bwd(const moe_cfg* c, const void* d_out, const void* y_perm, 
                        const int32_t* row_of, const int32_t* offsets, const int32_t* kept, const int32_t* lo,
                        const int32_t* hi, void* dy_perm, float* dw, hipStream_t s) {
   const int grid = (c->T + CB_THREADS / WAVE - 1) / (CB_THREADS / WAVE);
-  if (c->dtype == MOE_DTYPE_BF16)
-    combine_bwd_kernel<bf16><<<grid, CB_THREADS, 0, s>>>((const bf16*)d_out, (const bf16*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (bf16*)dy_perm, dw, c->T, c->d_model, c->k);
-  else
-    combine_bwd_kernel<float><<<grid, CB_THREADS, 0, s>>>((const float*)d_out, (const float*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (float*)dy_perm, dw, c->T, c->d_model, c->k);
+#define MOE_COMBINE_BWD(TY, KM, CU) \
+  combine_bwd_kernel<TY, KM, CU><<<grid, CB_THREADS, 0, s>>>((const TY*)d_out, (const TY*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (TY*)dy_perm, dw, c->T, c->d_model, c->k)
+  if (c->dtype == MOE_DTYPE_BF16) { if (c->k <= 2) MOE_COMBINE_BWD(bf16, 2, 4); else if (c->k <= 4) MOE_COMBINE_BWD(bf16, 4, 2); else MOE_COMBINE_BWD(bf16, 8, 1); }
+  else { if (c->k <= 2) MOE_COMBINE_BWD(float, 2, 4); else if (c->k <= 4) MOE_COMBINE_BWD(float, 4, 2); else MOE_COMBINE_BWD(float, 8, 1); }
+#undef MOE_COMBINE_BWD
   return launch_status();
 }
 

@@ -80,13 +80,24 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
-// 16-byte vector of activations: 4 fp32 or 8 bf16.
+// 16-byte vector of activations: 4 fp32 or 8 bf16.  load_nt / store_nt mark streaming traffic (data touched
+// once by the kernel) as non-temporal, which is what lets a plain copy reach the machine's HBM ceiling.
+typedef unsigned nt_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load16_nt(const void* p) {
+  const nt_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store16_nt(void* p, const uint4& r) {
+  __builtin_nontemporal_store(nt_u32x4{r.x, r.y, r.z, r.w}, reinterpret_cast<nt_u32x4*>(p));
+}
 template <typename T> struct Vec16;
 template <> struct Vec16<float> {
   static constexpr int N = 4;
   float4 raw;
   __device__ __forceinline__ void load(const float* p) { raw = *reinterpret_cast<const float4*>(p); }
   __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = raw; }
+  __device__ __forceinline__ void load_nt(const float* p) { const uint4 u = load16_nt(p); raw = make_float4(__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w)); }
+  __device__ __forceinline__ void store_nt(float* p) const { store16_nt(p, make_uint4(__float_as_uint(raw.x), __float_as_uint(raw.y), __float_as_uint(raw.z), __float_as_uint(raw.w))); }
   __device__ __forceinline__ void unpack(float* f) const { f[0] = raw.x; f[1] = raw.y; f[2] = raw.z; f[3] = raw.w; }
   __device__ __forceinline__ void pack(const float* f) { raw = make_float4(f[0], f[1], f[2], f[3]); }
 };
@@ -95,6 +106,8 @@ template <> struct Vec16<bf16> {
   uint4 raw;
   __device__ __forceinline__ void load(const bf16* p) { raw = *reinterpret_cast<const uint4*>(p); }
   __device__ __forceinline__ void store(bf16* p) const { *reinterpret_cast<uint4*>(p) = raw; }
+  __device__ __forceinline__ void load_nt(const bf16* p) { raw = load16_nt(p); }
+  __device__ __forceinline__ void store_nt(bf16* p) const { store16_nt(p, raw); }
   __device__ __forceinline__ void unpack(float* f) const {
     const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll

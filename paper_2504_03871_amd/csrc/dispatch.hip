@@ -138,47 +138,55 @@ __global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
   }
 }
 
-// x_perm[row] = x[src_of[row] / k] for the rows inside this GPU's shares.  A wave copies GR rows at a
-// time (their index look-ups and 16-byte loads are all issued before the first store).
-constexpr int GR = 4;
-template <typename T>
+// x_perm[row_of[t*k+j]] = x[t] for the slots that are kept and inside this GPU's shares.  Token-major: a wave
+// owns a token, reads its row once (16 bytes per lane, GU column chunks in flight) and writes it to the rows
+// of its live slots, so the read traffic is the T*d elements the algorithm needs however large k is.  Every
+// in-share row belongs to exactly one slot, so all of them are written and no other row is touched.
+// The stores are non-temporal (x_perm is far larger than the caches and is read next by another kernel).
+constexpr int GU = 4;
+template <typename T, int KMAX>
 __global__ __launch_bounds__(256) void dispatch_gather_kernel(
-    const T* __restrict__ x, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ src_of,
+    const T* __restrict__ x, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ row_of,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept, const int32_t* __restrict__ lo,
-    const int32_t* __restrict__ hi, T* __restrict__ x_perm, int A, int d, int E, int k) {
+    const int32_t* __restrict__ hi, T* __restrict__ x_perm, int Tn, int d, int k) {
   constexpr int VN = Vec16<T>::N;
   const int lane = threadIdx.x & (WAVE - 1);
-  const int wave_global = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
-  const int nwaves = gridDim.x * blockDim.x / WAVE;
-  const int R = offsets[E];
-  for (int base = wave_global * GR; base < R; base += nwaves * GR) {
-    int tok[GR];
+  const int t = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+  if (t >= Tn) return;
+  int rows[KMAX];
+  bool any = false;
 #pragma unroll
-    for (int u = 0; u < GR; ++u) {
-      const int row = base + u;
-      tok[u] = -1;
-      if (row < R) {
-        const int a = src_of[row];
+  for (int j = 0; j < KMAX; ++j) {
+    rows[j] = -1;
+    if (j < k) {
+      const int a = t * k + j, row = row_of[a];
+      if (row >= 0) {
         bool mine = true;
-        if (lo != nullptr) {   // with no shares given every row below offsets[E] is ours: skip the expert lookup
+        if (lo != nullptr) {   // with no shares given every kept row is ours: skip the expert lookup
           const int e = topk_idx[a];
           int l, h;
           share_of(lo, hi, kept[e], e, l, h);
           const int pos = row - offsets[e];
           mine = pos >= l && pos < h;
         }
-        if (mine) tok[u] = a / k;
+        if (mine) { rows[j] = row; any = true; }
       }
     }
-    for (int c = lane * VN; c < d; c += WAVE * VN) {
-      Vec16<T> v[GR];
+  }
+  if (!any) return;
+  const T* src = x + (size_t)t * d;
+  for (int c0 = lane * VN; c0 < d; c0 += WAVE * VN * GU) {
+    Vec16<T> v[GU];
 #pragma unroll
-      for (int u = 0; u < GR; ++u)
-        if (tok[u] >= 0) v[u].load(x + (size_t)tok[u] * d + c);
+    for (int u = 0; u < GU; ++u)
+      if (c0 + u * WAVE * VN < d) v[u].load_nt(src + c0 + u * WAVE * VN);
 #pragma unroll
-      for (int u = 0; u < GR; ++u)
-        if (tok[u] >= 0) v[u].store(x_perm + (size_t)(base + u) * d + c);
-    }
+    for (int j = 0; j < KMAX; ++j)
+      if (rows[j] >= 0) {
+#pragma unroll
+        for (int u = 0; u < GU; ++u)
+          if (c0 + u * WAVE * VN < d) v[u].store_nt(x_perm + (size_t)rows[j] * d + c0 + u * WAVE * VN);
+      }
   }
 }
 
@@ -234,12 +242,12 @@ int launch_dispatch(const moe_cfg* c, const void* x, const int32_t* idx, const i
   rc = launch_status();
   if (rc != MOE_OK || x_perm == nullptr || A == 0) return rc;
   ProfScope ps(c, MOE_PROF_GATHER, s);
-  const int waves_per_block = 256 / WAVE;
-  const int grid = min((A + waves_per_block * GR - 1) / (waves_per_block * GR), 256 * 32);
-  if (c->dtype == MOE_DTYPE_BF16)
-    dispatch_gather_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)x, idx, src_of, offsets, kept, lo, hi, (bf16*)x_perm, A, c->d_model, c->E, c->k);
-  else
-    dispatch_gather_kernel<float><<<grid, 256, 0, s>>>((const float*)x, idx, src_of, offsets, kept, lo, hi, (float*)x_perm, A, c->d_model, c->E, c->k);
+  const int grid = (c->T + 256 / WAVE - 1) / (256 / WAVE);
+#define MOE_GATHER(TY, KM) \
+  dispatch_gather_kernel<TY, KM><<<grid, 256, 0, s>>>((const TY*)x, idx, row_of, offsets, kept, lo, hi, (TY*)x_perm, c->T, c->d_model, c->k)
+  if (c->dtype == MOE_DTYPE_BF16) { if (c->k <= 2) MOE_GATHER(bf16, 2); else if (c->k <= 4) MOE_GATHER(bf16, 4); else MOE_GATHER(bf16, 8); }
+  else { if (c->k <= 2) MOE_GATHER(float, 2); else if (c->k <= 4) MOE_GATHER(float, 4); else MOE_GATHER(float, 8); }
+#undef MOE_GATHER
   return launch_status();
 }
 

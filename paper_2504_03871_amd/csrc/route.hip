@@ -236,11 +236,13 @@ __global__ void wr_frag_kernel(const float* __restrict__ Wr, rt_bf16x8* __restri
   wfrag[u] = v;
 }
 
-template <int NTL>
-__global__ __launch_bounds__(256) void route_mfma_kernel(
+// NW waves per block split K (more waves in flight per compute unit when the token count alone gives too few
+// blocks to cover the memory latency).
+template <int NTL, int NW>
+__global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
     const bf16* __restrict__ x, const rt_bf16x8* __restrict__ wfrag, const float* __restrict__ bias,
     float* __restrict__ logits_out, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d, int E, int k) {
-  extern __shared__ float part[];   // [4 waves][32 tokens][LD]; the sum ends up in part[0]
+  extern __shared__ float part[];   // [NW waves][32 tokens][LD]; the sum ends up in part[0]
   constexpr int LD = NTL * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tok0 = blockIdx.x * RM_TOK, nkb = d / 64;
@@ -267,13 +269,13 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(
       for (int q = 0; q < 8; ++q) { b[q] = wfrag[((size_t)kb0 * 8 + q) * 64 + lane]; bn[q] = b[q]; }
     }
   }
-  for (int kb = wave; kb < nkb; kb += 4) {
-    if (kb + 4 < nkb) {
+  for (int kb = wave; kb < nkb; kb += NW) {
+    if (kb + NW < nkb) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s) an[s] = *reinterpret_cast<const rt_bf16x8*>(xrow + (size_t)(kb + 4) * 64 + s * 8);
+      for (int s = 0; s < 4; ++s) an[s] = *reinterpret_cast<const rt_bf16x8*>(xrow + (size_t)(kb + NW) * 64 + s * 8);
       if constexpr (PFB) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) bn[q] = wfrag[((size_t)(kb + 4) * 8 + q) * 64 + lane];
+        for (int q = 0; q < 8; ++q) bn[q] = wfrag[((size_t)(kb + NW) * 8 + q) * 64 + lane];
       }
     }
 #pragma unroll
@@ -299,14 +301,16 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(
 #pragma unroll
     for (int v = 0; v < 16; ++v) mine[((v >> 2) * 8 + h * 4 + (v & 3)) * LD + nt * 32 + r] = acc[nt][v];
   __syncthreads();
-  for (int i = tid; i < RM_TOK * LD; i += 256) {
+  for (int i = tid; i < RM_TOK * LD; i += NW * 64) {
     const int e = i % LD;
-    const float sum = ((part[i] + part[RM_TOK * LD + i]) + part[2 * RM_TOK * LD + i]) + part[3 * RM_TOK * LD + i];
+    float sum = part[i];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) sum += part[w * RM_TOK * LD + i];   // wave order: deterministic
     part[i] = sum + ((bias != nullptr && e < E) ? bias[e] : 0.f);
   }
   __syncthreads();
   const int ntok = min(RM_TOK, Tn - tok0);
-  for (int i = tid; i < ntok * E; i += 256) logits_out[(size_t)tok0 * E + i] = part[(i / E) * LD + i % E];
+  for (int i = tid; i < ntok * E; i += NW * 64) logits_out[(size_t)tok0 * E + i] = part[(i / E) * LD + i % E];
   const int tl = tid >> 3;   // eight lanes per token
   route_select(part, LD, tl, tid & 7, 8, tl < ntok, tok0 + tl, E, k, topk_idx, topk_w);
 }
@@ -529,20 +533,20 @@ size_t route_wfrag_bytes(int d, int E) {
   return (size_t)ntl * ((d + 63) / 64) * 8 * 64 * 16;
 }
 
-template <int NTL>
+template <int NTL, int NW>
 static int launch_route_mfma(const moe_cfg* c, const void* x, const float* Wr, const float* bias, float* logits_out,
                              int32_t* idx, float* w, void* wfrag, hipStream_t s) {
   const int nkb = c->d_model / 64, units = NTL * nkb * 8 * 64;
   wr_frag_kernel<<<(units + 255) / 256, 256, 0, s>>>(Wr, (rt_bf16x8*)wfrag, c->d_model, c->E, nkb, NTL);
   int rc = launch_status();
   if (rc != MOE_OK) return rc;
-  const size_t lds = (size_t)4 * RM_TOK * NTL * 32 * 4;
-  auto kern = route_mfma_kernel<NTL>;
+  const size_t lds = (size_t)NW * RM_TOK * NTL * 32 * 4;
+  auto kern = route_mfma_kernel<NTL, NW>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return set_hip_error(e);
   }
-  kern<<<(c->T + RM_TOK - 1) / RM_TOK, 256, lds, s>>>((const bf16*)x, (const rt_bf16x8*)wfrag, bias, logits_out, idx, w,
+  kern<<<(c->T + RM_TOK - 1) / RM_TOK, NW * 64, lds, s>>>((const bf16*)x, (const rt_bf16x8*)wfrag, bias, logits_out, idx, w,
                                                      c->T, c->d_model, c->E, c->k);
   return launch_status();
 }
@@ -551,10 +555,14 @@ static int launch_route_mfma(const moe_cfg* c, const void* x, const float* Wr, c
 int launch_route(const moe_cfg* c, const void* x, const float* Wr, const float* bias, const float* logits_in,
                  float* logits_out, int32_t* idx, float* w, void* wfrag, hipStream_t s) {
   if (c->dtype == MOE_DTYPE_BF16 && logits_in == nullptr) {
-    if (c->E <= 32) return launch_route_mfma<1>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-    if (c->E <= 64) return launch_route_mfma<2>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-    if (c->E <= 128) return launch_route_mfma<4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-    return launch_route_mfma<8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    // long rows and few expert tiles: eight waves per block (a block per 32 tokens leaves only T / 32 blocks)
+    const bool wide = c->d_model >= 2048;
+    if (c->E <= 32) return wide ? launch_route_mfma<1, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
+                                : launch_route_mfma<1, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    if (c->E <= 64) return wide ? launch_route_mfma<2, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
+                                : launch_route_mfma<2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    if (c->E <= 128) return launch_route_mfma<4, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    return launch_route_mfma<8, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
   }
   const RouteGeom gm = route_geom(c->E);
   const int grid = (c->T + gm.tok - 1) / gm.tok;
