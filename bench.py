@@ -118,7 +118,7 @@ def gemm_flops(w, S_rows, S, present):
     unit = 2 * S_rows * w.d * w.f
     flops = {"gemm1_fwd": unit * (2 if swi else 1), "gemm2_fwd": unit, "dh_bwd": unit, "dw2_bwd": unit,
              "dw1_bwd": unit * (2 if swi else 1), "dx_bwd": unit * (2 if swi else 1)}
-    if w.dtype == S.DT_BF16:
+    if w.dtype != S.DT_F32:
         # moe_expert_ffn_bwd: a row-tile GEMM of at most 2048 tiles shares its launch with the weight-gradient
         # GEMM after it, and the shared launch is bracketed under the row-tile GEMM
         max_tiles = (w.T * w.k + 255) // 256 + w.E
@@ -139,8 +139,10 @@ def run_workload(name, steps, warmup, args, full):
     from paper_2504_03871_amd.layer import MoELayer
 
     w = S.WORKLOADS[name]
+    if args.f16 and w.dtype == S.DT_BF16:
+        w = w.scaled(dtype=S.DT_F16)
     inp = S.make_inputs(w, threads=16)
-    bf = w.dtype == S.DT_BF16
+    bf = w.dtype != S.DT_F32      # 16-bit storage: the MFMA path
     dev = "cuda:0"
     L = MoELayer(w.T, w.d, w.f, w.E, w.k, dtype=w.dtype, act=w.act, capacity=w.capacity, device=dev)
     if args.overlap_gate_bwd:
@@ -148,7 +150,7 @@ def run_workload(name, steps, warmup, args, full):
 
     def up(nm):
         if bf:
-            return torch.from_numpy(inp[nm + "_bits"].view(np.int16)).to(dev).view(torch.bfloat16)
+            return torch.from_numpy(inp[nm + "_bits"].view(np.int16)).to(dev).view(torch.float16 if w.dtype == S.DT_F16 else torch.bfloat16)
         return torch.from_numpy(inp[nm]).to(dev)
 
     for nm in ("x", "W1", "W2", "d_out") + (("W1b",) if w.act == S.ACT_SWIGLU else ()):
@@ -215,7 +217,7 @@ def run_workload(name, steps, warmup, args, full):
                 f"{'SwiGLU' if swi else 'GELU'} rows_computed={S_rows}"
                 + (", activation checkpointing (gate, dispatch, GEMM1 repeated)" if args.checkpoint else ""))
     res = {"w": w, "inp": inp, "S_rows": S_rows, "ms_per_step": ms_per_step, "all_gemms": all_gemms, "workload": workload,
-           "dtype": "bf16" if bf else "f32"}
+           "dtype": {S.DT_BF16: "bf16", S.DT_F16: "f16"}.get(w.dtype, "f32")}
     if not full:
         del L
         torch.cuda.empty_cache()
@@ -354,6 +356,8 @@ def main():
     ap.add_argument("--checkpoint", action="store_true",
                     help="time the step of an activation-checkpointed layer: gate, dispatch and the saved "
                          "activations are computed again before the backward (not the default metric)")
+    ap.add_argument("--f16", action="store_true",
+                    help="run the bf16 workloads with fp16 storage instead (the paper's FP16 mixed precision; not the default metric)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB copy with the library's streaming kernel three times "
                          "(calibrates rocprofv3 byte counters)")

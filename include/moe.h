@@ -18,8 +18,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is enqueued on
  *     it; no call synchronises with the host and none reads device memory from the host.
  *   - Activations (x, x_perm, y_perm, saved, d_out, dy_perm, dx_perm, out, dx) and expert weights
- *     (W1, W1b, W2) have the storage type cfg->dtype: fp32, or bf16 (round-to-nearest-even) with
- *     fp32 accumulation.  Router tensors (Wr, bias, logits, topk_w, d_topk_w, d_logits, dWr) and
+ *     (W1, W1b, W2) have the storage type cfg->dtype: fp32, or bf16 or fp16 (round-to-nearest-even; the
+ *     paper trains in FP16 mixed precision, Section 6.1) with fp32 accumulation on the matrix cores.  Router tensors (Wr, bias, logits, topk_w, d_topk_w, d_logits, dWr) and
  *     expert weight gradients (dW1, dW1b, dW2) are always fp32.  Index tensors are int32.
  *   - All matrices are dense row-major: x[T][d_model], W1[E][d_model][d_ff], W2[E][d_ff][d_model],
  *     Wr[d_model][E], topk_*[T][k], permuted buffers [T*k][...].
@@ -32,7 +32,7 @@
  *     inverted range is empty.  Rows of permuted buffers outside the shares are never read for a
  *     result and never written.
  *   - Shapes: 1 <= k <= min(E, MOE_MAX_K), E <= MOE_MAX_E, T >= 0 (T = 0 is a no-op),
- *     T*k <= 2^30.  bf16: d_model and d_ff multiples of 64; fp32: multiples of 4.  The kernels address
+ *     T*k <= 2^30.  bf16 / fp16: d_model and d_ff multiples of 64; fp32: multiples of 4.  The kernels address
  *     one operand through 32-bit byte offsets, so T*k * max(d_model, d_ff) * (bytes per element) and
  *     d_model * d_ff * 4 must both stay below 2^32 (MOE_ERR_BAD_SHAPE otherwise).
  *   - `ws` is the caller's device workspace and `ws_bytes` its size; a call that uses it returns
@@ -56,7 +56,7 @@ extern "C" {
 #define MOE_MAX_E 256
 #define MOE_MAX_K 8
 
-enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
+enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1, MOE_DTYPE_F16 = 2 };
 enum { MOE_ACT_GELU = 0, MOE_ACT_SWIGLU = 1 };
 
 enum {
@@ -129,7 +129,7 @@ MOE_API int moe_saved_bytes(const moe_cfg* cfg, size_t* bytes);
  * bias[E] may be NULL.  logits_out may be NULL only when logits_in is given.
  * bf16: the product runs on the matrix cores with the fp32 gate weight split into two bf16 terms
  * (about 16 mantissa bits); ws (moe_workspace_bytes, device) holds the re-laid-out weight and is
- * required unless logits_in is given.  fp32: plain fp32 FMAs, ws may be NULL.
+ * required unless logits_in is given.  fp32 and fp16: plain fp32 FMAs on the stored values, ws may be NULL.
  */
 MOE_API int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* bias,
               const float* logits_in, float* logits_out, int32_t* topk_idx, float* topk_w,

@@ -14,12 +14,12 @@ int set_hip_error(hipError_t e) {
 
 int check_cfg(const moe_cfg* c) {
   if (c == nullptr) return MOE_ERR_NULL;
-  if (c->dtype != MOE_DTYPE_F32 && c->dtype != MOE_DTYPE_BF16) return MOE_ERR_BAD_DTYPE;
+  if (c->dtype != MOE_DTYPE_F32 && c->dtype != MOE_DTYPE_BF16 && c->dtype != MOE_DTYPE_F16) return MOE_ERR_BAD_DTYPE;
   if (c->act != MOE_ACT_GELU && c->act != MOE_ACT_SWIGLU) return MOE_ERR_BAD_DTYPE;
   if (c->T < 0 || c->d_model <= 0 || c->d_ff <= 0) return MOE_ERR_BAD_SHAPE;
   if (c->E < 1 || c->E > MOE_MAX_E) return MOE_ERR_BAD_SHAPE;
   if (c->k < 1 || c->k > MOE_MAX_K || c->k > c->E) return MOE_ERR_BAD_SHAPE;
-  const int mult = (c->dtype == MOE_DTYPE_BF16) ? 64 : 4;
+  const int mult = is_half(c) ? 64 : 4;
   if (c->d_model % mult != 0 || c->d_ff % mult != 0) return MOE_ERR_BAD_SHAPE;
   if ((long long)c->T * c->k > (1ll << 30)) return MOE_ERR_BAD_SHAPE;
   if (!offsets_fit_32_bits(c->T, c->k, c->d_model, c->d_ff, (int)elt_size(c))) return MOE_ERR_BAD_SHAPE;
@@ -43,7 +43,7 @@ WsLayout ws_layout(const moe_cfg* c) {
   w.route_wrt = off;   // shared with the forward's gate weight in MFMA operand layout (never live together)
   off += align_up(std::max((size_t)c->d_model * c->E * 4, route_wfrag_bytes(c->d_model, c->E)), 256);
   w.ffn_split = off;
-  if (c->dtype == MOE_DTYPE_BF16 && split_k_applies(c->E, c->d_ff))
+  if (is_half(c) && split_k_applies(c->E, c->d_ff))
     off += align_up(split_ws_bytes(c->E, std::max(c->d_model, 1)), 256);
   w.ffn_bwd_dact = off;
   off += align_up((c->act == MOE_ACT_SWIGLU ? 2 : 1) * A * c->d_ff * elt_size(c), 256);
@@ -97,10 +97,10 @@ static int check_slices(const int32_t* lo, const int32_t* hi) {
 
 static int launch_gemm(const moe_cfg* c, int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles,
                        hipStream_t s) {
-  return c->dtype == MOE_DTYPE_BF16 ? launch_gemm_bf16(mode, epi, dual, chain, g, max_tiles, s)
-                                    : launch_gemm_f32(mode, epi, dual, chain, g, max_tiles, s);
+  return is_half(c) ? launch_gemm_half(c->dtype, mode, epi, dual, chain, g, max_tiles, s)
+                    : launch_gemm_f32(mode, epi, dual, chain, g, max_tiles, s);
 }
-static int tile_rows_for(const moe_cfg* c) { return c->dtype == MOE_DTYPE_BF16 ? gemm_bf16_tile_rows() : 64; }
+static int tile_rows_for(const moe_cfg* c) { return is_half(c) ? gemm_bf16_tile_rows() : 64; }
 
 }  // namespace moe
 
@@ -161,7 +161,7 @@ int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* b
               float* logits_out, int32_t* topk_idx, float* topk_w, void* ws, size_t ws_bytes, void* stream) {
   CHECK(check_cfg(cfg));
   if (logits_in == nullptr) { REQUIRE(x); REQUIRE(Wr); REQUIRE(logits_out); }
-  if (logits_in == nullptr && cfg->dtype == MOE_DTYPE_BF16) REQUIRE(ws);
+  if (logits_in == nullptr && cfg->dtype == MOE_DTYPE_BF16) REQUIRE(ws);   // the matrix-core gate (bf16 only)
   REQUIRE(topk_idx);
   REQUIRE(topk_w);
   ALIGNED(x); ALIGNED(Wr); ALIGNED(bias); ALIGNED(logits_in); ALIGNED(logits_out); ALIGNED(topk_idx); ALIGNED(topk_w);
@@ -237,7 +237,7 @@ int ffn_fwd_impl(const moe_cfg* cfg, const void* x_perm, const void* W1, const v
   // y = hidden W2
   g.A = swiglu ? sv + 2 * plane : sv + plane; g.B = W2; g.B2 = nullptr; g.N = d; g.K = f;
   g.C = y_perm; g.C2 = g.C3 = nullptr;
-  if (cfg->dtype == MOE_DTYPE_BF16 && split_k_applies(cfg->E, f))   // smallest row tiles: split-K (gemm.h)
+  if (is_half(cfg) && split_k_applies(cfg->E, f))   // smallest row tiles: split-K (gemm.h)
     g.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ffn_split);
   ProfScope ps(cfg, MOE_PROF_GEMM2_FWD, s);
   return launch_gemm(cfg, MODE_NN, EPI_STORE, false, false, g, max_tiles, s);
@@ -350,13 +350,13 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
   // follows it (dH with dW2, dx with dW1), whose tiles then start on the compute units that its last,
   // partly filled round leaves idle.  With many rounds that idle share is small and separate launches
   // keep the cache to one GEMM at a time.  (Timing brackets: a shared launch counts under the row-tile GEMM.)
-  const bool bf = cfg->dtype == MOE_DTYPE_BF16;
+  const bool bf = is_half(cfg);
   const long long few = 8ll * 256;   // tiles: about eight rounds on this chip
   const bool pair_h = bf && (long long)((f + tr - 1) / tr) * max_tiles <= few;
   const bool pair_x = bf && (long long)((d + tr - 1) / tr) * max_tiles <= few;
   {
     ProfScope ps(cfg, MOE_PROF_DH_BWD, s);
-    if (pair_h) CHECK(launch_gemm_bf16_pair(epi_h, false, gh, max_tiles, gw2, s));
+    if (pair_h) CHECK(launch_gemm_half_pair(cfg->dtype, epi_h, false, gh, max_tiles, gw2, s));
     else CHECK(launch_gemm(cfg, MODE_NT, epi_h, false, false, gh, max_tiles, s));
   }
   if (!pair_h) {
@@ -375,7 +375,7 @@ int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const void* x_pe
   ProfScope ps(cfg, MOE_PROF_DX_BWD, s);
   if (bf && !swiglu && split_k_applies(cfg->E, f))   // the smallest row tiles of the GELU dx use split-K (gemm.h)
     gx.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ffn_split);
-  if (pair_x) return launch_gemm_bf16_pair(EPI_STORE, swiglu, gx, max_tiles, gw1, s);
+  if (pair_x) return launch_gemm_half_pair(cfg->dtype, EPI_STORE, swiglu, gx, max_tiles, gw1, s);
   return launch_gemm(cfg, MODE_NT, EPI_STORE, false, swiglu, gx, max_tiles, s);
 }
 

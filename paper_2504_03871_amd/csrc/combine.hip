@@ -152,6 +152,7 @@ int launch_combine(const moe_cfg* c, const void* y_perm, const float* w, const i
 #define MOE_COMBINE(TY, KM, CU) \
   combine_kernel<TY, KM, CU><<<grid, CB_THREADS, 0, s>>>((const TY*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (TY*)out, c->T, c->d_model, c->k, accumulate)
   if (c->dtype == MOE_DTYPE_BF16) { if (c->k <= 2) MOE_COMBINE(bf16, 2, 4); else if (c->k <= 4) MOE_COMBINE(bf16, 4, 2); else MOE_COMBINE(bf16, 8, 1); }
+  else if (c->dtype == MOE_DTYPE_F16) { if (c->k <= 2) MOE_COMBINE(f16, 2, 4); else if (c->k <= 4) MOE_COMBINE(f16, 4, 2); else MOE_COMBINE(f16, 8, 1); }
   else { if (c->k <= 2) MOE_COMBINE(float, 2, 4); else if (c->k <= 4) MOE_COMBINE(float, 4, 2); else MOE_COMBINE(float, 8, 1); }
 #undef MOE_COMBINE
   return launch_status();
@@ -164,6 +165,7 @@ int launch_combine_bwd(const moe_cfg* c, const void* d_out, const void* y_perm, 
 #define MOE_COMBINE_BWD(TY, KM, CU) \
   combine_bwd_kernel<TY, KM, CU><<<grid, CB_THREADS, 0, s>>>((const TY*)d_out, (const TY*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (TY*)dy_perm, dw, c->T, c->d_model, c->k)
   if (c->dtype == MOE_DTYPE_BF16) { if (c->k <= 2) MOE_COMBINE_BWD(bf16, 2, 4); else if (c->k <= 4) MOE_COMBINE_BWD(bf16, 4, 2); else MOE_COMBINE_BWD(bf16, 8, 1); }
+  else if (c->dtype == MOE_DTYPE_F16) { if (c->k <= 2) MOE_COMBINE_BWD(f16, 2, 4); else if (c->k <= 4) MOE_COMBINE_BWD(f16, 4, 2); else MOE_COMBINE_BWD(f16, 8, 1); }
   else { if (c->k <= 2) MOE_COMBINE_BWD(float, 2, 4); else if (c->k <= 4) MOE_COMBINE_BWD(float, 4, 2); else MOE_COMBINE_BWD(float, 8, 1); }
 #undef MOE_COMBINE_BWD
   return launch_status();

@@ -18,7 +18,8 @@ inline int launch_status() {
   return e == hipSuccess ? MOE_OK : set_hip_error(e);
 }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-inline size_t elt_size(const moe_cfg* c) { return c->dtype == MOE_DTYPE_BF16 ? 2 : 4; }
+inline size_t elt_size(const moe_cfg* c) { return c->dtype == MOE_DTYPE_F32 ? 4 : 2; }
+inline bool is_half(const moe_cfg* c) { return c->dtype != MOE_DTYPE_F32; }   // 16-bit storage: the MFMA kernels
 // The grouped GEMMs reach an operand through one buffer descriptor and a 32-bit byte offset per lane.  The
 // longest walks are an expert's whole share in the weight-gradient GEMM (rows x max(d, f) elements; one expert
 // may hold every assignment) and one expert's weight matrix (d x f elements; fp32 gradients are 4 bytes wide).
@@ -70,6 +71,7 @@ constexpr int TILE_ROWS_MIN = 64;      // smallest row-tile height any grouped G
 // ---------------------------------------------------------------- device side
 #ifdef __HIPCC__
 typedef __bf16 bf16;
+typedef _Float16 f16;
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
@@ -78,6 +80,17 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 }
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t b) {
+  const unsigned short h = (unsigned short)b;
+  return (float)(*reinterpret_cast<const f16*>(&h));
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
+  const f16 h = (f16)f;   // round to nearest even
+  return (uint32_t)(*reinterpret_cast<const unsigned short*>(&h));
+}
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+  return f32_to_f16_bits(lo) | (f32_to_f16_bits(hi) << 16);
 }
 
 // 16-byte vector of activations: 4 fp32 or 8 bf16.  load_nt / store_nt mark streaming traffic (data touched
@@ -118,11 +131,30 @@ template <> struct Vec16<bf16> {
   }
 };
 
+template <> struct Vec16<f16> {
+  static constexpr int N = 8;
+  uint4 raw;
+  __device__ __forceinline__ void load(const f16* p) { raw = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void store(f16* p) const { *reinterpret_cast<uint4*>(p) = raw; }
+  __device__ __forceinline__ void load_nt(const f16* p) { raw = load16_nt(p); }
+  __device__ __forceinline__ void store_nt(f16* p) const { store16_nt(p, raw); }
+  __device__ __forceinline__ void unpack(float* f) const {
+    const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[2 * i] = f16_bits_to_f32(u[i] & 0xffffu); f[2 * i + 1] = f16_bits_to_f32(u[i] >> 16); }
+  }
+  __device__ __forceinline__ void pack(const float* f) {
+    raw = make_uint4(pack_f16x2(f[0], f[1]), pack_f16x2(f[2], f[3]), pack_f16x2(f[4], f[5]), pack_f16x2(f[6], f[7]));
+  }
+};
+
 __device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(f16 v) { return (float)v; }
 __device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
+template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return (f16)v; }
 
 // This GPU's share [l, h) of expert e's kept list: clamped to [0, kept], inverted = empty.
 __device__ __forceinline__ void share_of(const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
@@ -144,6 +176,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // exact-erf GELU pieces, SiLU pieces (fp32)
 __device__ __forceinline__ float gelu_f(float a) { return 0.5f * a * erfcf(-a * 0.70710678118654752440f); }
+__device__ __forceinline__ float phi_f(float a) { return 0.5f * erfcf(-a * 0.70710678118654752440f); }
 __device__ __forceinline__ float gelu_grad_f(float a) {
   return 0.5f * erfcf(-a * 0.70710678118654752440f) + a * 0.39894228040143267794f * __expf(-0.5f * a * a);
 }

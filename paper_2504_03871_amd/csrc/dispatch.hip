@@ -246,6 +246,7 @@ int launch_dispatch(const moe_cfg* c, const void* x, const int32_t* idx, const i
 #define MOE_GATHER(TY, KM) \
   dispatch_gather_kernel<TY, KM><<<grid, 256, 0, s>>>((const TY*)x, idx, row_of, offsets, kept, lo, hi, (TY*)x_perm, c->T, c->d_model, c->k)
   if (c->dtype == MOE_DTYPE_BF16) { if (c->k <= 2) MOE_GATHER(bf16, 2); else if (c->k <= 4) MOE_GATHER(bf16, 4); else MOE_GATHER(bf16, 8); }
+  else if (c->dtype == MOE_DTYPE_F16) { if (c->k <= 2) MOE_GATHER(f16, 2); else if (c->k <= 4) MOE_GATHER(f16, 4); else MOE_GATHER(f16, 8); }
   else { if (c->k <= 2) MOE_GATHER(float, 2); else if (c->k <= 4) MOE_GATHER(float, 4); else MOE_GATHER(float, 8); }
 #undef MOE_GATHER
   return launch_status();

@@ -114,13 +114,11 @@ int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* 
 
 // fp32 storage, fp32 FMA (any shape that passes check_cfg)
 int launch_gemm_f32(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s);
-// bf16 storage, MFMA with fp32 accumulation
-int launch_gemm_bf16(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s);
+// 16-bit storage (dtype = MOE_DTYPE_BF16 or MOE_DTYPE_F16), MFMA with fp32 accumulation
+int launch_gemm_half(int dtype, int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s);
 // one launch for an NT GEMM (epilogue epi1, chained or not) followed by a TN weight-gradient GEMM
-int launch_gemm_bf16_pair(int epi1, bool chain1, const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s);
+int launch_gemm_half_pair(int dtype, int epi1, bool chain1, const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s);
 int gemm_bf16_tile_rows();
-// adds the SPLIT_K partial sums of every split row tile and writes the bf16 rows of C [rows][N]
-int launch_split_reduce(const GemmArgs& g, hipStream_t s);
 
 #ifdef __HIPCC__
 // Element-wise epilogues, shared by both kernels.  `row` is the absolute permuted row, `col` the

@@ -1,4 +1,4 @@
-// Launchers of the bf16 MFMA grouped GEMM (kernel in gemm_bf16_kernel.h).
+// Launchers of the MFMA grouped GEMM for 16-bit storage, bf16 or fp16 (kernel in gemm_bf16_kernel.h).
 #include "gemm_bf16_kernel.h"
 
 namespace moe {
@@ -14,12 +14,21 @@ template <int MODE> struct Pipe {
 };
 int gemm_bf16_tile_rows() { return T_BM; }
 
-template <int MODE, int EPI, bool DUAL, bool CHAIN>
+// adds the SPLIT_K partial sums of every split row tile and writes the 16-bit rows of C [rows][N]
+template <typename ST>
+static int launch_split_reduce(const GemmArgs& g, hipStream_t s) {
+  const dim3 grid((SPLIT_ROWS * (g.N / 4) + 255) / 256, g.E);
+  split_reduce_kernel<ST><<<grid, 256, 0, s>>>(g);
+  return launch_status();
+}
+
+template <typename ST, int MODE, int EPI, bool DUAL, bool CHAIN>
 static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
   constexpr int BN = DUAL ? T_BN_DUAL : T_BN;
   constexpr int BK = Pipe<MODE>::BK, NB = Pipe<MODE>::NB;
-  constexpr int lds = gemm_bf16_lds_bytes<T_BM, BN, BK, DUAL, T_WGM, T_WGN, NB, EPI == EPI_GELU_BWD || EPI == EPI_GELU_FWD>();
-  auto kern = gemm_bf16_kernel<MODE, EPI, DUAL, CHAIN, T_BM, BN, BK, T_WGM, T_WGN, NB>;
+  constexpr bool TAB = (EPI == EPI_GELU_BWD || EPI == EPI_GELU_FWD) && Half16<ST>::GELU_TABLE;
+  constexpr int lds = gemm_bf16_lds_bytes<T_BM, BN, BK, DUAL, T_WGM, T_WGN, NB, TAB>();
+  auto kern = gemm_bf16_kernel<ST, MODE, EPI, DUAL, CHAIN, T_BM, BN, BK, T_WGM, T_WGN, NB>;
   // more than 64 KB of dynamic LDS needs the attribute on the current device; set on every launch (a cheap
   // host-side call) rather than remembered, so the library keeps no per-process or per-device state
   {
@@ -35,22 +44,16 @@ static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
   kern<<<dim3(gemm_bf16_grid(tiles)), T_WGM * T_WGN * 64, lds, s>>>(g);
   int rc = launch_status();
   if (rc != MOE_OK || !split) return rc;
-  return launch_split_reduce(g, s);
-}
-
-int launch_split_reduce(const GemmArgs& g, hipStream_t s) {
-  const dim3 grid((SPLIT_ROWS * (g.N / 4) + 255) / 256, g.E);
-  split_reduce_kernel<<<grid, 256, 0, s>>>(g);
-  return launch_status();
+  return launch_split_reduce<ST>(g, s);
 }
 
 // A row-tile GEMM (NT) and a weight-gradient GEMM (TN) in one launch; the first one's blocks come first.
-template <int EPI1, bool CHAIN1>
+template <typename ST, int EPI1, bool CHAIN1>
 static int launch_pair(const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s) {
-  constexpr int lds1 = gemm_bf16_lds_bytes<T_BM, T_BN, Pipe<MODE_NT>::BK, false, T_WGM, T_WGN, Pipe<MODE_NT>::NB, EPI1 == EPI_GELU_BWD>();
+  constexpr int lds1 = gemm_bf16_lds_bytes<T_BM, T_BN, Pipe<MODE_NT>::BK, false, T_WGM, T_WGN, Pipe<MODE_NT>::NB, EPI1 == EPI_GELU_BWD && Half16<ST>::GELU_TABLE>();
   constexpr int lds2 = gemm_bf16_lds_bytes<T_BM, T_BN, Pipe<MODE_TN>::BK, false, T_WGM, T_WGN, Pipe<MODE_TN>::NB>();
   constexpr int lds = lds1 > lds2 ? lds1 : lds2;
-  auto kern = gemm_bf16_pair_kernel<MODE_NT, EPI1, CHAIN1, Pipe<MODE_NT>::BK, Pipe<MODE_NT>::NB, MODE_TN, EPI_DW,
+  auto kern = gemm_bf16_pair_kernel<ST, MODE_NT, EPI1, CHAIN1, Pipe<MODE_NT>::BK, Pipe<MODE_NT>::NB, MODE_TN, EPI_DW,
                                     Pipe<MODE_TN>::BK, Pipe<MODE_TN>::NB, T_BM, T_BN, T_WGM, T_WGN>;
   // more than 64 KB of dynamic LDS needs the attribute on the current device; set on every launch (a cheap
   // host-side call) rather than remembered, so the library keeps no per-process or per-device state
@@ -71,27 +74,37 @@ static int launch_pair(const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hi
   kern<<<dim3(gemm_bf16_grid(n1 + n2)), T_WGM * T_WGN * 64, lds, s>>>(g1, g2, (int)n1);
   const int rc = launch_status();
   if (rc != MOE_OK || !split) return rc;
-  return launch_split_reduce(g1, s);
+  return launch_split_reduce<ST>(g1, s);
 }
 
-int launch_gemm_bf16_pair(int epi1, bool chain1, const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s) {
-  if (epi1 == EPI_GELU_BWD) return launch_pair<EPI_GELU_BWD, false>(g1, max_tiles, g2, s);
-  if (epi1 == EPI_SWIGLU_BWD) return launch_pair<EPI_SWIGLU_BWD, false>(g1, max_tiles, g2, s);
-  if (epi1 == EPI_STORE && !chain1) return launch_pair<EPI_STORE, false>(g1, max_tiles, g2, s);
-  if (epi1 == EPI_STORE && chain1) return launch_pair<EPI_STORE, true>(g1, max_tiles, g2, s);
+template <typename ST>
+static int pair_for(int epi1, bool chain1, const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s) {
+  if (epi1 == EPI_GELU_BWD) return launch_pair<ST, EPI_GELU_BWD, false>(g1, max_tiles, g2, s);
+  if (epi1 == EPI_SWIGLU_BWD) return launch_pair<ST, EPI_SWIGLU_BWD, false>(g1, max_tiles, g2, s);
+  if (epi1 == EPI_STORE && !chain1) return launch_pair<ST, EPI_STORE, false>(g1, max_tiles, g2, s);
+  if (epi1 == EPI_STORE && chain1) return launch_pair<ST, EPI_STORE, true>(g1, max_tiles, g2, s);
   return MOE_ERR_BAD_DTYPE;
 }
 
-int launch_gemm_bf16(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s) {
-  if (mode == MODE_NN && epi == EPI_GELU_FWD) return launch_one<MODE_NN, EPI_GELU_FWD, false, false>(g, max_tiles, s);
-  if (mode == MODE_NN && epi == EPI_SWIGLU_FWD && dual) return launch_one<MODE_NN, EPI_SWIGLU_FWD, true, false>(g, max_tiles, s);
-  if (mode == MODE_NN && epi == EPI_STORE) return launch_one<MODE_NN, EPI_STORE, false, false>(g, max_tiles, s);
-  if (mode == MODE_NT && epi == EPI_GELU_BWD) return launch_one<MODE_NT, EPI_GELU_BWD, false, false>(g, max_tiles, s);
-  if (mode == MODE_NT && epi == EPI_SWIGLU_BWD) return launch_one<MODE_NT, EPI_SWIGLU_BWD, false, false>(g, max_tiles, s);
-  if (mode == MODE_NT && epi == EPI_STORE && !chain) return launch_one<MODE_NT, EPI_STORE, false, false>(g, max_tiles, s);
-  if (mode == MODE_NT && epi == EPI_STORE && chain) return launch_one<MODE_NT, EPI_STORE, false, true>(g, max_tiles, s);
-  if (mode == MODE_TN && epi == EPI_DW) return launch_one<MODE_TN, EPI_DW, false, false>(g, max_tiles, s);
+template <typename ST>
+static int one_for(int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s) {
+  if (mode == MODE_NN && epi == EPI_GELU_FWD) return launch_one<ST, MODE_NN, EPI_GELU_FWD, false, false>(g, max_tiles, s);
+  if (mode == MODE_NN && epi == EPI_SWIGLU_FWD && dual) return launch_one<ST, MODE_NN, EPI_SWIGLU_FWD, true, false>(g, max_tiles, s);
+  if (mode == MODE_NN && epi == EPI_STORE) return launch_one<ST, MODE_NN, EPI_STORE, false, false>(g, max_tiles, s);
+  if (mode == MODE_NT && epi == EPI_GELU_BWD) return launch_one<ST, MODE_NT, EPI_GELU_BWD, false, false>(g, max_tiles, s);
+  if (mode == MODE_NT && epi == EPI_SWIGLU_BWD) return launch_one<ST, MODE_NT, EPI_SWIGLU_BWD, false, false>(g, max_tiles, s);
+  if (mode == MODE_NT && epi == EPI_STORE && !chain) return launch_one<ST, MODE_NT, EPI_STORE, false, false>(g, max_tiles, s);
+  if (mode == MODE_NT && epi == EPI_STORE && chain) return launch_one<ST, MODE_NT, EPI_STORE, false, true>(g, max_tiles, s);
+  if (mode == MODE_TN && epi == EPI_DW) return launch_one<ST, MODE_TN, EPI_DW, false, false>(g, max_tiles, s);
   return MOE_ERR_BAD_DTYPE;
+}
+
+int launch_gemm_half_pair(int dtype, int epi1, bool chain1, const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s) {
+  return dtype == MOE_DTYPE_F16 ? pair_for<f16>(epi1, chain1, g1, max_tiles, g2, s) : pair_for<bf16>(epi1, chain1, g1, max_tiles, g2, s);
+}
+
+int launch_gemm_half(int dtype, int mode, int epi, bool dual, bool chain, const GemmArgs& g, int max_tiles, hipStream_t s) {
+  return dtype == MOE_DTYPE_F16 ? one_for<f16>(mode, epi, dual, chain, g, max_tiles, s) : one_for<bf16>(mode, epi, dual, chain, g, max_tiles, s);
 }
 
 }  // namespace moe

@@ -1,4 +1,7 @@
-// bf16 grouped GEMM kernel for the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+// Grouped GEMM kernel for the gfx950 matrix cores with 16-bit storage: bf16 (v_mfma_f32_32x32x16_bf16) or
+// fp16 (v_mfma_f32_32x32x16_f16), fp32 accumulate.  The storage type ST is a template parameter of the one
+// kernel; it selects the MFMA instruction, the conversions of the epilogues, and whether the GELU epilogues
+// look their function up (bf16: a table over all bf16 numbers fits in LDS) or evaluate it (fp16).
 //
 // Work decomposition: block tile BM x BN, WGM x WGN waves; a wave owns BN/WGN adjacent columns and the
 // 32-row bands b = wm, wm + WGM, ... of the tile, as a grid of 32x32 MFMA tiles; K advances BKT elements
@@ -40,6 +43,29 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// What depends on the 16-bit storage type: packing two fp32 values, unpacking, and the MFMA instruction.
+template <typename ST> struct Half16;
+template <> struct Half16<bf16> {
+  static constexpr bool GELU_TABLE = true;
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return pack_bf16x2(lo, hi); }
+  static __device__ __forceinline__ float lo(uint32_t u) { return __uint_as_float(u << 16); }
+  static __device__ __forceinline__ float hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+  static __device__ __forceinline__ f32x16 mfma(const bf16x8& a, const bf16x8& b, const f32x16& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+};
+template <> struct Half16<f16> {
+  static constexpr bool GELU_TABLE = false;
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return pack_f16x2(lo, hi); }
+  static __device__ __forceinline__ float lo(uint32_t u) { return f16_bits_to_f32(u & 0xffffu); }
+  static __device__ __forceinline__ float hi(uint32_t u) { return f16_bits_to_f32(u >> 16); }
+  static __device__ __forceinline__ f32x16 mfma(const bf16x8& a, const bf16x8& b, const f32x16& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+};
 
 constexpr int NUM_XCD = 8;
 constexpr int NBUF = 4;   // LDS stages in the ring
@@ -159,24 +185,29 @@ __device__ __forceinline__ float gelu_tab_lookup(const float* tab, uint32_t bits
   return tab[m + (int)(bits >> 15) * GELU_TAB_NMAG];
 }
 
-template <int EPI>
+template <typename ST, int EPI>
 __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f32x4& a, const f32x4& a2,
                                           const u32x2& sv1, const u32x2& sv2, const float* tab) {
+  typedef Half16<ST> H;
   auto st = [](void* base, size_t i, float v0, float v1, float v2, float v3) {
-    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16*>(base) + i) = u32x2{pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
+    *reinterpret_cast<u32x2*>(reinterpret_cast<ST*>(base) + i) = u32x2{H::pack2(v0, v1), H::pack2(v2, v3)};
   };
-  auto ld = [](const u32x2& r, float* f) {   // four saved bf16 values, loaded by the caller ahead of time
-    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
-    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+  auto ld = [](const u32x2& r, float* f) {   // four saved 16-bit values, loaded by the caller ahead of time
+    f[0] = H::lo(r.x); f[1] = H::hi(r.x);
+    f[2] = H::lo(r.y); f[3] = H::hi(r.y);
   };
   if constexpr (EPI == EPI_STORE) {
     st(g.C, idx, a[0], a[1], a[2], a[3]);
   } else if constexpr (EPI == EPI_GELU_FWD) {
-    // h = a Phi(v), v = the pre-activation as stored (bf16): GELU of the saved tensor, Phi looked up
-    const uint32_t p0 = pack_bf16x2(a[0], a[1]), p1 = pack_bf16x2(a[2], a[3]);
-    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16*>(g.C) + idx) = u32x2{p0, p1};
-    st(g.C2, idx, a[0] * gelu_tab_lookup(tab, p0 & 0xffffu), a[1] * gelu_tab_lookup(tab, p0 >> 16),
-       a[2] * gelu_tab_lookup(tab, p1 & 0xffffu), a[3] * gelu_tab_lookup(tab, p1 >> 16));
+    // h = a Phi(v), v = the pre-activation as stored: GELU of the saved tensor; Phi looked up (bf16) or evaluated (fp16)
+    const uint32_t p0 = H::pack2(a[0], a[1]), p1 = H::pack2(a[2], a[3]);
+    *reinterpret_cast<u32x2*>(reinterpret_cast<ST*>(g.C) + idx) = u32x2{p0, p1};
+    if constexpr (H::GELU_TABLE) {
+      st(g.C2, idx, a[0] * gelu_tab_lookup(tab, p0 & 0xffffu), a[1] * gelu_tab_lookup(tab, p0 >> 16),
+         a[2] * gelu_tab_lookup(tab, p1 & 0xffffu), a[3] * gelu_tab_lookup(tab, p1 >> 16));
+    } else {
+      st(g.C2, idx, a[0] * phi_f(H::lo(p0)), a[1] * phi_f(H::hi(p0)), a[2] * phi_f(H::lo(p1)), a[3] * phi_f(H::hi(p1)));
+    }
   } else if constexpr (EPI == EPI_SWIGLU_FWD) {
     st(g.C, idx, a[0], a[1], a[2], a[3]);
     st(g.C2, idx, a2[0], a2[1], a2[2], a2[3]);
@@ -185,9 +216,15 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
     for (int i = 0; i < 4; ++i) h[i] = a[i] * sigmoid_fast(a[i]) * a2[i];
     st(g.C3, idx, h[0], h[1], h[2], h[3]);
   } else if constexpr (EPI == EPI_GELU_BWD) {
-    // the saved pre-activation is a bf16 number: its derivative is looked up, not computed
-    const float o0 = a[0] * gelu_tab_lookup(tab, sv1.x & 0xffffu), o1 = a[1] * gelu_tab_lookup(tab, sv1.x >> 16);
-    const float o2 = a[2] * gelu_tab_lookup(tab, sv1.y & 0xffffu), o3 = a[3] * gelu_tab_lookup(tab, sv1.y >> 16);
+    // the derivative at the saved pre-activation: looked up (bf16) or evaluated (fp16)
+    float o0, o1, o2, o3;
+    if constexpr (H::GELU_TABLE) {
+      o0 = a[0] * gelu_tab_lookup(tab, sv1.x & 0xffffu); o1 = a[1] * gelu_tab_lookup(tab, sv1.x >> 16);
+      o2 = a[2] * gelu_tab_lookup(tab, sv1.y & 0xffffu); o3 = a[3] * gelu_tab_lookup(tab, sv1.y >> 16);
+    } else {
+      o0 = a[0] * gelu_grad_f(H::lo(sv1.x)); o1 = a[1] * gelu_grad_f(H::hi(sv1.x));
+      o2 = a[2] * gelu_grad_f(H::lo(sv1.y)); o3 = a[3] * gelu_grad_f(H::hi(sv1.y));
+    }
     st(g.C, idx, o0, o1, o2, o3);
   } else if constexpr (EPI == EPI_SWIGLU_BWD) {
     float gg[4], uu[4], dg[4], du[4];
@@ -216,7 +253,7 @@ constexpr int gemm_bf16_lds_bytes() {
 
 // One output tile; vb = the tile's number in dispatch order.  Block-uniform control flow; returns at
 // once for numbers past the last tile (the grid is sized for the worst case).
-template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB>
+template <typename ST, int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, char* smem) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM / 32, WTN = BN / WGN / 32;
@@ -240,16 +277,25 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     int rt, nt;
     if constexpr (MODE == MODE_TN) {
       // Weight gradients: tile (expert, m tile, n tile) costs its expert's row count.  Every expert's
-      // tiles are dealt round-robin over the XCDs (block b -> XCD b % 8), so a skewed load is even
-      // across XCDs and the tiles an XCD holds of one expert share operand panels; experts start in
-      // order of descending row count.
+      // tiles are split evenly over the XCDs (block b runs on XCD b % 8), so a skewed load is even across
+      // XCDs; experts start in order of descending row count.  An XCD's share of an expert is a contiguous
+      // range of the expert's tiles in patch order (four m tiles at a time, column by column), so the 32
+      // tiles it runs together form a 4 x 8 patch that needs 12 operand panels per K stage from its L2
+      // instead of up to 18 with the tiles dealt one by one (that order made dW2 of the Mixtral-like shape
+      // read 6.9 times its operands through the fabric).
       const int ntm = (g.M + BM - 1) / BM;
       const int P = ntm * ntn, P8 = (P + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
-      const int p = vb % P8;
+      const int q = vb % P8;
+      const int p = (q % NUM_XCD) * (P8 / NUM_XCD) + q / NUM_XCD;   // position in patch order
       if (p >= P) return;
       e = g.order[vb / P8];
-      m0 = (p / ntn) * BM;
-      nt = p % ntn;
+      {
+        constexpr int GROUP = 4;
+        const int per_group = GROUP * ntn, grp = p / per_group, in = p % per_group;
+        const int first = grp * GROUP, gsz = min(GROUP, ntm - first);
+        m0 = (first + in % gsz) * BM;
+        nt = in / gsz;
+      }
       rt = 0;
       int l, h;
       share_of(g.lo, g.hi, g.kept[e], e, l, h);
@@ -444,9 +490,9 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
       _Pragma("unroll") for (int m__ = r__ * GM; m__ < (r__ + 1) * GM; ++m__) {                             \
         const int i__ = m__ / WTN, j__ = m__ % WTN;                                                         \
         if (i__ < (NI_)) {                                                                                  \
-          acc[i__][j__] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i__], bfr[cur_][j__], acc[i__][j__], 0, 0, 0); \
+          acc[i__][j__] = Half16<ST>::mfma(af[cur_][i__], bfr[cur_][j__], acc[i__][j__]); \
           if constexpr (DUAL)                                                                               \
-            acc2[i__][j__] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i__], bfr2[cur_][j__], acc2[i__][j__], 0, 0, 0); \
+            acc2[i__][j__] = Half16<ST>::mfma(af[cur_][i__], bfr2[cur_][j__], acc2[i__][j__]); \
         }                                                                                                   \
       }                                                                                                     \
       if (DO_LOAD_) {                                                                                       \
@@ -471,7 +517,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     asm volatile("" ::: "memory");                                                                          \
     bload = b0; b0 = b1; b1 = (b1 + STAGE == NB * STAGE) ? 0 : b1 + STAGE;                                  \
   } while (0)
-    if constexpr (EPI == EPI_GELU_BWD || EPI == EPI_GELU_FWD) {
+    if constexpr ((EPI == EPI_GELU_BWD || EPI == EPI_GELU_FWD) && Half16<ST>::GELU_TABLE) {
       // the GELU table rides along with the first stage loads (older than they are, so the
       // first wait of the pipeline covers it): 1 KB per wave and instruction, behind the ring
       static_assert(GELU_TAB_FLOATS * 4 % (NT * 16) == 0, "whole block-wide loads");
@@ -498,9 +544,9 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
       _Pragma("unroll") for (int m__ = r__ * GM; m__ < (r__ + 1) * GM; ++m__) {                             \
         const int i__ = m__ / WTN, j__ = m__ % WTN;                                                         \
         if (i__ < (NI_)) {                                                                                  \
-          acc[i__][j__] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i__], bfr[cur_][j__], acc[i__][j__], 0, 0, 0); \
+          acc[i__][j__] = Half16<ST>::mfma(af[cur_][i__], bfr[cur_][j__], acc[i__][j__]); \
           if constexpr (DUAL)                                                                               \
-            acc2[i__][j__] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur_][i__], bfr2[cur_][j__], acc2[i__][j__], 0, 0, 0); \
+            acc2[i__][j__] = Half16<ST>::mfma(af[cur_][i__], bfr2[cur_][j__], acc2[i__][j__]); \
         }                                                                                                   \
       }                                                                                                     \
       if (DO_LOAD_) {                                                                                       \
@@ -663,7 +709,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
             f32x4* c = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + ((size_t)e * g.M + m0 + m) * g.N + n0 + n);
             *c = g.accumulate ? *c + va[p] : va[p];
           } else {
-            epilogue4<EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0],
+            epilogue4<ST, EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0],
                            s1[NEED_S1 ? i & 1 : 0][NEED_S1 ? p : 0], s2[NEED_S2 ? i & 1 : 0][NEED_S2 ? p : 0], tab_lds);
           }
         }
@@ -674,6 +720,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
 
 // Second half of split-K: C[row][n..n+3] = sum over the SPLIT_K parts, in part order, of the fp32 partial
 // sums of split row tile blockIdx.y; a thread owns four adjacent columns of one row.
+template <typename ST>
 __global__ __launch_bounds__(256) void split_reduce_kernel(GemmArgs g) {
   const int n_sp = g.ntiles[2], st = blockIdx.y;
   if (st >= n_sp) return;
@@ -685,27 +732,27 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(GemmArgs g) {
 #pragma unroll
   for (int ks = 0; ks < SPLIT_K; ++ks)
     sum += *reinterpret_cast<const f32x4*>(g.split_ws + (((size_t)st * SPLIT_K + ks) * SPLIT_ROWS + m) * g.N + n);
-  *reinterpret_cast<u32x2*>(reinterpret_cast<bf16*>(g.C) + (size_t)(t.row0 + m) * g.N + n) =
-      u32x2{pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3])};
+  *reinterpret_cast<u32x2*>(reinterpret_cast<ST*>(g.C) + (size_t)(t.row0 + m) * g.N + n) =
+      u32x2{Half16<ST>::pack2(sum[0], sum[1]), Half16<ST>::pack2(sum[2], sum[3])};
 }
 
-template <int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>
+template <typename ST, int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  gemm_bf16_tile<MODE, EPI, DUAL, CHAIN, BM, BN, BKT, WGM, WGN, NB>(g, blockIdx.x, smem);
+  gemm_bf16_tile<ST, MODE, EPI, DUAL, CHAIN, BM, BN, BKT, WGM, WGN, NB>(g, blockIdx.x, smem);
 }
 
 // Two independent GEMMs in one launch: blocks below `first_blocks` take a tile of the first, the others a
 // tile of the second.  Blocks are dispatched in order, so the second GEMM's tiles start on the compute
 // units that the first one's last, partly filled round leaves idle (no stream or event in between,
 // and the two never compete for the cache from the start as two concurrent kernels would).
-template <int MODE1, int EPI1, bool CHAIN1, int BK1, int NB1, int MODE2, int EPI2, int BK2, int NB2, int BM, int BN, int WGM, int WGN>
+template <typename ST, int MODE1, int EPI1, bool CHAIN1, int BK1, int NB1, int MODE2, int EPI2, int BK2, int NB2, int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_pair_kernel(GemmArgs g1, GemmArgs g2, int first_blocks) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   if ((int)blockIdx.x < first_blocks)
-    gemm_bf16_tile<MODE1, EPI1, false, CHAIN1, BM, BN, BK1, WGM, WGN, NB1>(g1, blockIdx.x, smem);
+    gemm_bf16_tile<ST, MODE1, EPI1, false, CHAIN1, BM, BN, BK1, WGM, WGN, NB1>(g1, blockIdx.x, smem);
   else
-    gemm_bf16_tile<MODE2, EPI2, false, false, BM, BN, BK2, WGM, WGN, NB2>(g2, blockIdx.x - first_blocks, smem);
+    gemm_bf16_tile<ST, MODE2, EPI2, false, false, BM, BN, BK2, WGM, WGN, NB2>(g2, blockIdx.x - first_blocks, smem);
 }
 
 inline unsigned gemm_bf16_grid(long long tiles) { return (unsigned)(tiles > 0 ? tiles : 1); }

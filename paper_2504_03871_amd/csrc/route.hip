@@ -566,10 +566,12 @@ int launch_route(const moe_cfg* c, const void* x, const float* Wr, const float* 
   }
   const RouteGeom gm = route_geom(c->E);
   const int grid = (c->T + gm.tok - 1) / gm.tok;
-  const size_t es = c->dtype == MOE_DTYPE_BF16 ? 2 : 4;
+  const size_t es = elt_size(c);
   const size_t lds = (size_t)gm.tok * (gm.dc + RT_XPAD) * es + (size_t)gm.dc * gm.e4 * 4 + (size_t)gm.tok * c->E * 4;
   if (c->dtype == MOE_DTYPE_BF16)
     route_kernel<bf16><<<grid, RT_THREADS, lds, s>>>((const bf16*)x, Wr, bias, logits_in, logits_out, idx, w, c->T, c->d_model, c->E, c->k, gm);
+  else if (c->dtype == MOE_DTYPE_F16)
+    route_kernel<f16><<<grid, RT_THREADS, lds, s>>>((const f16*)x, Wr, bias, logits_in, logits_out, idx, w, c->T, c->d_model, c->E, c->k, gm);
   else
     route_kernel<float><<<grid, RT_THREADS, lds, s>>>((const float*)x, Wr, bias, logits_in, logits_out, idx, w, c->T, c->d_model, c->E, c->k, gm);
   return launch_status();
@@ -589,31 +591,29 @@ static int launch_dwr(const moe_cfg* c, const void* x, const int32_t* idx, const
   return launch_status();
 }
 
-int launch_route_bwd(const moe_cfg* c, const void* x, const float* Wr, const int32_t* idx, const float* w,
-                     const float* dw, float* d_logits, float* dWr, void* dx, int accumulate, float* partials,
-                     float* WrT, hipStream_t s) {
+template <typename T>
+static int route_bwd_typed(const moe_cfg* c, const void* x, const float* Wr, const int32_t* idx, const float* w,
+                           const float* dw, float* d_logits, float* dWr, void* dx, int accumulate, float* partials,
+                           float* WrT, hipStream_t s) {
   const int n = c->d_model * c->E;
   const int chunks = (c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS;
-  const bool bf = c->dtype == MOE_DTYPE_BF16;
   int rc;
   if (dx != nullptr) {
     wr_transpose_kernel<<<(n + 255) / 256, 256, 0, s>>>(Wr, WrT, c->d_model, c->E);
     if ((rc = launch_status()) != MOE_OK) return rc;
   }
   const int grid = (c->T + 3) / 4;
-  if (bf) route_bwd_dx_kernel<bf16><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (bf16*)dx, c->T, c->d_model, c->E, c->k);
-  else route_bwd_dx_kernel<float><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (float*)dx, c->T, c->d_model, c->E, c->k);
+  route_bwd_dx_kernel<T><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (T*)dx, c->T, c->d_model, c->E, c->k);
   if ((rc = launch_status()) != MOE_OK) return rc;
   if (dWr == nullptr) return MOE_OK;
   if (c->E <= ROUTE_BWD_DENSE_E) {
-    const RouteBwdGeom gm = route_bwd_geom(c->T, c->d_model, bf ? 2 : 4);
+    const RouteBwdGeom gm = route_bwd_geom(c->T, c->d_model, (int)sizeof(T));
     const dim3 grid(gm.col_blocks, gm.row_blocks);
     const int eb = c->E <= 4 ? 4 : (c->E <= 8 ? 8 : 16);
     const size_t lds = (size_t)gm.slices_per_block * gm.tps * eb * 4;
-#define MOE_DWR_DENSE(TY, EB) \
-  route_bwd_dwr_dense_kernel<TY, EB><<<grid, 256, lds, s>>>((const TY*)x, d_logits, partials, c->T, c->d_model, c->E, gm)
-    if (bf) { if (eb == 4) MOE_DWR_DENSE(bf16, 4); else if (eb == 8) MOE_DWR_DENSE(bf16, 8); else MOE_DWR_DENSE(bf16, 16); }
-    else { if (eb == 4) MOE_DWR_DENSE(float, 4); else if (eb == 8) MOE_DWR_DENSE(float, 8); else MOE_DWR_DENSE(float, 16); }
+#define MOE_DWR_DENSE(EB) \
+  route_bwd_dwr_dense_kernel<T, EB><<<grid, 256, lds, s>>>((const T*)x, d_logits, partials, c->T, c->d_model, c->E, gm)
+    if (eb == 4) MOE_DWR_DENSE(4); else if (eb == 8) MOE_DWR_DENSE(8); else MOE_DWR_DENSE(16);
 #undef MOE_DWR_DENSE
     if ((rc = launch_status()) != MOE_OK) return rc;
     route_bwd_reduce_kernel<true><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, gm.partial_rows, accumulate);
@@ -621,12 +621,20 @@ int launch_route_bwd(const moe_cfg* c, const void* x, const float* Wr, const int
   }
   // columns per thread: as many as 128 KiB of LDS allow for 4 waves x E experts (d is a multiple of 4)
   const int vec = (c->E <= 32) ? 4 : (c->E <= 64 ? 2 : 1);
-  if (vec == 4) rc = bf ? launch_dwr<bf16, 4>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 4>(c, x, idx, d_logits, partials, chunks, s);
-  else if (vec == 2) rc = bf ? launch_dwr<bf16, 2>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 2>(c, x, idx, d_logits, partials, chunks, s);
-  else rc = bf ? launch_dwr<bf16, 1>(c, x, idx, d_logits, partials, chunks, s) : launch_dwr<float, 1>(c, x, idx, d_logits, partials, chunks, s);
+  if (vec == 4) rc = launch_dwr<T, 4>(c, x, idx, d_logits, partials, chunks, s);
+  else if (vec == 2) rc = launch_dwr<T, 2>(c, x, idx, d_logits, partials, chunks, s);
+  else rc = launch_dwr<T, 1>(c, x, idx, d_logits, partials, chunks, s);
   if (rc != MOE_OK) return rc;
   route_bwd_reduce_kernel<false><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, chunks, accumulate);
   return launch_status();
+}
+
+int launch_route_bwd(const moe_cfg* c, const void* x, const float* Wr, const int32_t* idx, const float* w,
+                     const float* dw, float* d_logits, float* dWr, void* dx, int accumulate, float* partials,
+                     float* WrT, hipStream_t s) {
+  if (c->dtype == MOE_DTYPE_BF16) return route_bwd_typed<bf16>(c, x, Wr, idx, w, dw, d_logits, dWr, dx, accumulate, partials, WrT, s);
+  if (c->dtype == MOE_DTYPE_F16) return route_bwd_typed<f16>(c, x, Wr, idx, w, dw, d_logits, dWr, dx, accumulate, partials, WrT, s);
+  return route_bwd_typed<float>(c, x, Wr, idx, w, dw, d_logits, dWr, dx, accumulate, partials, WrT, s);
 }
 
 }  // namespace moe

@@ -18,7 +18,7 @@ class MoELayer:
         layer seen by several micro-batches, each with activation buffers of its own)."""
         self.cfg = B.make_cfg(T, d_model, d_ff, E, k, dtype, act, capacity)
         self.T, self.d, self.f, self.E, self.k, self.act = T, d_model, d_ff, E, k, act
-        self.tdtype = torch.bfloat16 if dtype == B.DTYPE_BF16 else torch.float32
+        self.tdtype = {B.DTYPE_BF16: torch.bfloat16, B.DTYPE_F16: torch.float16}.get(dtype, torch.float32)
         self.device = torch.device(device)
         A = T * k
         dev, td = self.device, self.tdtype

@@ -27,7 +27,7 @@ BASE_SEED = 250403871
 TID_X, TID_WR, TID_W1, TID_W1B, TID_W2, TID_DOUT = 0, 1, 2, 3, 4, 5
 
 ACT_GELU, ACT_SWIGLU = 0, 1
-DT_F32, DT_BF16 = 0, 1
+DT_F32, DT_BF16, DT_F16 = 0, 1, 2
 
 _GOLDEN = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
@@ -85,6 +85,15 @@ def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def f32_to_f16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 to IEEE half precision (round to nearest, ties to even); returns the 16-bit patterns."""
+    return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return bits.view(np.float16).astype(np.float32)
 
 
 @dataclass(frozen=True)
@@ -147,9 +156,9 @@ def router_bias(w: Workload):
 def make_inputs(w: Workload, threads: int = 8) -> dict:
     """All input tensors of one workload.
 
-    Returns fp32 arrays holding the values both sides consume: for bf16 workloads x, the expert
-    weights and the upstream gradient are already rounded to bf16 (and `<name>_bits` holds the
-    16-bit patterns to upload); the router weight and bias stay fp32.
+    Returns fp32 arrays holding the values both sides consume: for bf16 and fp16 workloads x, the
+    expert weights and the upstream gradient are already rounded to the storage type (and
+    `<name>_bits` holds the 16-bit patterns to upload); the router weight and bias stay fp32.
     """
     out = {}
     x = normal_f32(_seed(w, TID_X), (w.T, w.d), 1.0, threads)
@@ -165,6 +174,10 @@ def make_inputs(w: Workload, threads: int = 8) -> dict:
             bits = f32_to_bf16_bits(a)
             out[name + "_bits"] = bits
             out[name] = bf16_bits_to_f32(bits)
+        elif w.dtype == DT_F16:
+            bits = f32_to_f16_bits(a)
+            out[name + "_bits"] = bits
+            out[name] = f16_bits_to_f32(bits)
         else:
             out[name] = a
     out["Wr"] = wr

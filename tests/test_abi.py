@@ -45,7 +45,8 @@ def test_cfg_validation():
         with pytest.raises(B.MoeError) as ei:
             B.moe_workspace_bytes(B.make_cfg(**{**ok, **b}))
         assert ei.value.code == -2, b
-    for b in (dict(dtype=2), dict(act=7)):
+    assert B.moe_saved_bytes(B.make_cfg(**{**ok, "dtype": B.DTYPE_F16})) == 2 * 16 * 128 * 2     # fp16 storage
+    for b in (dict(dtype=3), dict(act=7)):
         with pytest.raises(B.MoeError) as ei:
             B.moe_workspace_bytes(B.make_cfg(**{**ok, **b}))
         assert ei.value.code == -3

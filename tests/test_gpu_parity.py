@@ -42,6 +42,16 @@ CASES = {
     # d_ff long enough for split-K of the smallest row tiles: only such tiles / a full tile plus a small rest
     "split_k_tiny": W["cfg1"].scaled(T=40, d=128, f=2048, E=4, k=2),
     "split_k_mixed": W["cfg1"].scaled(T=620, d=128, f=2560, E=4, k=2),
+    # fp16 storage (the paper trains in FP16 mixed precision, Section 6.1): the bf16 cases again
+    "f16_cfg1_small": W["cfg1"].scaled(T=1000, d=256, f=512, dtype=S.DT_F16),
+    "f16_cfg2_small": W["cfg2"].scaled(T=2048, d=256, f=384, dtype=S.DT_F16),
+    "f16_cfg3_small": W["cfg3"].scaled(T=1536, d=512, f=448, dtype=S.DT_F16),
+    "f16_cfg4z_small": W["cfg4z"].scaled(T=2048, d=256, f=512, dtype=S.DT_F16),
+    "f16_swiglu_partial_cap": W["cfg3"].scaled(T=1200, d=256, f=320, E=6, k=3, capacity_factor=0.8, partial=True, zipf_s=0.7,
+                                               dtype=S.DT_F16),
+    "f16_many_experts": W["cfg1"].scaled(T=700, d=128, f=128, E=200, k=8, dtype=S.DT_F16),
+    "f16_one_token": W["cfg1"].scaled(T=1, d=64, f=128, E=4, k=2, dtype=S.DT_F16),
+    "f16_split_k_mixed": W["cfg1"].scaled(T=620, d=128, f=2560, E=4, k=2, dtype=S.DT_F16),
 }
 
 
@@ -81,7 +91,7 @@ def run_case(w: S.Workload):
         # sqrt(d) * 2^-24 * S (random-walk estimate; the factor 8 is the margin); the bf16 gate also
         # keeps the weight as two bf16 terms, i.e. to 2^-17 relative, which adds 2^-17 * S per logit.
         acc = 8 * 2.0 ** -24 * np.sqrt(w.d)
-        rep_w = 0.0 if w.dtype == S.DT_F32 else 2 * 2.0 ** -17
+        rep_w = 2 * 2.0 ** -17 if w.dtype == S.DT_BF16 else 0.0    # fp32 and fp16 inputs: plain fp32 FMAs on the fp32 weight
         mag = np.abs(inp["x"][diff].astype(np.float64)) @ np.abs(inp["Wr"].astype(np.float64))
         srt = np.sort(ref["logits"][diff], axis=1)[:, ::-1]
         gaps = np.abs(np.diff(srt[:, :w.k + 1], axis=1)).min(axis=1)

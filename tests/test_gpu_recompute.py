@@ -15,6 +15,8 @@ CASES = {
     "bf16_gelu_split_k": W["cfg1"].scaled(T=620, d=128, f=2560, E=4, k=2),
     "bf16_swiglu_partial_cap": W["cfg3"].scaled(T=1200, d=256, f=320, E=6, k=3, capacity_factor=0.8, partial=True,
                                                 zipf_s=0.7),
+    "f16_gelu": W["cfg1"].scaled(T=1000, d=256, f=512, dtype=S.DT_F16),
+    "f16_swiglu": W["cfg3"].scaled(T=900, d=256, f=320, E=6, k=3, dtype=S.DT_F16),
 }
 
 

@@ -17,6 +17,7 @@ CASES = {
     "bf16_gelu_L2_R3": (S.WORKLOADS["cfg1"].scaled(T=768, d=128, f=256, E=8, k=2), 2, 3),
     "bf16_swiglu_L3_R2": (S.WORKLOADS["cfg3"].scaled(T=512, d=128, f=192, E=6, k=3), 3, 2),
     "f32_L2_R4": (S.WORKLOADS["cfg0"].scaled(T=512, d=64, f=96, E=8, k=2), 2, 4),
+    "f16_gelu_L2_R2": (S.WORKLOADS["cfg1"].scaled(T=512, d=128, f=256, E=8, k=2, dtype=S.DT_F16), 2, 2),
 }
 
 

@@ -51,3 +51,15 @@ def test_workloads():
     assert inp["x_bits"].dtype == np.uint16
     assert (S.bf16_bits_to_f32(inp["x_bits"]) == inp["x"]).all()
     assert abs(inp["Wr"].std() * 8 - 1) < 0.1
+
+
+def test_f16_rounding_is_nearest_even_and_round_trips():
+    a = np.array([1.0, 1.0 + 2 ** -11, 1.0 + 3 * 2 ** -11, 65504.0, 6e-8, -0.1], dtype=np.float32)
+    bits = S.f32_to_f16_bits(a)
+    back = S.f16_bits_to_f32(bits)
+    # ties go to the even significand: 1 + 2^-11 -> 1, 1 + 3 * 2^-11 -> 1 + 2^-9
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.0 + 2 ** -9 and back[3] == 65504.0
+    assert (S.f32_to_f16_bits(back) == bits).all()
+    w = S.WORKLOADS["cfg1"].scaled(T=64, d=64, f=64, dtype=S.DT_F16)
+    inp = S.make_inputs(w)
+    assert (S.f16_bits_to_f32(inp["x_bits"]) == inp["x"]).all() and inp["Wr"].dtype == np.float32
