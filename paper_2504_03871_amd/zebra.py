@@ -28,6 +28,21 @@ def expert_stream_order(L: int, R: int):
     return fwd + bwd
 
 
+def attention_stream_forward_order(L: int, R: int, offload):
+    """Forward compute-stream order of an ATTENTION GPU under asymmetric expert assignment (Section 4.2):
+    ('A', layer, micro-batch) for attention, ('X', layer, micro-batch) for the experts that expert block
+    `layer` (0-based, L - 1 of them between L attention blocks) has offloaded to this GPU.  A layer's
+    offloaded experts run after that layer's attention of ALL micro-batches, because their tokens come from
+    the other attention GPUs with the dispatch.  The library side of such a task is the same call sequence
+    the expert GPUs use, restricted by the slice arguments that moe_asymea_shares returns for role 1."""
+    order = []
+    for i in range(L):
+        order += [("A", i, j) for j in range(R)]
+        if i < L - 1 and offload[i] > 0:
+            order += [("X", i, j) for j in range(R)]
+    return order
+
+
 class ZebraExpertEngine:
     def __init__(self, L, R, T_mb, d_model, d_ff, E, k, dtype=B.DTYPE_BF16, act=B.ACT_GELU, device="cuda:0"):
         self.L, self.R, self.T_mb = L, R, T_mb

@@ -1,6 +1,7 @@
 """Pins for the zebra timeline model (Section 4.1 of the paper: the two scheduling constraints, Theorem 1)
 and the check of the engine's task order against it."""
 import random
+from fractions import Fraction as F
 
 import pytest
 
@@ -82,3 +83,79 @@ def test_engine_uses_the_expert_order_of_theorem_one():
         # the engine numbers expert blocks 0 .. L-1; the model's expert blocks are 1 .. (L+1)-1
         want = [("F" if k == "EF" else "B", i - 1, j - 1) for k, i, j in Z.theorem1_expert_order(L + 1, R)]
         assert zebra.expert_stream_order(L, R) == want
+
+
+# ----------------------------------------------------------------------------- asymmetric expert assignment
+def test_asymea_with_nothing_offloaded_is_the_default_model():
+    for L, R, ta, te, tc in ((3, 3, 3, 4, 0), (4, 2, 2, 5, 1), (5, 4, 4, 3, 0)):
+        t0, span0 = fwd_only(L, R, float(ta), float(te), float(tc))
+        t1, span1 = Z.simulate_forward_asymea(L, R, ta, te, 6, [0] * (L - 1), F(1, 2), tc)
+        assert span1 == span0
+        for t, v in t1.items():
+            assert t0[t] == v, t
+
+
+def test_asymea_hand_computed_timeline():
+    # attention 3, a block of six experts 4 (a third slower), one expert of block 2 on the attention GPUs where it
+    # takes 1/2 per micro-batch, free communication, three micro-batches, A1 E1 A2 E2 A3: worked by hand
+    times, span = Z.simulate_forward_asymea(3, 3, F(3), F(4), 6, [0, 1], F(1, 2))
+    want = {("AF", 2, 1): F(9), ("AF", 2, 2): F(12), ("AF", 2, 3): F(15),
+            ("XF", 2, 1): F(18), ("XF", 2, 2): F(37, 2), ("XF", 2, 3): F(19),
+            ("EF", 2, 1): F(15), ("EF", 2, 2): F(55, 3), ("EF", 2, 3): F(65, 3),
+            ("AF", 3, 1): F(39, 2), ("AF", 3, 2): F(45, 2), ("AF", 3, 3): F(51, 2)}
+    for t, s in want.items():
+        assert times[t][0] == s, (t, times[t])
+    assert span == F(57, 2) and fwd_only(3, 3, 3.0, 4.0)[1] == 30.0
+
+
+def test_asymea_constraints_hold():
+    rnd = random.Random(5)
+    for _ in range(40):
+        L, R, n = rnd.randint(2, 5), rnd.randint(1, 4), 6
+        off = [rnd.randint(0, 3) for _ in range(L - 1)]
+        times, span = Z.simulate_forward_asymea(L, R, F(rnd.randint(1, 5)), F(rnd.randint(1, 7)), n, off,
+                                                F(rnd.randint(1, 4), 4), F(rnd.randint(0, 2)))
+        for (k, i, j), (s, e) in times.items():
+            if k == "XF":      # after this layer's attention of every micro-batch, and after its own dispatch
+                assert s >= times[("AF", i, R)][1] and s >= times[("DF", i, j)][1]
+            if k == "AF" and i > 1:
+                assert s >= times[("CF", i - 1, j)][1]
+            if k == "CF":
+                assert s >= times[("EF", i, j)][1] and (("XF", i, j) not in times or s >= times[("XF", i, j)][1])
+        for kinds in (("AF", "XF"), ("EF",), ("DF",), ("CF",)):
+            iv = sorted(v for t, v in times.items() if t[0] in kinds)
+            assert all(b[0] >= a[1] for a, b in zip(iv, iv[1:]))
+
+
+def test_asymea_statements_of_the_figure_text():
+    """Section 4.2 on its figure (experts a third slower, three micro-batches, six experts): one expert of the
+    later blocks on the attention GPUs makes everything after the second layer's attention bubble-free and the
+    forward pass shorter; offloading in the first block as well gives no further gain and leaves the expert GPUs
+    with bubbles.  Holds for every cost of the offloaded expert on an attention GPU between 1/2 and 2/3 per
+    micro-batch: on the expert GPUs one expert takes 4/6, and the paper's own measurement of expert modules on its
+    two GPU generations (the lower-end one reaches about 80 % of the other, Section 3.1) puts the attention GPUs
+    at 8/15.  The figure's own percentages depend on the drawing and are not pinned."""
+    for L in (3, 4, 6):
+        _asymea_statements(L)
+
+
+def _asymea_statements(L):
+    R, n = 3, 6
+    base, span0 = Z.simulate_forward_asymea(L, R, F(3), F(4), n, [0] * (L - 1), F(1, 2))
+    for tx in (F(1, 2), F(8, 15), F(3, 5), F(2, 3)):
+        t1, span1 = Z.simulate_forward_asymea(L, R, F(3), F(4), n, [0] + [1] * (L - 2), tx)
+        assert span1 < span0
+        # attention stream: no idle time from the end of A_2 on (its tasks follow each other back to back)
+        assert Z.stream_bubbles(t1, ("AF", "XF"), first=("XF", 2, 1)) == 0
+        assert Z.stream_bubbles(base, ("AF", "XF"), first=("AF", 3, 1)) > 0
+        # the expert GPUs stay busy from their first task to their last
+        assert Z.stream_bubbles(t1, ("EF",)) == 0
+        t2, span2 = Z.simulate_forward_asymea(L, R, F(3), F(4), n, [1] * (L - 1), tx)
+        assert span2 >= span1
+        assert Z.stream_bubbles(t2, ("EF",)) > 0
+
+
+def test_engine_attention_order_under_asymea_matches_the_model():
+    for L, R, off in ((3, 3, [0, 1]), (4, 2, [2, 0, 1]), (2, 1, [0])):
+        want = [("A" if k == "AF" else "X", i - 1, j - 1) for k, i, j in Z.asymea_attention_order(L, R, off)]
+        assert zebra.attention_stream_forward_order(L, R, off) == want
