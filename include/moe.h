@@ -282,6 +282,17 @@ MOE_API int moe_asymea_shares(int32_t n, int32_t M, int32_t N, int32_t o_l, int3
                       int32_t* slice_lo, int32_t* slice_hi);
 
 /*
+ * Introspection for tests, HOST-ONLY (nothing is enqueued, `out` is a HOST int32[6]): which tile block number
+ * `block` of a grouped-GEMM launch of the 16-bit path computes, by the same code the kernels run.
+ * kind 0, row-tile GEMMs (x W, dy W^T) over n_rt row tiles of which the first n_full_rt are full and the last
+ * n_split are split along K into 8 parts, ntn column tiles: out = {1, row tile, -1, column tile, index among the
+ * split tiles or -1, K part}.  kind 1, weight-gradient GEMM with ntm x ntn tiles per expert: out = {1, expert slot
+ * (position in descending-size order), m tile, n tile, -1, -1}.  out[0] = 0: a surplus block that exits at once.
+ */
+MOE_API int moe_gemm_block_tile(int32_t kind, int64_t block, int32_t n_rt, int32_t n_full_rt, int32_t n_split,
+                        int32_t ntm, int32_t ntn, int32_t* out);
+
+/*
  * Benchmark aid, not a step of the layer: a plain streaming kernel of this library over `bytes` bytes
  * (a multiple of 16; dst and src are device pointers, 16-byte aligned).  mode 0: dst = src (the copy
  * rate is the practical ceiling of the HBM-bound kernels on a given box); mode 1: dst is filled with

@@ -94,6 +94,32 @@ def plan(n, L, M, N, T_A_attn, T_E_attn, T_E_exp, n_min=None, n_max=None):
     return o
 
 
+def plan_exact(n, L, M, N, T_A_attn, T_E_attn, T_E_exp):
+    """The unbounded plan in a second, independent form, in exact rational arithmetic on the given doubles.
+
+    Algorithm 1's loop keeps t_bubble = l T_gather - (chunks so far) T_squeeze with 0 <= t_bubble < T_squeeze, so
+    after layer l the chunks so far are floor(l T_gather / T_squeeze) and layer l offloads the difference of two
+    consecutive floors.  No accumulation, no rounding: a misreading shared by the two double-precision copies of
+    the listing (this module's `plan` and the library) would show against this form.  Also returns the smallest
+    distance of any l T_gather / T_squeeze from an integer, so that a caller can tell inputs on which rounding
+    could legitimately flip a floor."""
+    from fractions import Fraction
+    n_1, n_2 = chunk_sizes(M, N)
+    ta, tx, te = Fraction(T_A_attn), Fraction(T_E_attn), Fraction(T_E_exp)
+    T_gather = te - ta
+    T_squeeze = te * N / n * n_1 + tx * N / n * n_2
+    if T_gather <= 0:
+        return [0] * L, Fraction(1)
+    o, prev, margin = [], 0, Fraction(1)
+    for l in range(1, L + 1):
+        q = l * T_gather / T_squeeze
+        c = q.numerator // q.denominator
+        margin = min(margin, q - c, c + 1 - q)
+        o.append((c - prev) * n_2)
+        prev = c
+    return o, margin
+
+
 def expert_owner(n, M, N, o_l):
     """Which GPU computes each expert of a layer once every expert GPU has offloaded o_l experts.
 

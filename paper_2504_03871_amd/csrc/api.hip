@@ -143,6 +143,29 @@ int moe_bench_stream(void* dst, const void* src, size_t bytes, int32_t mode, voi
   return launch_status();
 }
 
+int moe_gemm_block_tile(int32_t kind, int64_t block, int32_t n_rt, int32_t n_full_rt, int32_t n_split, int32_t ntm,
+                        int32_t ntn, int32_t* out) {
+  REQUIRE(out);
+  if (block < 0 || block > 0x7fffffffll || ntn < 1 || n_rt < 0 || n_full_rt < 0 || n_full_rt > n_rt || n_split < 0 ||
+      n_split > n_rt - n_full_rt)
+    return MOE_ERR_BAD_SHAPE;
+  for (int i = 0; i < 6; ++i) out[i] = -1;
+  if (kind == 0) {
+    RowBlock r;
+    out[0] = row_tile_block((int)block, n_rt, n_full_rt, n_split, ntn, r) ? 1 : 0;
+    if (out[0]) { out[1] = r.rt; out[3] = r.nt; out[4] = r.split_tile; out[5] = r.ksplit; }
+    return MOE_OK;
+  }
+  if (kind == 1) {
+    if (ntm < 1) return MOE_ERR_BAD_SHAPE;
+    int slot, mt, nt;
+    out[0] = dw_block((int)block, ntm, ntn, slot, mt, nt) ? 1 : 0;
+    if (out[0]) { out[1] = slot; out[2] = mt; out[3] = nt; }
+    return MOE_OK;
+  }
+  return MOE_ERR_BAD_DTYPE;
+}
+
 int moe_workspace_bytes(const moe_cfg* cfg, size_t* bytes) {
   CHECK(check_cfg(cfg));
   REQUIRE(bytes);

@@ -68,6 +68,76 @@ inline TileMap tile_map_at(void* ws_region, int max_tiles, int E) {
 }
 inline int max_row_tiles(int A, int E, int tile_rows) { return (A + tile_rows - 1) / tile_rows + E; }
 
+// ---- block -> tile numbering of the MFMA grouped GEMMs (host and device: a host-side test enumerates it) ----
+#ifdef __HIPCC__
+#define MOE_HD __host__ __device__
+#else
+#define MOE_HD
+#endif
+constexpr int NUM_XCD = 8;
+
+// Row-tile GEMMs.  Tiles are numbered (row tile, column tile) with the full row tiles first.  The full region
+// is walked in groups of GROUP row tiles, column by column, and cut into one contiguous range per XCD
+// (workgroups go to the eight XCDs round-robin), so tiles that run together on an XCD share operand panels in
+// its L2.  The partly filled row tiles follow in dispatch order: they are the last blocks to start and fill
+// the chip's final round.
+MOE_HD inline bool block_to_tile(int b, int n_rt, int n_full_rt, int ntn, int& rt, int& nt) {
+  constexpr int GROUP = 4;
+  const int n_full = n_full_rt * ntn, n_all = n_rt * ntn;
+  if (b >= n_all) return false;
+  if (b >= n_full) {                          // partial row tiles, largest first, in dispatch order
+    rt = n_full_rt + (b - n_full) / ntn;
+    nt = (b - n_full) % ntn;
+    return true;
+  }
+  const int per = n_full / NUM_XCD;           // full tiles per XCD; the few left over keep their own index
+  const int logical = (b < per * NUM_XCD) ? (b % NUM_XCD) * per + b / NUM_XCD : b;
+  const int per_group = GROUP * ntn;
+  const int grp = logical / per_group, in = logical % per_group;
+  const int first = grp * GROUP, gsz = (GROUP < n_full_rt - first) ? GROUP : n_full_rt - first;
+  rt = first + in % gsz;
+  nt = in / gsz;
+  return true;
+}
+
+// Block vb of a row-tile GEMM launch over n_rt row tiles (the first n_full_rt of them walked XCD by XCD), of
+// which the last n_sp are split along K: those are not part of the regular numbering; their blocks follow it,
+// SPLIT_K per (row tile, column tile), each with a K part of its own.  False: no tile (surplus block).
+struct RowBlock { int rt, nt, split_tile, ksplit; };
+MOE_HD inline bool row_tile_block(int vb, int n_rt, int n_full_rt, int n_sp, int ntn, RowBlock& r) {
+  const int n_reg = n_rt - n_sp;
+  r.split_tile = -1;
+  r.ksplit = 0;
+  if (vb < n_reg * ntn) return block_to_tile(vb, n_reg, n_full_rt, ntn, r.rt, r.nt);
+  const int q = vb - n_reg * ntn;
+  if (q >= n_sp * ntn * SPLIT_K) return false;
+  r.ksplit = q % SPLIT_K;
+  r.nt = (q / SPLIT_K) % ntn;
+  r.split_tile = q / (SPLIT_K * ntn);
+  r.rt = n_reg + r.split_tile;
+  return true;
+}
+
+// Block vb of a weight-gradient launch: tile (expert slot in descending-size order, m tile, n tile).  Every
+// expert's ntm x ntn tiles are split evenly over the XCDs (block b runs on XCD b % 8), so a skewed load is
+// even across XCDs.  An XCD's share of an expert is a contiguous range of the expert's tiles in patch order
+// (four m tiles at a time, column by column), so the 32 tiles it runs together form a 4 x 8 patch that needs
+// 12 operand panels per K stage from its L2 instead of up to 18 with the tiles dealt one by one.
+MOE_HD inline bool dw_block(int vb, int ntm, int ntn, int& slot, int& mt, int& nt) {
+  constexpr int GROUP = 4;
+  const int P = ntm * ntn, P8 = (P + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+  const int q = vb % P8, x = q % NUM_XCD, i = q / NUM_XCD;      // XCD, and the block's turn on it for this expert
+  const int base = P / NUM_XCD, extra = P % NUM_XCD;            // XCD x takes base (+1 for the first `extra`) tiles
+  if (i >= base + (x < extra ? 1 : 0)) return false;
+  const int p = x * base + (x < extra ? x : extra) + i;         // position in patch order
+  slot = vb / P8;
+  const int per_group = GROUP * ntn, grp = p / per_group, in = p % per_group;
+  const int first = grp * GROUP, gsz = (GROUP < ntm - first) ? GROUP : ntm - first;
+  mt = first + in % gsz;
+  nt = in / gsz;
+  return true;
+}
+
 enum GemmMode {
   MODE_NN = 0,  // C[rows, N] = A[rows, K] * B_e[K, N]          (forward GEMMs)
   MODE_NT = 1,  // C[rows, N] = A[rows, K] * B_e[N, K]^T        (dH, dX)

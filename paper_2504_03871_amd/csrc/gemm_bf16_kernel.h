@@ -67,7 +67,6 @@ template <> struct Half16<f16> {
   }
 };
 
-constexpr int NUM_XCD = 8;
 constexpr int NBUF = 4;   // LDS stages in the ring
 
 // ---- LDS layouts -------------------------------------------------------------------------------
@@ -148,30 +147,6 @@ struct Stage {
     }
   }
 };
-
-// Block -> tile.  Tiles are numbered (row tile, column tile) with the full row tiles first.  The
-// full region is walked in groups of GROUP row tiles, column by column, and cut into one contiguous
-// range per XCD (workgroups go to the eight XCDs round-robin), so tiles that run together on an XCD
-// share operand panels in its L2.  The partly filled row tiles follow in dispatch order: they are the
-// last blocks to start and fill the chip's final round.
-__device__ __forceinline__ bool block_to_tile(int b, int n_rt, int n_full_rt, int ntn, int& rt, int& nt) {
-  constexpr int GROUP = 4;
-  const int n_full = n_full_rt * ntn, n_all = n_rt * ntn;
-  if (b >= n_all) return false;
-  if (b >= n_full) {                          // partial row tiles, largest first, in dispatch order
-    rt = n_full_rt + (b - n_full) / ntn;
-    nt = (b - n_full) % ntn;
-    return true;
-  }
-  const int per = n_full / NUM_XCD;           // full tiles per XCD; the few left over keep their own index
-  const int logical = (b < per * NUM_XCD) ? (b % NUM_XCD) * per + b / NUM_XCD : b;
-  const int per_group = GROUP * ntn;
-  const int grp = logical / per_group, in = logical % per_group;
-  const int first = grp * GROUP, gsz = min(GROUP, n_full_rt - first);
-  rt = first + in % gsz;
-  nt = in / gsz;
-  return true;
-}
 
 // ---- fast activation pieces for bf16 outputs ----------------------------------------------------
 __device__ __forceinline__ float sigmoid_fast(float g) {
@@ -284,18 +259,10 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
       // instead of up to 18 with the tiles dealt one by one (that order made dW2 of the Mixtral-like shape
       // read 6.9 times its operands through the fabric).
       const int ntm = (g.M + BM - 1) / BM;
-      const int P = ntm * ntn, P8 = (P + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
-      const int q = vb % P8;
-      const int p = (q % NUM_XCD) * (P8 / NUM_XCD) + q / NUM_XCD;   // position in patch order
-      if (p >= P) return;
-      e = g.order[vb / P8];
-      {
-        constexpr int GROUP = 4;
-        const int per_group = GROUP * ntn, grp = p / per_group, in = p % per_group;
-        const int first = grp * GROUP, gsz = min(GROUP, ntm - first);
-        m0 = (first + in % gsz) * BM;
-        nt = in / gsz;
-      }
+      int slot, mt;
+      if (!dw_block(vb, ntm, ntn, slot, mt, nt)) return;
+      e = g.order[slot];
+      m0 = mt * BM;
       rt = 0;
       int l, h;
       share_of(g.lo, g.hi, g.kept[e], e, l, h);
@@ -309,17 +276,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
       // split-K (gemm.h): the last n_sp row tiles are not part of the regular numbering; their blocks
       // follow it, SPLIT_K per (row tile, column tile), each with a K range of its own
       const int n_sp = (CAN_SPLIT && g.split_ws != nullptr) ? g.ntiles[2] : 0;
-      const int n_reg = n_rt - n_sp;
-      if (vb < n_reg * ntn) {
-        if (!block_to_tile(vb, n_reg, g.ntiles[1], ntn, rt, nt)) return;
-        klen = g.K;
-      } else {
-        const int q = vb - n_reg * ntn;
-        if (q >= n_sp * ntn * SPLIT_K) return;
-        ksplit = q % SPLIT_K;
-        nt = (q / SPLIT_K) % ntn;
-        split_tile = q / (SPLIT_K * ntn);
-        rt = n_reg + split_tile;
+      RowBlock rb;
+      if (!row_tile_block(vb, n_rt, g.ntiles[1], n_sp, ntn, rb)) return;
+      rt = rb.rt;
+      nt = rb.nt;
+      klen = g.K;
+      if (rb.split_tile >= 0) {
+        split_tile = rb.split_tile;
+        ksplit = rb.ksplit;
         klen = g.K / SPLIT_K;
         kbase = ksplit * klen;
       }

@@ -33,6 +33,24 @@ def test_unbounded_matches_oracle_exactly():
         assert want == got, (n, L, M, N, ta, t_attn, t_exp)
 
 
+def test_unbounded_matches_the_exact_cumulative_form():
+    """The library against the oracle's second form (exact rationals, floors of cumulative quotients), which is
+    not a copy of the listing; inputs whose quotients sit within 1e-9 of an integer are skipped."""
+    rnd = random.Random(13)
+    checked = 0
+    for _ in range(2000):
+        M, N = rnd.choice(GROUPS)
+        n, L = N * rnd.randint(1, 8), rnd.randint(1, 64)
+        ta = rnd.uniform(0.1, 5.0)
+        t_exp, t_attn = ta + rnd.uniform(-0.5, 6.0), rnd.uniform(0.05, 5.0)
+        want, margin = A.plan_exact(n, L, M, N, ta, t_attn, t_exp)
+        if margin < 1e-9:
+            continue
+        checked += 1
+        assert B.moe_asymea_plan(n, L, M, N, ta, t_attn, t_exp) == want, (n, L, M, N, ta, t_attn, t_exp)
+    assert checked > 1900
+
+
 def test_bounded_matches_oracle_exactly():
     rnd = random.Random(4)
     for _ in range(2000):

@@ -167,3 +167,23 @@ def test_expert_owner_partition():
         A.expert_owner(8, 4, 2, 1)      # not a multiple of n_2
     with pytest.raises(ValueError):
         A.expert_owner(8, 1, 1, 9)
+
+
+def test_exact_cumulative_form_agrees_with_the_listing_and_the_figure():
+    """`plan` (the listing's loop in doubles) against `plan_exact` (floors of exact cumulative quotients)."""
+    import random
+    assert A.plan_exact(6, 3, 1, 1, 3.0, 3.0, 4.0)[0] == [0, 1, 1]
+    assert A.plan_exact(6, 4, 1, 1, 3.0, 3.0, 2.5)[0] == [0, 0, 0, 0]
+    rnd = random.Random(11)
+    checked = 0
+    for _ in range(3000):
+        M, N = rnd.choice([(1, 1), (1, 2), (2, 1), (2, 4), (4, 2), (3, 9)])
+        n, L = N * rnd.randint(1, 8), rnd.randint(1, 48)
+        ta = rnd.uniform(0.1, 5.0)
+        te, tx = ta + rnd.uniform(-0.5, 6.0), rnd.uniform(0.05, 5.0)
+        want, margin = A.plan_exact(n, L, M, N, ta, tx, te)
+        if margin < 1e-9:        # a quotient this close to an integer: double rounding may flip its floor
+            continue
+        checked += 1
+        assert A.plan(n, L, M, N, ta, tx, te) == want, (n, L, M, N, ta, tx, te)
+    assert checked > 2900
