@@ -43,7 +43,7 @@ size_t route_wfrag_bytes(int d, int E);   // gate weight in MFMA operand layout 
 
 constexpr int DISPATCH_CHUNK = 1024;   // assignments ranked by one block
 constexpr int ROUTE_BWD_TOKENS = 128;  // tokens per block of the gate-backward kernel (many experts)
-constexpr int ROUTE_BWD_DENSE_E = 16;  // up to this many experts the gate weight gradient keeps a dense [E] row in registers
+constexpr int ROUTE_BWD_DENSE_E = 64;  // up to this many experts the gate weight gradient is accumulated densely in registers, 16 experts per block
 
 // Geometry of the dense gate-weight-gradient kernel: a thread owns one 16-byte column group, cg_pow2
 // threads span a token row (a power of two, at most 256; wider rows take several column blocks), a block

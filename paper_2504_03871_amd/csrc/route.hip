@@ -441,8 +441,8 @@ __global__ __launch_bounds__(RB_MAX_WAVES* WAVE) void route_bwd_dwr_kernel(
   }
 }
 
-// Few experts (E <= EB <= ROUTE_BWD_DENSE_E): every thread keeps the whole [EB] x (16-byte column group)
-// block of the weight gradient in registers and adds d_logits[t][:] (x) x[t][cols] token after token,
+// Few experts (at most ROUTE_BWD_DENSE_E, in groups of EB <= 16 along gridDim.z): every thread keeps an [EB] x
+// (16-byte column group) block of the weight gradient in registers and adds d_logits[t][:] (x) x[t][cols] token after token,
 // zeros of the unselected experts included; no LDS read-modify-write, no branches, one 16-byte load of
 // x per token.  The slice's d_logits rows are staged in LDS once, padded with zeros to EB per row, and
 // read back as 16-byte broadcasts.  Geometry: RouteBwdGeom.
@@ -456,13 +456,14 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_dense_kernel(
   const int c = threadIdx.x & (gm.cg_pow2 - 1), slice = threadIdx.x / gm.cg_pow2;
   const int col = (blockIdx.x * gm.cg_pow2 + c) * VN;
   const int row = blockIdx.y * gm.slices_per_block + slice;   // row of partial sums = token slice
+  const int e0 = blockIdx.z * EB;                               // this block's group of experts (more than EB experts: x is read once per group)
   const int t0 = row * gm.tps;
   const int nt = max(0, min(gm.tps, Tn - t0));
   {   // the block's slices are adjacent tokens: one pass over them, zero past the last token and past E
     const int tb = blockIdx.y * gm.slices_per_block * gm.tps, n = gm.slices_per_block * gm.tps * EB;
     for (int i = threadIdx.x; i < n; i += 256) {
       const int t = tb + i / EB, e = i % EB;
-      s_dl[i] = (t < Tn && e < E) ? d_logits[(size_t)t * E + e] : 0.f;
+      s_dl[i] = (t < Tn && e0 + e < E) ? d_logits[(size_t)t * E + e0 + e] : 0.f;
     }
   }
   __syncthreads();
@@ -496,10 +497,10 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_dense_kernel(
   float* out = partials + (size_t)row * E * d + col;   // [row][e][col]: 16-byte stores, adjacent lanes adjacent
 #pragma unroll
   for (int e = 0; e < EB; ++e)
-    if (e < E) {
+    if (e0 + e < E) {
 #pragma unroll
       for (int v = 0; v < VN; v += 4)
-        *reinterpret_cast<float4*>(out + (size_t)e * d + v) = make_float4(acc[e][v], acc[e][v + 1], acc[e][v + 2], acc[e][v + 3]);
+        *reinterpret_cast<float4*>(out + (size_t)(e0 + e) * d + v) = make_float4(acc[e][v], acc[e][v + 1], acc[e][v + 2], acc[e][v + 3]);
     }
 }
 
@@ -608,8 +609,8 @@ static int route_bwd_typed(const moe_cfg* c, const void* x, const float* Wr, con
   if (dWr == nullptr) return MOE_OK;
   if (c->E <= ROUTE_BWD_DENSE_E) {
     const RouteBwdGeom gm = route_bwd_geom(c->T, c->d_model, (int)sizeof(T));
-    const dim3 grid(gm.col_blocks, gm.row_blocks);
     const int eb = c->E <= 4 ? 4 : (c->E <= 8 ? 8 : 16);
+    const dim3 grid(gm.col_blocks, gm.row_blocks, (c->E + eb - 1) / eb);
     const size_t lds = (size_t)gm.slices_per_block * gm.tps * eb * 4;
 #define MOE_DWR_DENSE(EB) \
   route_bwd_dwr_dense_kernel<T, EB><<<grid, 256, lds, s>>>((const T*)x, d_logits, partials, c->T, c->d_model, c->E, gm)
