@@ -195,6 +195,48 @@ def run_workload(name, steps, warmup, args, full):
     flops = gemm_flops(w, S_rows, S, kern_ms)
     dom = max(flops, key=lambda n: np.mean(kern_ms[n]))
 
+    # ---- optional: the shader clock the chip sustains under this work.  One-wave samplers on side streams record
+    # (shader counter, 100 MHz counter) pairs; single samples on the work's own stream before and after the steps
+    # bracket the loaded interval in the same 100 MHz time base, so only samples taken inside it are counted (a side
+    # stream that happens to share a hardware queue with the work runs before or after it and contributes none).
+    if full and args.clock_probe:
+        n_s, sleeps, n_side = 8000, 10, 3    # about 35-50 us between samples, 0.3-0.4 s per sampler
+        sides = [torch.cuda.Stream(device=dev) for _ in range(n_side)]
+        samples = [torch.zeros(2 * n_s, dtype=torch.int64, device=dev) for _ in range(n_side)]
+        marks = torch.zeros(4, dtype=torch.int64, device=dev)
+        torch.cuda.synchronize()
+        for st_, sm_ in zip(sides, samples):
+            with torch.cuda.stream(st_):
+                B.moe_bench_clock_probe(sm_, n_s, sleeps)
+        time.sleep(0.02)               # the first samples see an idle chip
+        B.moe_bench_clock_probe(marks[0:2], 1, 0)
+        n_probe_steps = 4
+        for _ in range(n_probe_steps):
+            step()
+        B.moe_bench_clock_probe(marks[2:4], 1, 0)
+        torch.cuda.synchronize()
+        mk = marks.cpu().numpy()
+        t_lo, t_hi = int(mk[1]), int(mk[3])
+        loaded, idle = [], []
+        for sm_ in samples:
+            sm = sm_.cpu().numpy().reshape(n_s, 2).astype(np.int64)
+            dt_, dr_ = np.diff(sm[:, 0]).astype(np.float64), np.diff(sm[:, 1]).astype(np.float64)
+            ok = dr_ > 0
+            mhz = np.where(ok, dt_ / np.maximum(dr_, 1.0) * 100.0, 0.0)
+            inside = ok & (sm[:-1, 1] >= t_lo) & (sm[1:, 1] <= t_hi)
+            before = ok & (sm[1:, 1] < t_lo)
+            loaded.append(mhz[inside]); idle.append(mhz[before])
+        loaded, idle = np.concatenate(loaded), np.concatenate(idle)
+        res_clock = {"samples_under_load": int(len(loaded)), "samples_idle": int(len(idle)),
+                     "idle_MHz_median": round(float(np.median(idle)), 1) if len(idle) else None,
+                     "under_load_MHz_median": round(float(np.median(loaded)), 1) if len(loaded) else None,
+                     "under_load_MHz_p10": round(float(np.percentile(loaded, 10)), 1) if len(loaded) else None,
+                     "under_load_MHz_p90": round(float(np.percentile(loaded, 90)), 1) if len(loaded) else None,
+                     "loaded_interval_ms": round((t_hi - t_lo) / 1e5, 2),
+                     "steps_in_interval": n_probe_steps, "nominal_MHz": 2400}
+    else:
+        res_clock = None
+
     # ---- timed region: exactly K steps, only the dominant kernel carries its event pair
     evs.arm(L.cfg, {dom: steps})
     torch.cuda.synchronize()
@@ -216,7 +258,7 @@ def run_workload(name, steps, warmup, args, full):
     workload = (f"{w.name}: T={w.T} d_model={w.d} d_ff={w.f} E={w.E} top-{w.k} "
                 f"{'SwiGLU' if swi else 'GELU'} rows_computed={S_rows}"
                 + (", activation checkpointing (gate, dispatch, GEMM1 repeated)" if args.checkpoint else ""))
-    res = {"w": w, "inp": inp, "S_rows": S_rows, "ms_per_step": ms_per_step, "all_gemms": all_gemms, "workload": workload,
+    res = {"w": w, "inp": inp, "S_rows": S_rows, "clock_probe": res_clock, "ms_per_step": ms_per_step, "all_gemms": all_gemms, "workload": workload,
            "dtype": {S.DT_BF16: "bf16", S.DT_F16: "f16"}.get(w.dtype, "f32")}
     if not full:
         del L
@@ -358,6 +400,9 @@ def main():
                          "activations are computed again before the backward (not the default metric)")
     ap.add_argument("--f16", action="store_true",
                     help="run the bf16 workloads with fp16 storage instead (the paper's FP16 mixed precision; not the default metric)")
+    ap.add_argument("--clock-probe", action="store_true",
+                    help="sample the shader clock with a one-wave kernel on a second stream while steps run "
+                         "(evidence for the clock the chip sustains under the GEMMs; not part of the timed region)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB copy with the library's streaming kernel three times "
                          "(calibrates rocprofv3 byte counters)")
@@ -439,6 +484,7 @@ def main():
         "kernels": r["kernels"],
         "stages": r["stages"],
         "device": r["device"],
+        "clock_probe": r.get("clock_probe"),
         "other_workloads": others,
     }
     print(json.dumps(out))

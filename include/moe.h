@@ -282,6 +282,15 @@ MOE_API int moe_asymea_shares(int32_t n, int32_t M, int32_t N, int32_t o_l, int3
                       int32_t* slice_lo, int32_t* slice_hi);
 
 /*
+ * Benchmark aid, not a step of the layer: a one-wave kernel that writes n pairs (shader-clock counter, 100 MHz
+ * real-time counter) to `samples` (device uint64[2 n]), pausing `sleeps` (0..1000) sleep instructions of about
+ * 8000 shader cycles between pairs.  Launched on a second stream next to other work it shows the clock the chip
+ * sustains under that work: (difference of the first) / (difference of the second) x 100 MHz per interval.
+ * The loop is bounded (n <= 2^20), so the kernel always ends.
+ */
+MOE_API int moe_bench_clock_probe(uint64_t* samples, int32_t n, int32_t sleeps, void* stream);
+
+/*
  * Introspection for tests, HOST-ONLY (nothing is enqueued, `out` is a HOST int32[6]): which tile block number
  * `block` of a grouped-GEMM launch of the 16-bit path computes, by the same code the kernels run.
  * kind 0, row-tile GEMMs (x W, dy W^T) over n_rt row tiles of which the first n_full_rt are full and the last

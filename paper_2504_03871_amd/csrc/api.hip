@@ -87,6 +87,17 @@ __global__ __launch_bounds__(256) void bench_stream_kernel(bs_u32x4* __restrict_
   }
 }
 
+// One lane samples the shader-clock counter and the 100 MHz real-time counter n times, sleeping in between
+// (a bounded loop: the kernel always ends).  Two consecutive samples give the shader clock over that interval.
+__global__ void clock_probe_kernel(unsigned long long* __restrict__ out, int n, int sleeps) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  for (int i = 0; i < n; ++i) {
+    out[2 * i] = __builtin_amdgcn_s_memtime();
+    out[2 * i + 1] = __builtin_amdgcn_s_memrealtime();
+    for (int s = 0; s < sleeps; ++s) __builtin_amdgcn_s_sleep(127);
+  }
+}
+
 static int check_ws(const moe_cfg* c, const void* ws, size_t ws_bytes) {
   return (ws != nullptr && ws_bytes < ws_layout(c).total) ? MOE_ERR_WORKSPACE : MOE_OK;
 }
@@ -140,6 +151,14 @@ int moe_bench_stream(void* dst, const void* src, size_t bytes, int32_t mode, voi
   const unsigned grid = (unsigned)(want < 256 * 16 ? want : 256 * 16);
   if (mode == 0) bench_stream_kernel<false><<<grid, 256, 0, (hipStream_t)stream>>>((bs_u32x4*)dst, (const bs_u32x4*)src, n16);
   else bench_stream_kernel<true><<<grid, 256, 0, (hipStream_t)stream>>>((bs_u32x4*)dst, nullptr, n16);
+  return launch_status();
+}
+
+int moe_bench_clock_probe(uint64_t* samples, int32_t n, int32_t sleeps, void* stream) {
+  REQUIRE(samples);
+  ALIGNED(samples);
+  if (n < 1 || n > (1 << 20) || sleeps < 0 || sleeps > 1000) return MOE_ERR_BAD_SHAPE;
+  clock_probe_kernel<<<1, 64, 0, (hipStream_t)stream>>>(reinterpret_cast<unsigned long long*>(samples), n, sleeps);
   return launch_status();
 }
 

@@ -4,7 +4,8 @@
                                              [--bench-json FILE] [--out profiles]
 
 DIR is the `-d` directory of a rocprofv3 run made with `--output-format csv -o <workload>`:
-  --trace  rocprofv3 --kernel-trace --stats ... -- python3 bench.py --workload W --also none --no-cpu-baseline
+  (all runs with -M, mangled kernel names: the demangler garbles the bf16 template argument)
+  --trace  rocprofv3 -M --kernel-trace --stats ... -- python3 bench.py --workload W --also none --no-cpu-baseline
   --fetch  rocprofv3 --pmc FETCH_SIZE ...       -- python3 bench.py --workload W --also none --no-cpu-baseline --steps 3 --warmup 1
   --write  rocprofv3 --pmc WRITE_SIZE ...       (same bench command)
   --busy   rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_ANY
@@ -34,18 +35,19 @@ def find_csv(d, suffix):
 
 
 def gemm_role(name, nth=0):
-    """(bench bracket, description) of a grouped-GEMM kernel name; nth = index of the launch within a step for
-    the weight-gradient kernel, which serves dW2, dW1 (and dW1b) in that order."""
-    m = re.search(r"gemm_bf16_pair_kernel<\(?(?:moe::GemmMode\))?(\d), \(?(?:moe::Epilogue\))?(\d), (false|true)", name)
+    """(bench bracket, description) of a grouped-GEMM kernel from its MANGLED name (rocprofv3 -M: its demangler
+    does not know the bf16 type); nth = index of the launch within a step for the weight-gradient kernel, which
+    serves dW2, dW1 (and dW1b) in that order."""
+    m = re.search(r"gemm_bf16_pair_kernelIDF16[b_]Li(\d)ELi(\d)ELb([01])E", name)
     if m:
-        mode, epi, chain = int(m.group(1)), int(m.group(2)), m.group(3) == "true"
+        epi, chain = int(m.group(2)), m.group(3) == "1"
         if epi in (3, 4):
             return "dh_bwd", "dH = dy W2^T with the activation-derivative epilogue, and dW2 = H^T dy, one launch"
         return "dx_bwd", "dx = dA W1^T" + (" (two chained products)" if chain else "") + ", and dW1 = x_perm^T dA, one launch"
-    m = re.search(r"gemm_bf16_kernel<\(?(?:moe::GemmMode\))?(\d), \(?(?:moe::Epilogue\))?(\d), (false|true), (false|true)", name)
+    m = re.search(r"gemm_bf16_kernelIDF16[b_]Li(\d)ELi(\d)ELb([01])ELb([01])E", name)
     if not m:
         return None, ""
-    mode, epi, dual, chain = int(m.group(1)), int(m.group(2)), m.group(3) == "true", m.group(4) == "true"
+    mode, epi, dual, chain = int(m.group(1)), int(m.group(2)), m.group(3) == "1", m.group(4) == "1"
     if mode == 0 and epi == 1:
         return "gemm1_fwd", "A = x_perm W1, H = gelu(A)"
     if mode == 0 and epi == 2:
@@ -62,11 +64,17 @@ def gemm_role(name, nth=0):
 
 
 def short(n):
-    m = re.search(r"(gemm_bf16(?:_pair)?_kernel<[^>]*>)", n)
+    """Readable form of a mangled kernel name: the function name and, for the GEMMs, the integer template arguments
+    <MODE, EPI, DUAL, CHAIN, BM, BN, BK, waves M, waves N, stages> (pair: <MODE1, EPI1, CHAIN1, BK1, NB1, MODE2, ...>)."""
+    m = re.search(r"_ZN3moe\d+([a-z_0-9]+?)I(.*?)EEv", n)
+    if m and m.group(1).startswith("gemm_bf16"):
+        args = re.findall(r"L[ib](\d+)E", m.group(2))
+        st = "bf16" if "DF16b" in m.group(2) else ("f16" if "DF16_" in m.group(2) else "")
+        return f"{m.group(1)}<{st}, {', '.join(args)}>"
+    m = re.search(r"_ZN3moe\d+([a-z_0-9]+?)(?:I|E)", n)
     if m:
-        return m.group(1).replace("(moe::GemmMode)", "").replace("(moe::Epilogue)", "")
-    m = re.search(r"(?:moe::)?([a-z_0-9]+_kernel)", n)
-    return m.group(1) if m else n.split("(")[0].replace("void ", "")
+        return m.group(1)
+    return n.split("(")[0].replace("void ", "")
 
 
 def per_kernel(path, counter=None):
@@ -105,7 +113,7 @@ def main():
         rows = list(csv.DictReader(open(find_csv(a.trace, "kernel_stats.csv"))))
         out = [f"# {title}: per-kernel durations", "",
                "Command (run from /tmp with TMPDIR=/tmp on the MI355X box):", "",
-               f"    rocprofv3 --kernel-trace --stats --output-format csv -d <out> -o {w} -- {bench_cmd}", "",
+               f"    rocprofv3 -M --kernel-trace --stats --output-format csv -d <out> -o {w} -- {bench_cmd}", "",
                "bench.py runs its warm-up steps, a detail pass (every kernel bracketed by events), the timed steps and a",
                "cold pass of the HBM-bound calls; durations in microseconds over all of them.", "",
                "| kernel | calls | avg us | min us | max us | % of GPU time | role |", "|---|---|---|---|---|---|---|"]
@@ -129,16 +137,16 @@ def main():
     if a.fetch and a.write:
         pf = per_kernel(find_csv(a.fetch, "counter_collection.csv"))
         pw = per_kernel(find_csv(a.write, "counter_collection.csv"))
-        copy = [k for k in pf if "bench_stream_kernel<false>" in k]
+        copy = [k for k in pf if "bench_stream_kernelILb0E" in k]
         if not copy:
-            raise SystemExit("no bench_stream_kernel<false> dispatch found for calibration")
+            raise SystemExit("no copy dispatch (bench_stream_kernel<false>) found for calibration")
         cf = max(v["FETCH_SIZE"] for _, v in pf[copy[0]])
         cw = max(v["WRITE_SIZE"] for _, v in pw[copy[0]])
         sf, sw = 524288.0 / cf, 524288.0 / cw
         lines = [f"# {title}: HBM traffic of the grouped-GEMM kernels from rocprofv3 counters", "",
                  "Commands (each counter in a run of its own; run from /tmp with TMPDIR=/tmp):", "",
-                 f"    rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out> -o {w} -- {bench_cmd} --steps 3 --warmup 1",
-                 f"    rocprofv3 --pmc WRITE_SIZE --output-format csv -d <out> -o {w} -- {bench_cmd} --steps 3 --warmup 1", "",
+                 f"    rocprofv3 -M --pmc FETCH_SIZE --output-format csv -d <out> -o {w} -- {bench_cmd} --steps 3 --warmup 1",
+                 f"    rocprofv3 -M --pmc WRITE_SIZE --output-format csv -d <out> -o {w} -- {bench_cmd} --steps 3 --warmup 1", "",
                  "Calibration: the library's 512 MiB streaming copy that bench.py times for its `device` entry (524288 KiB read,",
                  f"524288 KiB written) reads FETCH_SIZE = {cf:.1f} and WRITE_SIZE = {cw:.1f} per dispatch, so FETCH_SIZE is scaled",
                  f"by {sf:.3f} and WRITE_SIZE by {sw:.3f} to get KiB.  Averages over the dispatches of each kind.", "",
@@ -178,7 +186,7 @@ def main():
         pk = per_kernel(find_csv(a.busy, "counter_collection.csv"))
         lines = [f"# {title}: matrix-core occupancy of the grouped-GEMM launches from rocprofv3 counters", "",
                  "Command (run from /tmp with TMPDIR=/tmp on the MI355X box):", "",
-                 "    rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_ANY SQ_INSTS_VALU_MFMA_MOPS_BF16 "
+                 "    rocprofv3 -M --pmc SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_ANY SQ_INSTS_VALU_MFMA_MOPS_BF16 "
                  f"SQ_VMEM_TA_ADDR_FIFO_FULL SQ_LDS_BANK_CONFLICT SQ_ACTIVE_INST_LDS --output-format csv -d <out> -o {w} -- {bench_cmd} --steps 3 --warmup 1", "",
                  "Averages per dispatch.  SQ_VALU_MFMA_BUSY_CYCLES counts the four SIMDs of a compute unit separately, so",
                  "busy / (4 x SQ_BUSY_CU_CYCLES) is the share of a busy compute unit's cycles in which a matrix core works.", "",

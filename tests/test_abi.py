@@ -147,6 +147,15 @@ def test_shapes_whose_byte_offsets_pass_32_bits_are_rejected():
     assert ei.value.code == -2
 
 
+def test_clock_probe_validation():
+    s = ctypes.c_void_p(0)
+    lib = B.lib()
+    assert lib.moe_bench_clock_probe(None, 10, 1, s) == -1
+    assert lib.moe_bench_clock_probe(0x10008, 10, 1, s) == -5
+    assert lib.moe_bench_clock_probe(0x10000, 0, 1, s) == -2
+    assert lib.moe_bench_clock_probe(0x10000, 10, 1001, s) == -2
+
+
 def test_bench_stream_validation():
     s = ctypes.c_void_p(0)
     lib = B.lib()
