@@ -1,21 +1,25 @@
-// Grouped GEMM kernel for the gfx950 matrix cores with 16-bit storage: bf16 (v_mfma_f32_32x32x16_bf16) or
-// fp16 (v_mfma_f32_32x32x16_f16), fp32 accumulate.  The storage type ST is a template parameter of the one
+// Grouped GEMM kernel for the gfx950 matrix cores with 16-bit storage: bf16 (v_mfma_f32_16x16x32_bf16) or
+// fp16 (v_mfma_f32_16x16x32_f16), fp32 accumulate.  The storage type ST is a template parameter of the one
 // kernel; it selects the MFMA instruction, the conversions of the epilogues, and whether the GELU epilogues
 // look their function up (bf16: a table over all bf16 numbers fits in LDS) or evaluate it (fp16).
 //
-// Work decomposition: block tile BM x BN, WGM x WGN waves; a wave owns BN/WGN adjacent columns and the
-// 32-row bands b = wm, wm + WGM, ... of the tile, as a grid of 32x32 MFMA tiles; K advances BKT elements
-// per stage.  Interleaving the bands spreads a partly filled row tile over every wave row.
+// Why the 16 x 16 x 32 instruction and not 32 x 32 x 16 (same FLOP per cycle): the chip lowers its clock under
+// matrix-core load, and by how much depends on the instruction.  A loop of nothing but MFMAs, matrix cores
+// busy 99 % of the cycles in both cases, runs at 2.05 GHz (2140 TFLOP/s) with 16 x 16 x 32 and at 1.8 GHz
+// (1880 TFLOP/s) with 32 x 32 x 16, which moves twice the accumulator registers per FLOP.  In this kernel
+// the change was worth 4-6 % on x W and dy W^T and 1-2 % on x^T dy.
 //
-// Pipeline: a ring of NB (four) LDS stages filled by buffer loads that write LDS directly (no staging
-// registers, no LDS store instructions).  Iteration kt issues the loads of stage kt+NB-1, multiplies
-// stage kt while reading the fragments of stage kt+1 into a third register slot, then waits for its
-// own loads of stage kt+2 and joins the block barrier.  A global load has one to two iterations of
-// MFMA work to land, an LDS read a whole K step, and the barrier only guards buffer reuse.
-// Operands whose K index is contiguous (both of dy W^T, the activations of x W) use a second pipeline with
-// two 64-wide stages instead: a 32-wide stage fetches such an operand as 64-byte pieces of 128-byte lines,
-// which fills the address FIFO of the memory pipe (counters: full thirteen times as often) and holds the
-// matrix cores to 0.64 of their cycles against 0.72 with whole lines.
+// Work decomposition: block tile BM x BN, WGM x WGN waves; a wave owns BN/WGN adjacent columns and the
+// 32-row bands b = wm, wm + WGM, ... of the tile, each band two 16-row MFMA tiles; K advances BKT elements
+// per stage, 32 per MFMA ("K step").  Interleaving the bands spreads a partly filled row tile over every
+// wave row.
+//
+// Pipelines, both fed by buffer loads that write LDS directly (no staging registers, no LDS store
+// instructions).  (i) A ring of NB (four) 32-wide stages: iteration kt issues the loads of stage kt+NB-1,
+// multiplies stage kt while reading the fragments of stage kt+1, then waits for its own loads of stage kt+2
+// and joins the block barrier.  (ii) Operands whose K index is contiguous (both of dy W^T, the activations
+// of x W) use two 64-wide stages instead: a 32-wide stage fetches such an operand as 64-byte pieces of
+// 128-byte lines, which fills the address FIFO of the memory pipe (counters: full thirteen times as often).
 // The direct loads are raw instructions: if the compiler knew that they write LDS it would wait for
 // every outstanding load before each LDS read it cannot prove disjoint.  The pipeline orders loads and
 // reads itself (explicit vmcnt waits, block barriers); the LDS reads stay compiler-tracked.
@@ -29,9 +33,8 @@
 // so that every output (and every saved tensor the backward epilogues read) moves as 8-byte (bf16) or
 // 16-byte (fp32 weight gradients) pieces per lane that fill whole 128-byte lines.
 //
-// MFMA 32x32x16 register layout (checked on the hardware): lane l supplies row/column l%32 and the
-// eight K values (l/32)*8..+7 of the step; accumulator register v of lane l is row
-// (v/4)*8 + (l/32)*4 + v%4, column l%32 of the 32x32 tile.
+// MFMA 16x16x32 register layout: lane l supplies row/column l%16 and the eight K values (l/16)*8..+7 of
+// the step; accumulator register v of lane l is row (l/16)*4 + v, column l%16 of the 16x16 tile.
 #pragma once
 #include "gemm.h"
 
@@ -39,7 +42,6 @@ namespace moe {
 
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
@@ -53,8 +55,8 @@ template <> struct Half16<bf16> {
   static __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return pack_bf16x2(lo, hi); }
   static __device__ __forceinline__ float lo(uint32_t u) { return __uint_as_float(u << 16); }
   static __device__ __forceinline__ float hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
-  static __device__ __forceinline__ f32x16 mfma(const bf16x8& a, const bf16x8& b, const f32x16& c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  static __device__ __forceinline__ f32x4 mfma(const bf16x8& a, const bf16x8& b, const f32x4& c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
   }
 };
 template <> struct Half16<f16> {
@@ -62,8 +64,8 @@ template <> struct Half16<f16> {
   static __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return pack_f16x2(lo, hi); }
   static __device__ __forceinline__ float lo(uint32_t u) { return f16_bits_to_f32(u & 0xffffu); }
   static __device__ __forceinline__ float hi(uint32_t u) { return f16_bits_to_f32(u >> 16); }
-  static __device__ __forceinline__ f32x16 mfma(const bf16x8& a, const bf16x8& b, const f32x16& c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  static __device__ __forceinline__ f32x4 mfma(const bf16x8& a, const bf16x8& b, const f32x4& c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
   }
 };
 
@@ -79,16 +81,18 @@ __device__ __forceinline__ int kc_off(int row, int chunk) {
   return row * (BKT * 2) + ((chunk ^ ((row / RP) & (CPR - 1))) << 4);
 }
 // K-strided tile: [BKT][W] bf16; the 64-byte granules of a K row are XOR-swizzled with k%4, so the four
-// K rows that one transposing read touches fall into different bank groups.
+// K rows that one 16-lane block of a transposing read touches fall into different bank groups, and the
+// 32-byte halves of a granule with (k/8)%2, which separates two blocks that read the same columns eight K
+// rows apart (counters: no bank conflicts).
 template <int W>
 __device__ __forceinline__ int ks_off(int krow, int col_byte) {
-  return krow * (W * 2) + ((((col_byte >> 6) ^ (krow & 3)) << 6) | (col_byte & 63));
+  return krow * (W * 2) + (col_byte ^ (((krow & 3) << 6) | (((krow >> 3) & 1) << 5)));
 }
 
-// Fragment reads.  Eight K values of one K step for column l%32 of a K-strided tile come from two
-// transposing reads: the instruction works on blocks of 16 lanes, lane s of a block reads 8 bytes at
-// (K row s/4, columns 4*(s%4)..+3) and receives the four K rows of column s; the second read lies
-// four K rows further on.  `p` is the lane's address of the first read.
+// Fragment reads.  The eight K values of one lane (column l%16, K chunk l/16 of the step) of a K-strided
+// tile come from two transposing reads: the instruction works on blocks of 16 lanes, lane s of a block
+// reads 8 bytes at (K row s/4, columns 4*(s%4)..+3) and receives the four K rows of column s; the second
+// read lies four K rows further on.  `p` is the lane's address of the first read.
 template <int W>
 __device__ __forceinline__ bf16x8 lds_read_ks2(const char* p) {
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -143,7 +147,7 @@ struct Stage {
       constexpr int RP = 256 / (BKT * 2);
       return (unsigned)r * pitch + (unsigned)(pc ^ ((r / RP) & (CPR - 1))) * 16u;
     } else {
-      return (unsigned)r * pitch + (unsigned)((((pc >> 2) ^ (r & 3)) << 2) | (pc & 3)) * 16u;
+      return (unsigned)r * pitch + (unsigned)(pc ^ (((r & 3) << 2) | (((r >> 3) & 1) << 1))) * 16u;
     }
   }
 };
@@ -232,13 +236,13 @@ template <typename ST, int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN,
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, char* smem) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM / 32, WTN = BN / WGN / 32;
-  constexpr int KS = BKT / 16;               // MFMA K steps per stage (even)
+  constexpr int KS = BKT / 32;               // MFMA K steps per stage
+  constexpr int TM = 2 * WTM, TNN = 2 * WTN; // 16 x 16 MFMA tiles of a wave
   constexpr bool A_KC = (MODE != MODE_TN);   // A stored with K contiguous
   constexpr bool B_KC = (MODE == MODE_NT);
   constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2;
   constexpr int STAGE = gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
-  static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of K steps per stage");
-  static_assert(NB >= 4 || (NB == 2 && KS == 4), "a ring of four or more 32-wide stages, or two 64-wide stages");
+  static_assert((NB >= 4 && KS == 1) || (NB == 2 && KS == 2), "a ring of four or more 32-wide stages, or two 64-wide stages");
   constexpr int D = NB - 1;   // ring pipeline: loads run D stages ahead of the MFMAs
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -296,17 +300,13 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
   }
   const int nvalid = min(BN, g.N - n0);
 
-  f32x16 acc[WTM][WTN], acc2[DUAL ? WTM : 1][DUAL ? WTN : 1];
+  f32x4 acc[TM][TNN], acc2[DUAL ? TM : 1][DUAL ? TNN : 1];
 #pragma unroll
-  for (int i = 0; i < WTM; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < WTN; ++j) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-      if constexpr (DUAL) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc2[i][j][v] = 0.f;
-      }
+    for (int j = 0; j < TNN; ++j) {
+      acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if constexpr (DUAL) acc2[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
   const int KT = (klen + BKT - 1) / BKT;
@@ -317,27 +317,28 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
   typedef Stage<A_KC, BM, NT, BKT> StA;
   typedef Stage<B_KC, BN, NT, BKT> StB;
 
-  // fragment read offsets inside a stage.  K-contiguous: one per K step (the row term and the 32-row
-  // stride are the same for every MFMA tile); K-strided: one per MFMA tile (K steps are a constant apart).
-  int a_fr[A_KC ? KS : WTM], b_fr[B_KC ? KS : WTN];
+  // fragment read offsets inside a stage.  Lane l of a 16 x 16 x 32 MFMA holds row (column) l % 16 and the
+  // eight K values of chunk l / 16.  K-contiguous: one offset per K step (MFMA tiles are a constant 16 rows
+  // apart); K-strided: one per MFMA tile (K steps are a constant apart).
+  int a_fr[A_KC ? KS : TM], b_fr[B_KC ? KS : TNN];
   if constexpr (A_KC) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) a_fr[ks] = kc_off<BKT>(wm * 32 + (lane & 31), ks * 2 + (lane >> 5));
+    for (int ks = 0; ks < KS; ++ks) a_fr[ks] = kc_off<BKT>(wm * 32 + (lane & 15), ks * 4 + (lane >> 4));
   } else {
 #pragma unroll
-    for (int i = 0; i < WTM; ++i)
-      a_fr[i] = ks_off<BM>(((lane >> 5) & 1) * 8 + ((lane & 15) >> 2),
-                           ((i * WGM + wm) * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2);
+    for (int i = 0; i < TM; ++i)
+      a_fr[i] = ks_off<BM>((lane >> 4) * 8 + ((lane & 15) >> 2),
+                           (((i >> 1) * WGM + wm) * 32 + (i & 1) * 16 + (lane & 3) * 4) * 2);
   }
   if constexpr (B_KC) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      b_fr[ks] = A_BYTES + kc_off<BKT>(wn * WTN * 32 + (lane & 31), ks * 2 + (lane >> 5));
+      b_fr[ks] = A_BYTES + kc_off<BKT>(wn * WTN * 32 + (lane & 15), ks * 4 + (lane >> 4));
   } else {
 #pragma unroll
-    for (int j = 0; j < WTN; ++j)
-      b_fr[j] = A_BYTES + ks_off<BN>(((lane >> 5) & 1) * 8 + ((lane & 15) >> 2),
-                                     ((wn * WTN + j) * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2);
+    for (int j = 0; j < TNN; ++j)
+      b_fr[j] = A_BYTES + ks_off<BN>((lane >> 4) * 8 + ((lane & 15) >> 2),
+                                     (wn * WTN * 32 + j * 16 + (lane & 3) * 4) * 2);
   }
 
   {
@@ -378,6 +379,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     static_assert(PEND < 64, "the wait counter has six bits");
     constexpr int WAIT_L = (PEND & 15) | ((PEND >> 4) << 14) | 0x70 | (15 << 8);   // s_waitcnt vmcnt(PEND) only
     constexpr int WAIT_0 = 0x70 | (15 << 8);                                       // s_waitcnt vmcnt(0) only
+    constexpr int WAIT_LGKM0 = 0xC07F;                                             // s_waitcnt lgkmcnt(0) only
     unsigned a_vo[StA::CH], b_vo[StB::CH];
 #pragma unroll
     for (int i = 0; i < StA::CH; ++i) a_vo[i] = StA::goff(i, tid, pa);
@@ -385,16 +387,16 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     for (int i = 0; i < StB::CH; ++i) b_vo[i] = StB::goff(i, tid, pb);
     const int wbase = wave * 1024;   // a wave's 64 lanes fill 1 KB of the tile per load
     const unsigned smem_base = lds_addr(smem);
-    // Fragments are read two K steps (one stage) ahead of the MFMAs that use them, into three register
-    // slots, so a read has a whole K step of MFMAs to land before anything waits for it.
-    static_assert(KS == 2 || NB == 2, "ring pipeline: the fragment slots rotate with two K steps per stage");
-    constexpr int NU = WTM + WTN * (DUAL ? 2 : 1);   // fragments read per K step
-    constexpr int NMI = WTM * WTN;                   // MFMAs per K step (DUAL: pairs)
-    constexpr int NR = NMI >= 4 ? 4 : NMI;           // scheduling regions per K step
-    constexpr int GM = NMI / NR;                     // MFMAs (pairs) per region
-    constexpr int L0 = (L + 1) / 2;                  // loads issued with K step 0
-    static_assert(NMI % NR == 0, "regions hold equal numbers of MFMAs");
-    bf16x8 af[3][WTM], bfr[3][WTN], bfr2[3][DUAL ? WTN : 1];
+    // A K step is the 32 K values of one MFMA: TM x TNN instructions per wave, cut into TM regions that the
+    // scheduler may not move instructions across (sched_barrier).  Region i holds the MFMAs of row tile i;
+    // behind them, the read of row tile i's A fragment for the NEXT K step, into the same registers (their
+    // last use has just been issued, and the fragment is not needed for another TM - 1 regions), in the
+    // first TNN regions one B fragment of the next step (into the other of two B register sets), and this
+    // region's share of the global -> LDS loads.  LDS reads and, above all, the global loads then arrive as a
+    // steady trickle: loads issued in one burst fill the address FIFO of the memory pipe, and a wave that
+    // cannot issue a load cannot issue the MFMAs behind it either.
+    constexpr int NR = TM;                           // regions per K step
+    bf16x8 af[TM], bfr[2][TNN], bfr2[2][DUAL ? TNN : 1];
 #define MOE_LOAD(kt_, buf_)                                                                                 \
   do {                                                                                                      \
     _Pragma("unroll") for (int q__ = 0; q__ < L; ++q__) MOE_LOAD1(kt_, buf_, q__);                          \
@@ -416,70 +418,53 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
         load_to_lds16(rb1, st__ + A_BYTES + B_BYTES + NT * 16 * c__, b_vo[c__] + kl__ * bstep);             \
     }                                                                                                       \
   } while (0)
-// read unit u_ (0 .. NU-1) of K step ks_ of the stage at buf_ into slot slot_: the A fragments, then the
-// B fragments (DUAL: then those of the second weight matrix)
-#define MOE_FRAG1(slot_, buf_, ks_, u_)                                                                     \
+// A fragment of row tile i_ / B fragment(s) of column tile j_ for K step ks_ of the stage at buf_
+#define MOE_FRAG_A(i_, buf_, ks_)                                                                           \
   do {                                                                                                      \
     const char* st__ = smem + (buf_);                                                                       \
-    if ((u_) < WTM) {                                                                                       \
-      const int i__ = (u_) < WTM ? (u_) : 0;                                                                \
-      if constexpr (A_KC) af[slot_][i__] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + i__ * WGM * 32 * BKT * 2); \
-      else af[slot_][i__] = lds_read_ks2<BM>(st__ + a_fr[i__] + (ks_) * 16 * BM * 2);                       \
-    } else if ((u_) < WTM + WTN) {                                                                          \
-      const int j__ = ((u_) - WTM) % WTN;                                                                   \
-      if constexpr (B_KC) bfr[slot_][j__] = *reinterpret_cast<const bf16x8*>(st__ + b_fr[ks_] + j__ * 32 * BKT * 2); \
-      else bfr[slot_][j__] = lds_read_ks2<BN>(st__ + b_fr[j__] + (ks_) * 16 * BN * 2);                      \
-    } else if constexpr (DUAL) {                                                                            \
-      const int j__ = ((u_) - WTM - WTN) % WTN;                                                             \
-      bfr2[slot_][j__] = lds_read_ks2<BN>(st__ + B_BYTES + b_fr[j__] + (ks_) * 16 * BN * 2);                \
-    }                                                                                                       \
+    if constexpr (A_KC)                                                                                     \
+      af[i_] = *reinterpret_cast<const bf16x8*>(st__ + a_fr[ks_] + ((i_) >> 1) * WGM * 32 * BKT * 2 + ((i_) & 1) * 16 * BKT * 2); \
+    else af[i_] = lds_read_ks2<BM>(st__ + a_fr[i_] + (ks_) * 32 * BM * 2);                                  \
   } while (0)
-#define MOE_FRAGS(slot_, buf_, ks_)                                                                         \
+#define MOE_FRAG_B(set_, j_, buf_, ks_)                                                                     \
   do {                                                                                                      \
-    _Pragma("unroll") for (int u__ = 0; u__ < NU; ++u__) MOE_FRAG1(slot_, buf_, ks_, u__);                  \
+    const char* st__ = smem + (buf_);                                                                       \
+    if constexpr (B_KC) bfr[set_][j_] = *reinterpret_cast<const bf16x8*>(st__ + b_fr[ks_] + (j_) * 16 * BKT * 2); \
+    else bfr[set_][j_] = lds_read_ks2<BN>(st__ + b_fr[j_] + (ks_) * 32 * BN * 2);                           \
+    if constexpr (DUAL) bfr2[set_][j_] = lds_read_ks2<BN>(st__ + B_BYTES + b_fr[j_] + (ks_) * 32 * BN * 2); \
   } while (0)
-// One K step, cut into NR regions that nothing crosses (sched_barrier).  A region holds its share of the
-// MFMAs of this K step, of the fragment reads for the same K step of the next stage, and of the global
-// loads of the stage D ahead (the first half of a stage's loads go with K step 0, the rest with K step 1):
-// LDS reads and, above all, the global->LDS loads then arrive as a steady trickle.  Loads issued in one
-// burst fill the address FIFO of the memory pipe, and a wave that cannot issue a load cannot issue the
-// MFMAs behind it either.
-#define MOE_STEP(ks_, cur_, tgt_, DO_NEXT_, DO_LOAD_, kt_, NI_)                                             \
+#define MOE_FRAGS(set_, buf_, ks_)                                                                          \
+  do {                                                                                                      \
+    _Pragma("unroll") for (int i__ = 0; i__ < TM; ++i__) MOE_FRAG_A(i__, buf_, ks_);                        \
+    _Pragma("unroll") for (int j__ = 0; j__ < TNN; ++j__) MOE_FRAG_B(set_, j__, buf_, ks_);                 \
+  } while (0)
+// One K step on B register set set_; DO_NEXT_: read the fragments of K step rks_ of the stage at rbuf_;
+// DO_LOAD_: issue the loads LQ0_ .. LQ0_+LQN_-1 of stage lkt_ into the buffer at lbuf_.
+#define MOE_STEP(set_, DO_NEXT_, rbuf_, rks_, DO_LOAD_, lkt_, lbuf_, LQ0_, LQN_, NI_)                       \
   do {                                                                                                      \
     _Pragma("unroll") for (int r__ = 0; r__ < NR; ++r__) {                                                  \
-      if (DO_NEXT_) {                                                                                       \
-        _Pragma("unroll") for (int u__ = 0; u__ < NU; ++u__)                                                \
-          if (u__ * NR / NU == r__) MOE_FRAG1(tgt_, b1, ks_, u__);                                          \
-      }                                                                                                     \
-      _Pragma("unroll") for (int m__ = r__ * GM; m__ < (r__ + 1) * GM; ++m__) {                             \
-        const int i__ = m__ / WTN, j__ = m__ % WTN;                                                         \
-        if (i__ < (NI_)) {                                                                                  \
-          acc[i__][j__] = Half16<ST>::mfma(af[cur_][i__], bfr[cur_][j__], acc[i__][j__]); \
-          if constexpr (DUAL)                                                                               \
-            acc2[i__][j__] = Half16<ST>::mfma(af[cur_][i__], bfr2[cur_][j__], acc2[i__][j__]); \
+      if ((r__ >> 1) < (NI_)) {                                                                             \
+        _Pragma("unroll") for (int j__ = 0; j__ < TNN; ++j__) {                                             \
+          acc[r__][j__] = Half16<ST>::mfma(af[r__], bfr[set_][j__], acc[r__][j__]);                         \
+          if constexpr (DUAL) acc2[r__][j__] = Half16<ST>::mfma(af[r__], bfr2[set_][j__], acc2[r__][j__]);  \
         }                                                                                                   \
       }                                                                                                     \
+      if (DO_NEXT_) {                                                                                       \
+        MOE_FRAG_A(r__, rbuf_, rks_);                                                                       \
+        if (r__ < TNN) MOE_FRAG_B((set_) ^ 1, r__ < TNN ? r__ : 0, rbuf_, rks_);                            \
+      }                                                                                                     \
       if (DO_LOAD_) {                                                                                       \
-        constexpr int lo__ = (ks_) == 0 ? 0 : L0, n__ = (ks_) == 0 ? L0 : L - L0;                           \
-        _Pragma("unroll") for (int q__ = 0; q__ < n__; ++q__)                                               \
-          if (q__ * NR / n__ == r__) MOE_LOAD1((kt_) + D, bload, lo__ + q__);                               \
+        _Pragma("unroll") for (int q__ = 0; q__ < (LQN_); ++q__)                                            \
+          if (q__ * NR / ((LQN_) > 0 ? (LQN_) : 1) == r__) MOE_LOAD1(lkt_, lbuf_, (LQ0_) + q__);            \
       }                                                                                                     \
       __builtin_amdgcn_sched_barrier(0);                                                                    \
     }                                                                                                       \
   } while (0)
-// One iteration; S0_ is the fragment slot of its first K step (the second uses the next slot, the
-// reads for the next stage go to the slot after that and then to S0_ again).  DO_LOAD_ and DO_NEXT_
-// are literal `true` in the steady-state loop, so that it has no branches; the last iterations use
-// the run-time conditions.
-#define MOE_ITER(kt_, S0_, DO_LOAD_, DO_NEXT_, NI_)                                                         \
+#define MOE_BLOCK_BARRIER()                                                                                 \
   do {                                                                                                      \
-    MOE_STEP(0, (S0_) % 3, ((S0_) + 2) % 3, DO_NEXT_, DO_LOAD_, kt_, NI_);                                  \
-    MOE_STEP(1, ((S0_) + 1) % 3, (S0_) % 3, DO_NEXT_, DO_LOAD_, kt_, NI_);                                  \
-    if (DO_LOAD_) __builtin_amdgcn_s_waitcnt(WAIT_L); else __builtin_amdgcn_s_waitcnt(WAIT_0);              \
     asm volatile("" ::: "memory");                                                                          \
     __builtin_amdgcn_s_barrier();                                                                           \
     asm volatile("" ::: "memory");                                                                          \
-    bload = b0; b0 = b1; b1 = (b1 + STAGE == NB * STAGE) ? 0 : b1 + STAGE;                                  \
   } while (0)
     if constexpr ((EPI == EPI_GELU_BWD || EPI == EPI_GELU_FWD) && Half16<ST>::GELU_TABLE) {
       // the GELU table rides along with the first stage loads (older than they are, so the
@@ -492,46 +477,19 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     }
     if constexpr (NB == 2) {
       // ---- two 64-wide stages --------------------------------------------------------------------------
-      // Iteration S multiplies stage S (four K steps) out of buffer S % 2.  Fragments are still read two K
-      // steps ahead: K steps 0 and 1 read steps 2 and 3 of the same stage; then every wave waits for its own
-      // loads of stage S+1 and for its fragment reads and joins the one block barrier of the iteration, after
-      // which stage S+1 is visible to all and nobody reads buffer S % 2 again; K steps 2 and 3 read steps 0
-      // and 1 of stage S+1, and K step 2 also issues the loads of stage S+2 into buffer S % 2 (all of them:
-      // they have three to four K steps to land).  Unrolled three times for compile-time fragment slots.
-#define P2_STEP(cur_, tgt_, rbuf_, rks_, DO_NEXT_, DO_LOAD_, lkt_, lbuf_, NI_)                              \
+      // Iteration S multiplies stage S (two K steps) out of buffer S % 2.  K step 0 reads the fragments of
+      // K step 1; then every wave waits for its own loads of stage S+1 and for its fragment reads and joins
+      // the one block barrier of the iteration, after which stage S+1 is visible to all and nobody reads
+      // buffer S % 2 again; K step 1 reads the fragments of step 0 of stage S+1 and issues the loads of
+      // stage S+2 into buffer S % 2 (they have about a stage's worth of MFMAs to land).
+#define P2_ITER(S_, DO_NEXT_, DO_LOAD_, NI_)                                                                \
   do {                                                                                                      \
-    _Pragma("unroll") for (int r__ = 0; r__ < NR; ++r__) {                                                  \
-      if (DO_NEXT_) {                                                                                       \
-        _Pragma("unroll") for (int u__ = 0; u__ < NU; ++u__)                                                \
-          if (u__ * NR / NU == r__) MOE_FRAG1(tgt_, rbuf_, rks_, u__);                                      \
-      }                                                                                                     \
-      _Pragma("unroll") for (int m__ = r__ * GM; m__ < (r__ + 1) * GM; ++m__) {                             \
-        const int i__ = m__ / WTN, j__ = m__ % WTN;                                                         \
-        if (i__ < (NI_)) {                                                                                  \
-          acc[i__][j__] = Half16<ST>::mfma(af[cur_][i__], bfr[cur_][j__], acc[i__][j__]); \
-          if constexpr (DUAL)                                                                               \
-            acc2[i__][j__] = Half16<ST>::mfma(af[cur_][i__], bfr2[cur_][j__], acc2[i__][j__]); \
-        }                                                                                                   \
-      }                                                                                                     \
-      if (DO_LOAD_) {                                                                                       \
-        _Pragma("unroll") for (int q__ = 0; q__ < L; ++q__)                                                 \
-          if (q__ * NR / L == r__) MOE_LOAD1(lkt_, lbuf_, q__);                                             \
-      }                                                                                                     \
-      __builtin_amdgcn_sched_barrier(0);                                                                    \
-    }                                                                                                       \
-  } while (0)
-#define P2_ITER(S_, S0_, DO_NEXT_, DO_LOAD_, NI_)                                                           \
-  do {                                                                                                      \
-    P2_STEP((S0_) % 3, ((S0_) + 2) % 3, b0, 2, true, false, 0, 0, NI_);                                     \
-    P2_STEP(((S0_) + 1) % 3, (S0_) % 3, b0, 3, true, false, 0, 0, NI_);                                     \
+    MOE_STEP(0, true, b0, 1, false, 0, 0, 0, 0, NI_);                                                       \
     if (DO_NEXT_) {                                                                                         \
       __builtin_amdgcn_s_waitcnt(0);   /* vmcnt(0) lgkmcnt(0): own loads of stage S+1, own reads of stage S */ \
-      asm volatile("" ::: "memory");                                                                        \
-      __builtin_amdgcn_s_barrier();                                                                         \
-      asm volatile("" ::: "memory");                                                                        \
+      MOE_BLOCK_BARRIER();                                                                                  \
     }                                                                                                       \
-    P2_STEP(((S0_) + 2) % 3, ((S0_) + 1) % 3, b1, 0, DO_NEXT_, DO_LOAD_, (S_) + 2, b0, NI_);                \
-    P2_STEP((S0_) % 3, ((S0_) + 2) % 3, b1, 1, DO_NEXT_, false, 0, 0, NI_);                                 \
+    MOE_STEP(1, DO_NEXT_, b1, 0, DO_LOAD_, (S_) + 2, b0, 0, L, NI_);                                        \
     { const int t__ = b0; b0 = b1; b1 = t__; }                                                              \
   } while (0)
       if (KTT > 0) {
@@ -543,81 +501,77 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
         } else {
           __builtin_amdgcn_s_waitcnt(WAIT_0);
         }
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
+        MOE_BLOCK_BARRIER();
 #define P2_MAINLOOP(NI_)                                                                        \
   do {                                                                                          \
     MOE_FRAGS(0, b0, 0);                                                                        \
-    MOE_FRAGS(1, b0, 1);                                                                        \
+    __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);   /* nothing pending at the loop head: the waits inside the loop then count only its own reads */ \
     int S = 0;                                                                                  \
-    _Pragma("unroll 1") for (; S + 4 < KTT; S += 3) {                                           \
-      P2_ITER(S, 0, true, true, NI_);                                                           \
-      P2_ITER(S + 1, 1, true, true, NI_);                                                       \
-      P2_ITER(S + 2, 2, true, true, NI_);                                                       \
-    }                                                                                           \
-    _Pragma("unroll 1") for (; S < KTT; S += 3) {                                               \
-      P2_ITER(S, 0, S + 1 < KTT, S + 2 < KTT, NI_);                                             \
-      if (S + 1 < KTT) P2_ITER(S + 1, 1, S + 2 < KTT, S + 3 < KTT, NI_);                        \
-      if (S + 2 < KTT) P2_ITER(S + 2, 2, S + 3 < KTT, S + 4 < KTT, NI_);                        \
-    }                                                                                           \
+    _Pragma("unroll 1") for (; S + 2 < KTT; ++S) P2_ITER(S, true, true, NI_);                   \
+    _Pragma("unroll 1") for (; S < KTT; ++S) P2_ITER(S, S + 1 < KTT, S + 2 < KTT, NI_);         \
   } while (0)
         if (ni == WTM) P2_MAINLOOP(WTM);
         else P2_MAINLOOP(ni);
 #undef P2_MAINLOOP
         // the epilogue's slabs reuse the ring: every wave must be done reading fragments first
         __builtin_amdgcn_s_waitcnt(0);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
+        MOE_BLOCK_BARRIER();
       }
-#undef P2_STEP
 #undef P2_ITER
     } else if (KTT > 0) {
-      // ring offsets: stage kt, stage kt+1, and the buffer the loads of stage kt+D go to (the one before b0)
-      int b0 = 0, b1 = STAGE, bload = D * STAGE;
+      // ---- ring of NB 32-wide stages -------------------------------------------------------------------
+      // Iteration kt issues the loads of stage kt+D, multiplies stage kt (one K step) while reading the
+      // fragments of stage kt+1, then waits until its own loads of stage kt+2 have landed (all but the
+      // newest D-2 stages) and joins the block barrier, after which stage kt+2 is visible to every wave and
+      // stage kt's buffer may be overwritten.  Unrolled twice: the B register sets alternate.
+      int b1 = STAGE, bload = D * STAGE;   // stage kt+1, and the buffer the loads of stage kt+D go to
 #pragma unroll
       for (int j = 0; j < D; ++j)
         if (j < KTT) MOE_LOAD(j, j * STAGE);
       if (KTT >= D) __builtin_amdgcn_s_waitcnt(WAIT_L);   // stages 0 and 1 have landed
       else __builtin_amdgcn_s_waitcnt(WAIT_0);
-      asm volatile("" ::: "memory");
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
-      // A partly filled row tile multiplies only the 32-row MFMA bands that hold valid rows (ni of
-      // them in this wave); the loads, fragment reads and barriers stay the same for every wave.  The loop is unrolled
-      // three times so that the fragment slots are compile-time constants.
+      MOE_BLOCK_BARRIER();
+#define MOE_ITER(kt_, set_, DO_LOAD_, DO_NEXT_, NI_)                                                        \
+  do {                                                                                                      \
+    MOE_STEP(set_, DO_NEXT_, b1, 0, DO_LOAD_, (kt_) + D, bload, 0, L, NI_);                                 \
+    if (DO_LOAD_) __builtin_amdgcn_s_waitcnt(WAIT_L); else __builtin_amdgcn_s_waitcnt(WAIT_0);              \
+    MOE_BLOCK_BARRIER();                                                                                    \
+    bload = (bload + STAGE == NB * STAGE) ? 0 : bload + STAGE;                                              \
+    b1 = (b1 + STAGE == NB * STAGE) ? 0 : b1 + STAGE;                                                       \
+  } while (0)
+      // A partly filled row tile multiplies only the 32-row bands that hold valid rows (ni of them in this
+      // wave); the loads, fragment reads and barriers stay the same for every wave.
 #define MOE_MAINLOOP(NI_)                                                                       \
   do {                                                                                          \
-    MOE_FRAGS(0, b0, 0);                                                                        \
-    MOE_FRAGS(1, b0, 1);                                                                        \
+    MOE_FRAGS(0, 0, 0);                                                                         \
+    __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);                                                     \
     int kt = 0;                                                                                 \
-    _Pragma("unroll 1") for (; kt + D + 2 < KTT; kt += 3) {                                     \
+    _Pragma("unroll 1") for (; kt + D + 1 < KTT; kt += 2) {                                     \
       MOE_ITER(kt, 0, true, true, NI_);                                                         \
-      MOE_ITER(kt + 1, 2, true, true, NI_);                                                     \
-      MOE_ITER(kt + 2, 1, true, true, NI_);                                                     \
+      MOE_ITER(kt + 1, 1, true, true, NI_);                                                     \
     }                                                                                           \
-    _Pragma("unroll 1") for (; kt < KTT; kt += 3) {                                             \
+    _Pragma("unroll 1") for (; kt < KTT; kt += 2) {                                             \
       MOE_ITER(kt, 0, kt + D < KTT, kt + 1 < KTT, NI_);                                         \
-      if (kt + 1 < KTT) MOE_ITER(kt + 1, 2, kt + 1 + D < KTT, kt + 2 < KTT, NI_);               \
-      if (kt + 2 < KTT) MOE_ITER(kt + 2, 1, kt + 2 + D < KTT, kt + 3 < KTT, NI_);               \
+      if (kt + 1 < KTT) MOE_ITER(kt + 1, 1, kt + 1 + D < KTT, kt + 2 < KTT, NI_);               \
     }                                                                                           \
   } while (0)
       if (ni == WTM) MOE_MAINLOOP(WTM);
       else MOE_MAINLOOP(ni);
 #undef MOE_MAINLOOP
+#undef MOE_ITER
     }
 #undef MOE_LOAD
 #undef MOE_LOAD1
-#undef MOE_FRAG1
+#undef MOE_FRAG_A
+#undef MOE_FRAG_B
 #undef MOE_FRAGS
 #undef MOE_STEP
-#undef MOE_ITER
+#undef MOE_BLOCK_BARRIER
   }
 
   {
     // per-wave slab [32][WTN*32 + 8] fp32 (the ring is free: the loop ended with a block barrier)
-    constexpr int C = WTN * 32, P = C + 8, LPR = C / 4, RPP = 64 / LPR, PASSES = 32 / RPP;
+    constexpr int C = WTN * 32, P = C + 4, LPR = C / 4, RPP = 64 / LPR, PASSES = 32 / RPP;
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * P);
     const int rr = lane / LPR, c4 = lane % LPR;
     constexpr bool NEED_S1 = (EPI == EPI_GELU_BWD || EPI == EPI_SWIGLU_BWD), NEED_S2 = (EPI == EPI_SWIGLU_BWD);
@@ -648,11 +602,12 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int j = 0; j < WTN; ++j)
+        for (int j = 0; j < TNN; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int r = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-            slab[r * P + j * 32 + (lane & 31)] = (half == 0) ? acc[i][j][v] : acc2[DUAL ? i : 0][DUAL ? j : 0][v];
+          for (int v = 0; v < 8; ++v) {   // lane l of a 16 x 16 tile: column l % 16, rows 4 (l / 16) .. + 3
+            const int i2 = v >> 2, r = i2 * 16 + (lane >> 4) * 4 + (v & 3);
+            slab[r * P + j * 16 + (lane & 15)] =
+                (half == 0) ? acc[2 * i + i2][j][v & 3] : acc2[DUAL ? 2 * i + i2 : 0][DUAL ? j : 0][v & 3];
           }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
