@@ -5,13 +5,8 @@ namespace moe {
 
 // Block tile 256 x 256 (SwiGLU forward: 256 x 128 for each of its two weight matrices), 2 x 4 waves: two
 // waves per SIMD, so one wave's LDS and global traffic hides under the other's MFMAs.  Global loads write LDS
-// directly.  The row-tile GEMMs (x W, dy W^T: the activation operand, for dy W^T both, have K contiguous)
-// run two 64-wide K stages; the weight-gradient GEMM (both operands K-strided) a ring of four 32-wide ones.
+// directly, two 64-wide K stages for all three operand layouts.
 constexpr int T_BM = 256, T_BN = 256, T_BN_DUAL = 128, T_WGM = 2, T_WGN = 4;
-template <int MODE> struct Pipe {
-  static constexpr int BK = MODE == MODE_TN ? 32 : 64;
-  static constexpr int NB = MODE == MODE_TN ? 4 : 2;
-};
 int gemm_bf16_tile_rows() { return T_BM; }
 
 // adds the SPLIT_K partial sums of every split row tile and writes the 16-bit rows of C [rows][N]
@@ -25,10 +20,9 @@ static int launch_split_reduce(const GemmArgs& g, hipStream_t s) {
 template <typename ST, int MODE, int EPI, bool DUAL, bool CHAIN>
 static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
   constexpr int BN = DUAL ? T_BN_DUAL : T_BN;
-  constexpr int BK = Pipe<MODE>::BK, NB = Pipe<MODE>::NB;
   constexpr bool TAB = (EPI == EPI_GELU_BWD || EPI == EPI_GELU_FWD) && Half16<ST>::GELU_TABLE;
-  constexpr int lds = gemm_bf16_lds_bytes<T_BM, BN, BK, DUAL, T_WGM, T_WGN, NB, TAB>();
-  auto kern = gemm_bf16_kernel<ST, MODE, EPI, DUAL, CHAIN, T_BM, BN, BK, T_WGM, T_WGN, NB>;
+  constexpr int lds = gemm_bf16_lds_bytes<T_BM, BN, DUAL, T_WGM, T_WGN, TAB>();
+  auto kern = gemm_bf16_kernel<ST, MODE, EPI, DUAL, CHAIN, T_BM, BN, T_WGM, T_WGN>;
   // more than 64 KB of dynamic LDS needs the attribute on the current device; set on every launch (a cheap
   // host-side call) rather than remembered, so the library keeps no per-process or per-device state
   {
@@ -50,11 +44,10 @@ static int launch_one(const GemmArgs& g, int max_tiles, hipStream_t s) {
 // A row-tile GEMM (NT) and a weight-gradient GEMM (TN) in one launch; the first one's blocks come first.
 template <typename ST, int EPI1, bool CHAIN1>
 static int launch_pair(const GemmArgs& g1, int max_tiles, const GemmArgs& g2, hipStream_t s) {
-  constexpr int lds1 = gemm_bf16_lds_bytes<T_BM, T_BN, Pipe<MODE_NT>::BK, false, T_WGM, T_WGN, Pipe<MODE_NT>::NB, EPI1 == EPI_GELU_BWD && Half16<ST>::GELU_TABLE>();
-  constexpr int lds2 = gemm_bf16_lds_bytes<T_BM, T_BN, Pipe<MODE_TN>::BK, false, T_WGM, T_WGN, Pipe<MODE_TN>::NB>();
+  constexpr int lds1 = gemm_bf16_lds_bytes<T_BM, T_BN, false, T_WGM, T_WGN, EPI1 == EPI_GELU_BWD && Half16<ST>::GELU_TABLE>();
+  constexpr int lds2 = gemm_bf16_lds_bytes<T_BM, T_BN, false, T_WGM, T_WGN>();
   constexpr int lds = lds1 > lds2 ? lds1 : lds2;
-  auto kern = gemm_bf16_pair_kernel<ST, MODE_NT, EPI1, CHAIN1, Pipe<MODE_NT>::BK, Pipe<MODE_NT>::NB, MODE_TN, EPI_DW,
-                                    Pipe<MODE_TN>::BK, Pipe<MODE_TN>::NB, T_BM, T_BN, T_WGM, T_WGN>;
+  auto kern = gemm_bf16_pair_kernel<ST, MODE_NT, EPI1, CHAIN1, MODE_TN, EPI_DW, T_BM, T_BN, T_WGM, T_WGN>;
   // more than 64 KB of dynamic LDS needs the attribute on the current device; set on every launch (a cheap
   // host-side call) rather than remembered, so the library keeps no per-process or per-device state
   {

@@ -14,12 +14,14 @@
 // per stage, 32 per MFMA ("K step").  Interleaving the bands spreads a partly filled row tile over every
 // wave row.
 //
-// Pipelines, both fed by buffer loads that write LDS directly (no staging registers, no LDS store
-// instructions).  (i) A ring of NB (four) 32-wide stages: iteration kt issues the loads of stage kt+NB-1,
-// multiplies stage kt while reading the fragments of stage kt+1, then waits for its own loads of stage kt+2
-// and joins the block barrier.  (ii) Operands whose K index is contiguous (both of dy W^T, the activations
-// of x W) use two 64-wide stages instead: a 32-wide stage fetches such an operand as 64-byte pieces of
-// 128-byte lines, which fills the address FIFO of the memory pipe (counters: full thirteen times as often).
+// Pipeline: two LDS stages of 64 K values, filled by buffer loads that write LDS directly (no staging
+// registers, no LDS store instructions).  An iteration multiplies one stage in two K steps; the first reads
+// the fragments of the second, then every wave waits for its own loads of the next stage and joins the
+// iteration's one block barrier; the second K step reads the first fragments of the next stage and issues
+// the loads of the stage after that into the buffer just released.  64-wide because a 32-wide stage fetches
+// an operand with contiguous K as 64-byte pieces of 128-byte lines, which fills the address FIFO of the
+// memory pipe (counters: full thirteen times as often); the operands with strided K gain a little from the
+// halved number of barriers (weight gradients +2 % against a ring of four 32-wide stages).
 // The direct loads are raw instructions: if the compiler knew that they write LDS it would wait for
 // every outstanding load before each LDS read it cannot prove disjoint.  The pipeline orders loads and
 // reads itself (explicit vmcnt waits, block barriers); the LDS reads stay compiler-tracked.
@@ -69,13 +71,13 @@ template <> struct Half16<f16> {
   }
 };
 
-constexpr int NBUF = 4;   // LDS stages in the ring
+constexpr int BKT = 64;   // K values per LDS stage: two MFMA K steps; an operand row with contiguous K is one 128-byte line
+constexpr int NBUF = 2;   // LDS stages
 
 // ---- LDS layouts -------------------------------------------------------------------------------
 // K-contiguous tile: [rows][BKT] bf16.  The 16-byte chunks of a row are XOR-swizzled with the index
 // of the 256-byte LDS line the row lies in, so 16 lanes reading the same chunk of 16 consecutive
 // rows hit 16 distinct 16-byte bank groups (the LDS serves 64 banks x 4 bytes per clock).
-template <int BKT>
 __device__ __forceinline__ int kc_off(int row, int chunk) {
   constexpr int CPR = BKT / 8, RP = 256 / (BKT * 2);
   return row * (BKT * 2) + ((chunk ^ ((row / RP) & (CPR - 1))) << 4);
@@ -133,7 +135,7 @@ __device__ __forceinline__ void load_to_lds16(rsrc_t rs, unsigned lds, unsigned 
 // One operand tile of one stage, cut into 16-byte chunks; thread tid moves chunks tid + NT*i.
 // KC: [ROWS][BKT], chunk id -> (row id/CPR, chunk id%CPR).
 // KS: [BKT][ROWS] (ROWS = tile width), chunk id -> (K row id/(ROWS/8), chunk id%(ROWS/8)).
-template <bool KC, int ROWS, int NT, int BKT>
+template <bool KC, int ROWS, int NT>
 struct Stage {
   static constexpr int CPR = KC ? BKT / 8 : ROWS / 8;
   static constexpr int CH = ROWS * BKT / 8 / NT;
@@ -220,19 +222,19 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
   }
 }
 
-template <int BM, int BN, int BKT, bool DUAL>
+template <int BM, int BN, bool DUAL>
 constexpr int gemm_bf16_stage_bytes() { return BM * BKT * 2 + BN * BKT * 2 * (DUAL ? 2 : 1); }
 // TAB: a GELU table sits behind the ring (the GELU epilogues)
-template <int BM, int BN, int BKT, bool DUAL, int WGM, int WGN, int NB = NBUF, bool TAB = false>
+template <int BM, int BN, bool DUAL, int WGM, int WGN, bool TAB = false>
 constexpr int gemm_bf16_lds_bytes() {
-  constexpr int ring = NB * gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
+  constexpr int ring = NBUF * gemm_bf16_stage_bytes<BM, BN, DUAL>();
   constexpr int slab = WGM * WGN * 32 * (BN / WGN + 8) * 4;   // epilogue: one 32-row fp32 slab per wave
   return (ring > slab ? ring : slab) + (TAB ? GELU_TAB_FLOATS * 4 : 0);
 }
 
 // One output tile; vb = the tile's number in dispatch order.  Block-uniform control flow; returns at
 // once for numbers past the last tile (the grid is sized for the worst case).
-template <typename ST, int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB>
+template <typename ST, int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int WGM, int WGN>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, char* smem) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM / 32, WTN = BN / WGN / 32;
@@ -241,9 +243,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
   constexpr bool A_KC = (MODE != MODE_TN);   // A stored with K contiguous
   constexpr bool B_KC = (MODE == MODE_NT);
   constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2;
-  constexpr int STAGE = gemm_bf16_stage_bytes<BM, BN, BKT, DUAL>();
-  static_assert((NB >= 4 && KS == 1) || (NB == 2 && KS == 2), "a ring of four or more 32-wide stages, or two 64-wide stages");
-  constexpr int D = NB - 1;   // ring pipeline: loads run D stages ahead of the MFMAs
+  constexpr int STAGE = gemm_bf16_stage_bytes<BM, BN, DUAL>();
+  static_assert(KS == 2 && NBUF == 2, "the pipeline below: two stages of two K steps");
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps wave-dependent values scalar
@@ -314,8 +315,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
   // (row band b of the tile belongs to wave row b % WGM, as its band b / WGM: a partly filled tile then
   // spreads its valid bands over all wave rows instead of loading the first ones only)
   const int ni = (MODE == MODE_TN) ? WTM : min(max(((mvalid + 31) / 32 - wm + WGM - 1) / WGM, 0), WTM);
-  typedef Stage<A_KC, BM, NT, BKT> StA;
-  typedef Stage<B_KC, BN, NT, BKT> StB;
+  typedef Stage<A_KC, BM, NT> StA;
+  typedef Stage<B_KC, BN, NT> StB;
 
   // fragment read offsets inside a stage.  Lane l of a 16 x 16 x 32 MFMA holds row (column) l % 16 and the
   // eight K values of chunk l / 16.  K-contiguous: one offset per K step (MFMA tiles are a constant 16 rows
@@ -323,7 +324,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
   int a_fr[A_KC ? KS : TM], b_fr[B_KC ? KS : TNN];
   if constexpr (A_KC) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) a_fr[ks] = kc_off<BKT>(wm * 32 + (lane & 15), ks * 4 + (lane >> 4));
+    for (int ks = 0; ks < KS; ++ks) a_fr[ks] = kc_off(wm * 32 + (lane & 15), ks * 4 + (lane >> 4));
   } else {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -333,7 +334,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
   if constexpr (B_KC) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      b_fr[ks] = A_BYTES + kc_off<BKT>(wn * WTN * 32 + (lane & 15), ks * 4 + (lane >> 4));
+      b_fr[ks] = A_BYTES + kc_off(wn * WTN * 32 + (lane & 15), ks * 4 + (lane >> 4));
   } else {
 #pragma unroll
     for (int j = 0; j < TNN; ++j)
@@ -375,7 +376,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     // stages) and joins the block barrier, after which stage kt+2 is visible to every wave and stage
     // kt's buffer may be overwritten.
     constexpr int L = StA::CH + StB::CH * (DUAL ? 2 : 1);   // loads per thread per stage
-    constexpr int PEND = NB == 2 ? L : L * (D - 2);          // loads that may stay in flight at the barrier (two stages: after the prologue)
+    constexpr int PEND = L;                                  // loads that may stay in flight at the prologue's barrier: stage 1
     static_assert(PEND < 64, "the wait counter has six bits");
     constexpr int WAIT_L = (PEND & 15) | ((PEND >> 4) << 14) | 0x70 | (15 << 8);   // s_waitcnt vmcnt(PEND) only
     constexpr int WAIT_0 = 0x70 | (15 << 8);                                       // s_waitcnt vmcnt(0) only
@@ -473,16 +474,15 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
       const rsrc_t rt = make_rsrc(g.gelu_tab, (size_t)GELU_TAB_FLOATS * 4);
 #pragma unroll
       for (int i = 0; i < GELU_TAB_FLOATS * 4 / (NT * 16); ++i)
-        load_to_lds16(rt, smem_base + NB * STAGE + i * NT * 16 + wbase, (unsigned)(i * NT + tid) * 16u);
+        load_to_lds16(rt, smem_base + NBUF * STAGE + i * NT * 16 + wbase, (unsigned)(i * NT + tid) * 16u);
     }
-    if constexpr (NB == 2) {
-      // ---- two 64-wide stages --------------------------------------------------------------------------
+    {
       // Iteration S multiplies stage S (two K steps) out of buffer S % 2.  K step 0 reads the fragments of
       // K step 1; then every wave waits for its own loads of stage S+1 and for its fragment reads and joins
       // the one block barrier of the iteration, after which stage S+1 is visible to all and nobody reads
       // buffer S % 2 again; K step 1 reads the fragments of step 0 of stage S+1 and issues the loads of
       // stage S+2 into buffer S % 2 (they have about a stage's worth of MFMAs to land).
-#define P2_ITER(S_, DO_NEXT_, DO_LOAD_, NI_)                                                                \
+#define MOE_ITER(S_, DO_NEXT_, DO_LOAD_, NI_)                                                                \
   do {                                                                                                      \
     MOE_STEP(0, true, b0, 1, false, 0, 0, 0, 0, NI_);                                                       \
     if (DO_NEXT_) {                                                                                         \
@@ -502,62 +502,21 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
           __builtin_amdgcn_s_waitcnt(WAIT_0);
         }
         MOE_BLOCK_BARRIER();
-#define P2_MAINLOOP(NI_)                                                                        \
+#define MOE_MAINLOOP(NI_)                                                                        \
   do {                                                                                          \
     MOE_FRAGS(0, b0, 0);                                                                        \
     __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);   /* nothing pending at the loop head: the waits inside the loop then count only its own reads */ \
     int S = 0;                                                                                  \
-    _Pragma("unroll 1") for (; S + 2 < KTT; ++S) P2_ITER(S, true, true, NI_);                   \
-    _Pragma("unroll 1") for (; S < KTT; ++S) P2_ITER(S, S + 1 < KTT, S + 2 < KTT, NI_);         \
+    _Pragma("unroll 1") for (; S + 2 < KTT; ++S) MOE_ITER(S, true, true, NI_);                   \
+    _Pragma("unroll 1") for (; S < KTT; ++S) MOE_ITER(S, S + 1 < KTT, S + 2 < KTT, NI_);         \
   } while (0)
-        if (ni == WTM) P2_MAINLOOP(WTM);
-        else P2_MAINLOOP(ni);
-#undef P2_MAINLOOP
+        if (ni == WTM) MOE_MAINLOOP(WTM);
+        else MOE_MAINLOOP(ni);
+#undef MOE_MAINLOOP
         // the epilogue's slabs reuse the ring: every wave must be done reading fragments first
         __builtin_amdgcn_s_waitcnt(0);
         MOE_BLOCK_BARRIER();
       }
-#undef P2_ITER
-    } else if (KTT > 0) {
-      // ---- ring of NB 32-wide stages -------------------------------------------------------------------
-      // Iteration kt issues the loads of stage kt+D, multiplies stage kt (one K step) while reading the
-      // fragments of stage kt+1, then waits until its own loads of stage kt+2 have landed (all but the
-      // newest D-2 stages) and joins the block barrier, after which stage kt+2 is visible to every wave and
-      // stage kt's buffer may be overwritten.  Unrolled twice: the B register sets alternate.
-      int b1 = STAGE, bload = D * STAGE;   // stage kt+1, and the buffer the loads of stage kt+D go to
-#pragma unroll
-      for (int j = 0; j < D; ++j)
-        if (j < KTT) MOE_LOAD(j, j * STAGE);
-      if (KTT >= D) __builtin_amdgcn_s_waitcnt(WAIT_L);   // stages 0 and 1 have landed
-      else __builtin_amdgcn_s_waitcnt(WAIT_0);
-      MOE_BLOCK_BARRIER();
-#define MOE_ITER(kt_, set_, DO_LOAD_, DO_NEXT_, NI_)                                                        \
-  do {                                                                                                      \
-    MOE_STEP(set_, DO_NEXT_, b1, 0, DO_LOAD_, (kt_) + D, bload, 0, L, NI_);                                 \
-    if (DO_LOAD_) __builtin_amdgcn_s_waitcnt(WAIT_L); else __builtin_amdgcn_s_waitcnt(WAIT_0);              \
-    MOE_BLOCK_BARRIER();                                                                                    \
-    bload = (bload + STAGE == NB * STAGE) ? 0 : bload + STAGE;                                              \
-    b1 = (b1 + STAGE == NB * STAGE) ? 0 : b1 + STAGE;                                                       \
-  } while (0)
-      // A partly filled row tile multiplies only the 32-row bands that hold valid rows (ni of them in this
-      // wave); the loads, fragment reads and barriers stay the same for every wave.
-#define MOE_MAINLOOP(NI_)                                                                       \
-  do {                                                                                          \
-    MOE_FRAGS(0, 0, 0);                                                                         \
-    __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);                                                     \
-    int kt = 0;                                                                                 \
-    _Pragma("unroll 1") for (; kt + D + 1 < KTT; kt += 2) {                                     \
-      MOE_ITER(kt, 0, true, true, NI_);                                                         \
-      MOE_ITER(kt + 1, 1, true, true, NI_);                                                     \
-    }                                                                                           \
-    _Pragma("unroll 1") for (; kt < KTT; kt += 2) {                                             \
-      MOE_ITER(kt, 0, kt + D < KTT, kt + 1 < KTT, NI_);                                         \
-      if (kt + 1 < KTT) MOE_ITER(kt + 1, 1, kt + 1 + D < KTT, kt + 2 < KTT, NI_);               \
-    }                                                                                           \
-  } while (0)
-      if (ni == WTM) MOE_MAINLOOP(WTM);
-      else MOE_MAINLOOP(ni);
-#undef MOE_MAINLOOP
 #undef MOE_ITER
     }
 #undef MOE_LOAD
@@ -575,7 +534,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * P);
     const int rr = lane / LPR, c4 = lane % LPR;
     constexpr bool NEED_S1 = (EPI == EPI_GELU_BWD || EPI == EPI_SWIGLU_BWD), NEED_S2 = (EPI == EPI_SWIGLU_BWD);
-    const float* tab_lds = reinterpret_cast<const float*>(smem + NB * STAGE);
+    const float* tab_lds = reinterpret_cast<const float*>(smem + NBUF * STAGE);
     // Saved tensors the backward epilogues read: the loads of a band are issued one band ahead (those of
     // the first band before anything else), so their latency hides behind the previous band's LDS round
     // trip and arithmetic (rows past the tile read the tile's first row and are dropped).
@@ -655,23 +614,23 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(GemmArgs g) {
       u32x2{Half16<ST>::pack2(sum[0], sum[1]), Half16<ST>::pack2(sum[2], sum[3])};
 }
 
-template <typename ST, int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int BKT, int WGM, int WGN, int NB = NBUF>
+template <typename ST, int MODE, int EPI, bool DUAL, bool CHAIN, int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  gemm_bf16_tile<ST, MODE, EPI, DUAL, CHAIN, BM, BN, BKT, WGM, WGN, NB>(g, blockIdx.x, smem);
+  gemm_bf16_tile<ST, MODE, EPI, DUAL, CHAIN, BM, BN, WGM, WGN>(g, blockIdx.x, smem);
 }
 
 // Two independent GEMMs in one launch: blocks below `first_blocks` take a tile of the first, the others a
 // tile of the second.  Blocks are dispatched in order, so the second GEMM's tiles start on the compute
 // units that the first one's last, partly filled round leaves idle (no stream or event in between,
 // and the two never compete for the cache from the start as two concurrent kernels would).
-template <typename ST, int MODE1, int EPI1, bool CHAIN1, int BK1, int NB1, int MODE2, int EPI2, int BK2, int NB2, int BM, int BN, int WGM, int WGN>
+template <typename ST, int MODE1, int EPI1, bool CHAIN1, int MODE2, int EPI2, int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_pair_kernel(GemmArgs g1, GemmArgs g2, int first_blocks) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   if ((int)blockIdx.x < first_blocks)
-    gemm_bf16_tile<ST, MODE1, EPI1, false, CHAIN1, BM, BN, BK1, WGM, WGN, NB1>(g1, blockIdx.x, smem);
+    gemm_bf16_tile<ST, MODE1, EPI1, false, CHAIN1, BM, BN, WGM, WGN>(g1, blockIdx.x, smem);
   else
-    gemm_bf16_tile<ST, MODE2, EPI2, false, false, BM, BN, BK2, WGM, WGN, NB2>(g2, blockIdx.x - first_blocks, smem);
+    gemm_bf16_tile<ST, MODE2, EPI2, false, false, BM, BN, WGM, WGN>(g2, blockIdx.x - first_blocks, smem);
 }
 
 inline unsigned gemm_bf16_grid(long long tiles) { return (unsigned)(tiles > 0 ? tiles : 1); }
