@@ -371,6 +371,24 @@ def run_workload(name, steps, warmup, args, full):
     res["device"] = {"name": props.name, "compute_units": props.multi_processor_count, "max_clock_MHz": max_clock,
                      "copy_kernel_512MiB_GBps": round(own, 1), "copy_kernel_frac_hbm": round(own / PEAK_HBM_GBS, 4),
                      "runtime_copy_512MiB_GBps": round(blit, 1)}
+    if args.mfma_loop:
+        # the rate of a kernel of nothing but MFMAs, per instruction shape: what the chip's power management allows
+        opnd = (torch.randn(64 * 1024, device=dev) * 0.5).to(torch.bfloat16)
+        sink = torch.zeros(1024 * 512, dtype=torch.float32, device=dev)
+        iters = 10000
+        flop = 1024 * 8 * iters * 32 * 16384
+        res["device"]["mfma_loop"] = {}
+        for kind, nm in ((0, "16x16x32"), (1, "32x32x16")):
+            B.moe_bench_mfma_loop(kind, 2000, opnd, sink)
+            torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            for i in range(3):
+                ev[i].record()
+                B.moe_bench_mfma_loop(kind, iters, opnd, sink)
+            ev[3].record()
+            torch.cuda.synchronize()
+            ms = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(3)]))
+            res["device"]["mfma_loop"][nm + "_bf16_TFLOPs"] = round(flop / ms / 1e9, 1)
     for nm in ("gather", "combine", "combine_bwd", "dispatch_bwd", "route"):
         if nm in kernels and "cold_GBps" in kernels[nm]:
             kernels[nm]["frac_copy_kernel"] = round(kernels[nm]["cold_GBps"] / own, 4)
@@ -403,6 +421,9 @@ def main():
     ap.add_argument("--clock-probe", action="store_true",
                     help="sample the shader clock with a one-wave kernel on a second stream while steps run "
                          "(evidence for the clock the chip sustains under the GEMMs; not part of the timed region)")
+    ap.add_argument("--mfma-loop", action="store_true",
+                    help="also time a kernel of nothing but MFMAs for both bf16 instruction shapes "
+                         "(device.mfma_loop: the matrix-core rate the chip's power management allows)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB copy with the library's streaming kernel three times "
                          "(calibrates rocprofv3 byte counters)")

@@ -291,6 +291,16 @@ MOE_API int moe_asymea_shares(int32_t n, int32_t M, int32_t N, int32_t o_l, int3
 MOE_API int moe_bench_clock_probe(uint64_t* samples, int32_t n, int32_t sleeps, void* stream);
 
 /*
+ * Benchmark aid, not a step of the layer: a kernel of nothing but bf16 MFMA instructions on register operands
+ * (1024 blocks of eight waves, `iters` (1..10^6) rounds of 32 independent accumulations per wave), to show the
+ * rate the chip sustains for an instruction shape under its own power management.  kind 0: 16 x 16 x 32, the
+ * instruction the grouped GEMM uses; kind 1: 32 x 32 x 16.  `operand` is device memory of at least 64 KiB that the
+ * register operands are read from (random bf16 values give realistic switching activity), `sink` device float[1024 * 512]
+ * that receives one sum per lane.  FLOP of one launch: 1024 * 8 * iters * 32 * 16384.
+ */
+MOE_API int moe_bench_mfma_loop(int32_t kind, int32_t iters, const void* operand, float* sink, void* stream);
+
+/*
  * Introspection for tests, HOST-ONLY (nothing is enqueued, `out` is a HOST int32[6]): which tile block number
  * `block` of a grouped-GEMM launch of the 16-bit path computes, by the same code the kernels run.
  * kind 0, row-tile GEMMs (x W, dy W^T) over n_rt row tiles of which the first n_full_rt are full and the last

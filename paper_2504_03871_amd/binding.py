@@ -19,7 +19,7 @@ MAX_E, MAX_K = 256, 8
 
 SYMBOLS = ("moe_error_string", "moe_last_hip_error", "moe_workspace_bytes", "moe_saved_bytes", "moe_route",
            "moe_dispatch", "moe_dispatch_static", "moe_expert_ffn_fwd", "moe_expert_ffn_recompute", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
-           "moe_route_bwd", "moe_asymea_plan", "moe_asymea_shares", "moe_bench_stream", "moe_bench_clock_probe", "moe_gemm_block_tile")
+           "moe_route_bwd", "moe_asymea_plan", "moe_asymea_shares", "moe_bench_stream", "moe_bench_clock_probe", "moe_bench_mfma_loop", "moe_gemm_block_tile")
 
 PROF = {"gemm1_fwd": 0, "gemm2_fwd": 1, "dh_bwd": 2, "dw2_bwd": 3, "dw1_bwd": 4, "dx_bwd": 5, "gather": 6,
         "combine": 7, "combine_bwd": 8, "route": 9}
@@ -76,6 +76,7 @@ def lib():
             "moe_asymea_shares": [i32] * 6 + [ctypes.POINTER(i32), ctypes.POINTER(i32)],
             "moe_bench_stream": [p, p, sz, i32, p],
             "moe_bench_clock_probe": [p, i32, i32, p],
+            "moe_bench_mfma_loop": [i32, i32, p, p, p],
             "moe_gemm_block_tile": [i32, ctypes.c_int64, i32, i32, i32, i32, i32, ctypes.POINTER(i32)],
         }
         for name, args in sig.items():
@@ -231,6 +232,12 @@ def moe_bench_clock_probe(samples, n, sleeps, stream=None):
     """Benchmark aid: n (shader clock, 100 MHz clock) counter pairs into the uint64 tensor `samples`."""
     _check("moe_bench_clock_probe", lib().moe_bench_clock_probe(_ptr(samples), int(n), int(sleeps),
                                                                 _stream() if stream is None else stream))
+
+
+def moe_bench_mfma_loop(kind, iters, operand, sink, stream=None):
+    """Benchmark aid: a kernel of nothing but MFMAs (kind 0: 16x16x32, 1: 32x32x16); FLOP = 1024*8*iters*32*16384."""
+    _check("moe_bench_mfma_loop", lib().moe_bench_mfma_loop(int(kind), int(iters), _ptr(operand), _ptr(sink),
+                                                            _stream() if stream is None else stream))
 
 
 def moe_gemm_block_tile(kind, block, n_rt=0, n_full_rt=0, n_split=0, ntm=1, ntn=1):

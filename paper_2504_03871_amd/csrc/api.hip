@@ -98,6 +98,48 @@ __global__ void clock_probe_kernel(unsigned long long* __restrict__ out, int n, 
   }
 }
 
+// Nothing but MFMAs on register operands: 32 accumulations per round, each on an accumulator of its own
+// (16 x 16 x 32: 32 accumulators of 4 registers; 32 x 32 x 16: 8 accumulators of 16 registers, four rounds of them).
+typedef __bf16 ml_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float ml_f32x4 __attribute__((ext_vector_type(4)));
+typedef float ml_f32x16 __attribute__((ext_vector_type(16)));
+template <int KIND>
+__global__ __launch_bounds__(512, 1) void mfma_loop_kernel(const ml_bf16x8* __restrict__ in, float* __restrict__ out, int iters) {
+  ml_bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = in[(threadIdx.x * 8 + i) % 4096];
+    b[i] = in[(threadIdx.x * 8 + 4 + i) % 4096];
+  }
+  float s = 0.f;
+  if constexpr (KIND == 0) {
+    ml_f32x4 acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = ml_f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i % 4], b[(i / 4) % 4], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  } else {
+    ml_f32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    for (int it = 0; it < 2 * iters; ++it) {   // 16 instructions of twice the FLOP = the FLOP of a round above
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i % 4], b[(i / 4) % 4], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s += acc[i][v];
+  }
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 static int check_ws(const moe_cfg* c, const void* ws, size_t ws_bytes) {
   return (ws != nullptr && ws_bytes < ws_layout(c).total) ? MOE_ERR_WORKSPACE : MOE_OK;
 }
@@ -159,6 +201,19 @@ int moe_bench_clock_probe(uint64_t* samples, int32_t n, int32_t sleeps, void* st
   ALIGNED(samples);
   if (n < 1 || n > (1 << 20) || sleeps < 0 || sleeps > 1000) return MOE_ERR_BAD_SHAPE;
   clock_probe_kernel<<<1, 64, 0, (hipStream_t)stream>>>(reinterpret_cast<unsigned long long*>(samples), n, sleeps);
+  return launch_status();
+}
+
+int moe_bench_mfma_loop(int32_t kind, int32_t iters, const void* operand, float* sink, void* stream) {
+  REQUIRE(operand);
+  REQUIRE(sink);
+  ALIGNED(operand);
+  ALIGNED(sink);
+  if (kind < 0 || kind > 1 || iters < 1 || iters > 1000000) return MOE_ERR_BAD_SHAPE;
+  if (kind == 0)
+    mfma_loop_kernel<0><<<1024, 512, 0, (hipStream_t)stream>>>(reinterpret_cast<const ml_bf16x8*>(operand), sink, iters);
+  else
+    mfma_loop_kernel<1><<<1024, 512, 0, (hipStream_t)stream>>>(reinterpret_cast<const ml_bf16x8*>(operand), sink, iters);
   return launch_status();
 }
 

@@ -4,10 +4,11 @@
 // look their function up (bf16: a table over all bf16 numbers fits in LDS) or evaluate it (fp16).
 //
 // Why the 16 x 16 x 32 instruction and not 32 x 32 x 16 (same FLOP per cycle): the chip lowers its clock under
-// matrix-core load, and by how much depends on the instruction.  A loop of nothing but MFMAs, matrix cores
-// busy 99 % of the cycles in both cases, runs at 2.05 GHz (2140 TFLOP/s) with 16 x 16 x 32 and at 1.8 GHz
-// (1880 TFLOP/s) with 32 x 32 x 16, which moves twice the accumulator registers per FLOP.  In this kernel
-// the change was worth 4-6 % on x W and dy W^T and 1-2 % on x^T dy.
+// matrix-core load, and by how much depends on the instruction.  A loop of nothing but MFMAs (the library's
+// moe_bench_mfma_loop), matrix cores busy 99 % of the cycles in both cases, runs 1.14 times faster with
+// 16 x 16 x 32 (about 2.0-2.1 PFLOP/s against 1.7-1.9): 32 x 32 x 16 moves twice the accumulator registers per
+// FLOP.  In this kernel the change was worth 4-6 % on x W and dy W^T and 1-2 % on x^T dy, and the shader clock
+// sampled during a whole layer step rose from 1.66 to 1.80 GHz.
 //
 // Work decomposition: block tile BM x BN, WGM x WGN waves; a wave owns BN/WGN adjacent columns and the
 // 32-row bands b = wm, wm + WGM, ... of the tile, each band two 16-row MFMA tiles; K advances BKT elements

@@ -154,6 +154,10 @@ def test_clock_probe_validation():
     assert lib.moe_bench_clock_probe(0x10008, 10, 1, s) == -5
     assert lib.moe_bench_clock_probe(0x10000, 0, 1, s) == -2
     assert lib.moe_bench_clock_probe(0x10000, 10, 1001, s) == -2
+    assert lib.moe_bench_mfma_loop(0, 10, None, 0x10000, s) == -1
+    assert lib.moe_bench_mfma_loop(2, 10, 0x10000, 0x20000, s) == -2
+    assert lib.moe_bench_mfma_loop(0, 0, 0x10000, 0x20000, s) == -2
+    assert lib.moe_bench_mfma_loop(1, 10, 0x10000, 0x20008, s) == -5
 
 
 def test_bench_stream_validation():
