@@ -32,7 +32,7 @@ inline bool offsets_fit_32_bits(long long T, long long k, long long d, long long
 struct WsLayout {
   size_t dispatch_blk_cnt;  // int32 [nblk + 1][E]: per-block counts (or their prefixes) and a row of totals
   size_t tile_map;          // int32 header + int4 entries (grouped GEMM row tiles)
-  size_t route_partials;    // fp32 [nchunk][d][E]
+  size_t route_partials;    // fp32 [token slice][E][d]: partial sums of the gate weight gradient
   size_t route_wrt;         // fp32 [E][d]: transposed router weight
   size_t ffn_split;         // fp32 partial sums of split-K row tiles (gemm.h), when split_k_applies
   size_t ffn_bwd_dact;      // storage type [planes][T*k][f]: dA (GELU) or dG | dU (SwiGLU)
@@ -42,23 +42,23 @@ WsLayout ws_layout(const moe_cfg* c);
 size_t route_wfrag_bytes(int d, int E);   // gate weight in MFMA operand layout (route.hip)
 
 constexpr int DISPATCH_CHUNK = 1024;   // assignments ranked by one block
-constexpr int ROUTE_BWD_TOKENS = 128;  // tokens per block of the gate-backward kernel (many experts)
-constexpr int ROUTE_BWD_DENSE_E = 64;  // up to this many experts the gate weight gradient is accumulated densely in registers, 16 experts per block
 
 // Geometry of the dense gate-weight-gradient kernel: a thread owns one 16-byte column group, cg_pow2
 // threads span a token row (a power of two, at most 256; wider rows take several column blocks), a block
 // of 256 threads works on 256 / cg_pow2 token slices at once, each `tps` tokens long, and every slice
-// writes its own row of partial sums.  tps grows with the problem so that the grid stays near two
-// blocks per compute unit and the partial sums stay small.
+// writes its own row of partial sums.  More than 16 experts are split into groups of 16 that run as blocks of
+// their own.  tps grows with the problem and with the number of groups so that the grid stays near two
+// blocks per compute unit and the partial sums (a row of E x d floats per slice) stay small.
 struct RouteBwdGeom { int cg_pow2, slices_per_block, tps, col_blocks, row_blocks, partial_rows; };
-inline RouteBwdGeom route_bwd_geom(int T, int d, int elt_bytes) {
+inline RouteBwdGeom route_bwd_geom(int T, int d, int elt_bytes, int E) {
   RouteBwdGeom gm;
   const int cg = d / (16 / elt_bytes);
   gm.cg_pow2 = 4;   // at most 64 slices per block
   while (gm.cg_pow2 < cg && gm.cg_pow2 < 256) gm.cg_pow2 <<= 1;
   gm.slices_per_block = 256 / gm.cg_pow2;
   gm.col_blocks = (cg + gm.cg_pow2 - 1) / gm.cg_pow2;
-  long long tps = ((long long)T * gm.col_blocks) / (512ll * gm.slices_per_block);
+  const int groups = (E + 15) / 16;
+  long long tps = ((long long)T * gm.col_blocks * groups) / (512ll * gm.slices_per_block);
   const int cap = 1024 / gm.slices_per_block;   // the block stages slices * tps * E <= 1024 * 16 floats in LDS
   gm.tps = (int)(tps < 16 ? 16 : (tps > 256 ? 256 : tps));
   if (gm.tps > cap) gm.tps = cap;

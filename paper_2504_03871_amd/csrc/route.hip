@@ -383,65 +383,7 @@ __global__ __launch_bounds__(256) void route_bwd_dx_kernel(
   }
 }
 
-constexpr int RB_MAX_WAVES = 4;  // waves per block of the dWr kernel (fewer when E is large: LDS)
-constexpr int RB_BATCH = 8;      // tokens whose x values a thread keeps in flight
-
-// Block = nw waves; thread owns VEC adjacent columns; wave w handles tokens w, w+nw, ... of the chunk.
-template <typename T, int VEC>
-__global__ __launch_bounds__(RB_MAX_WAVES* WAVE) void route_bwd_dwr_kernel(
-    const T* __restrict__ x, const int32_t* __restrict__ topk_idx, const float* __restrict__ d_logits,
-    float* __restrict__ partials, int Tn, int d, int E, int k) {
-  extern __shared__ float smem[];
-  constexpr int COLS = WAVE * VEC;
-  const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE, nw = blockDim.x / WAVE;
-  float* acc = smem + (size_t)wave * E * COLS;   // [E][COLS], private to the wave
-  float* s_ds = smem + (size_t)nw * E * COLS;    // [ROUTE_BWD_TOKENS][k]: the chunk's non-zero d_logits ...
-  int* s_e = reinterpret_cast<int*>(s_ds + ROUTE_BWD_TOKENS * MOE_MAX_K);   // ... and their experts
-  const int c0 = blockIdx.x * COLS + lane * VEC;
-  const int t0 = blockIdx.y * ROUTE_BWD_TOKENS;
-  const int nt = min(ROUTE_BWD_TOKENS, Tn - t0);
-  for (int i = lane; i < E * COLS; i += WAVE) acc[i] = 0.f;
-  for (int i = threadIdx.x; i < nt * k; i += blockDim.x) {
-    const int e = topk_idx[(size_t)t0 * k + i];
-    const bool ok = e >= 0 && e < E;   // an id outside [0, E) contributes nothing
-    s_e[i] = ok ? e : 0;
-    s_ds[i] = ok ? d_logits[(size_t)(t0 + i / k) * E + e] : 0.f;
-  }
-  __syncthreads();
-  const bool live = c0 < d;   // d is a multiple of VEC
-  for (int tb = wave; tb < nt; tb += nw * RB_BATCH) {
-    float xv[RB_BATCH][VEC];
-#pragma unroll
-    for (int u = 0; u < RB_BATCH; ++u) {
-      const int t = tb + u * nw;
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) xv[u][v] = (live && t < nt) ? to_f32(x[(size_t)(t0 + t) * d + c0 + v]) : 0.f;
-    }
-#pragma unroll
-    for (int u = 0; u < RB_BATCH; ++u) {
-      const int t = tb + u * nw;
-      if (t < nt) {
-        for (int j = 0; j < k; ++j) {
-          const int e = s_e[t * k + j];        // wave-uniform
-          const float ds = s_ds[t * k + j];
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) acc[e * COLS + lane * VEC + v] = fmaf(ds, xv[u][v], acc[e * COLS + lane * VEC + v]);
-        }
-      }
-    }
-  }
-  __syncthreads();
-  // sum the waves in wave order and write partials[chunk][col][e]
-  for (int i = threadIdx.x; i < E * COLS; i += blockDim.x) {
-    const int e = i / COLS, c = i % COLS;
-    float s = 0.f;
-    for (int w = 0; w < nw; ++w) s += smem[(size_t)w * E * COLS + i];
-    const int col = blockIdx.x * COLS + c;
-    if (col < d) partials[((size_t)blockIdx.y * d + col) * E + e] = s;
-  }
-}
-
-// Few experts (at most ROUTE_BWD_DENSE_E, in groups of EB <= 16 along gridDim.z): every thread keeps an [EB] x
+// Gate weight gradient dWr = x^T d_logits.  Experts in groups of EB <= 16 along gridDim.z: every thread keeps an [EB] x
 // (16-byte column group) block of the weight gradient in registers and adds d_logits[t][:] (x) x[t][cols] token after token,
 // zeros of the unselected experts included; no LDS read-modify-write, no branches, one 16-byte load of
 // x per token.  The slice's d_logits rows are staged in LDS once, padded with zeros to EB per row, and
@@ -506,9 +448,7 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_dense_kernel(
 
 // dWr = sum over the rows of partial sums, in a fixed order (deterministic).  A block owns 64 adjacent
 // elements of a row of partial sums; its four waves take the rows r = w, w+4, ... (each a coalesced
-// 256-byte read), and the four wave sums are added in wave order.  EXPERT_MAJOR: the rows are laid
-// out [E][d] (the dense kernel) instead of [d][E] like dWr itself.
-template <bool EXPERT_MAJOR>
+// 256-byte read), and the four wave sums are added in wave order.  The rows are laid out [E][d], dWr itself [d][E].
 __global__ __launch_bounds__(256) void route_bwd_reduce_kernel(const float* __restrict__ partials, float* __restrict__ dWr,
                                                                int d, int E, int rows, int accumulate) {
   __shared__ float s_part[4][64];
@@ -523,7 +463,7 @@ __global__ __launch_bounds__(256) void route_bwd_reduce_kernel(const float* __re
   __syncthreads();
   if (w == 0 && i < n) {
     const float t = ((s_part[0][lane] + s_part[1][lane]) + s_part[2][lane]) + s_part[3][lane];
-    float* o = dWr + (EXPERT_MAJOR ? (size_t)(i % d) * E + i / d : (size_t)i);
+    float* o = dWr + (size_t)(i % d) * E + i / d;
     *o = accumulate ? *o + t : t;
   }
 }
@@ -578,26 +518,11 @@ int launch_route(const moe_cfg* c, const void* x, const float* Wr, const float* 
   return launch_status();
 }
 
-template <typename T, int VEC>
-static int launch_dwr(const moe_cfg* c, const void* x, const int32_t* idx, const float* d_logits, float* partials,
-                      int chunks, hipStream_t s) {
-  int nw = RB_MAX_WAVES;
-  while (nw > 1 && (size_t)nw * c->E * WAVE * VEC * 4 > 128 * 1024) nw >>= 1;
-  const size_t lds = (size_t)nw * c->E * WAVE * VEC * 4 + (size_t)ROUTE_BWD_TOKENS * MOE_MAX_K * 8;
-  auto kern = route_bwd_dwr_kernel<T, VEC>;
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return set_hip_error(e);
-  const dim3 grid((c->d_model + WAVE * VEC - 1) / (WAVE * VEC), chunks);
-  kern<<<grid, nw * WAVE, lds, s>>>((const T*)x, idx, d_logits, partials, c->T, c->d_model, c->E, c->k);
-  return launch_status();
-}
-
 template <typename T>
 static int route_bwd_typed(const moe_cfg* c, const void* x, const float* Wr, const int32_t* idx, const float* w,
                            const float* dw, float* d_logits, float* dWr, void* dx, int accumulate, float* partials,
                            float* WrT, hipStream_t s) {
   const int n = c->d_model * c->E;
-  const int chunks = (c->T + ROUTE_BWD_TOKENS - 1) / ROUTE_BWD_TOKENS;
   int rc;
   if (dx != nullptr) {
     wr_transpose_kernel<<<(n + 255) / 256, 256, 0, s>>>(Wr, WrT, c->d_model, c->E);
@@ -607,26 +532,16 @@ static int route_bwd_typed(const moe_cfg* c, const void* x, const float* Wr, con
   route_bwd_dx_kernel<T><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (T*)dx, c->T, c->d_model, c->E, c->k);
   if ((rc = launch_status()) != MOE_OK) return rc;
   if (dWr == nullptr) return MOE_OK;
-  if (c->E <= ROUTE_BWD_DENSE_E) {
-    const RouteBwdGeom gm = route_bwd_geom(c->T, c->d_model, (int)sizeof(T));
-    const int eb = c->E <= 4 ? 4 : (c->E <= 8 ? 8 : 16);
-    const dim3 grid(gm.col_blocks, gm.row_blocks, (c->E + eb - 1) / eb);
-    const size_t lds = (size_t)gm.slices_per_block * gm.tps * eb * 4;
+  const RouteBwdGeom gm = route_bwd_geom(c->T, c->d_model, (int)sizeof(T), c->E);
+  const int eb = c->E <= 4 ? 4 : (c->E <= 8 ? 8 : 16);
+  const dim3 dgrid(gm.col_blocks, gm.row_blocks, (c->E + eb - 1) / eb);
+  const size_t lds = (size_t)gm.slices_per_block * gm.tps * eb * 4;
 #define MOE_DWR_DENSE(EB) \
-  route_bwd_dwr_dense_kernel<T, EB><<<grid, 256, lds, s>>>((const T*)x, d_logits, partials, c->T, c->d_model, c->E, gm)
-    if (eb == 4) MOE_DWR_DENSE(4); else if (eb == 8) MOE_DWR_DENSE(8); else MOE_DWR_DENSE(16);
+  route_bwd_dwr_dense_kernel<T, EB><<<dgrid, 256, lds, s>>>((const T*)x, d_logits, partials, c->T, c->d_model, c->E, gm)
+  if (eb == 4) MOE_DWR_DENSE(4); else if (eb == 8) MOE_DWR_DENSE(8); else MOE_DWR_DENSE(16);
 #undef MOE_DWR_DENSE
-    if ((rc = launch_status()) != MOE_OK) return rc;
-    route_bwd_reduce_kernel<true><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, gm.partial_rows, accumulate);
-    return launch_status();
-  }
-  // columns per thread: as many as 128 KiB of LDS allow for 4 waves x E experts (d is a multiple of 4)
-  const int vec = (c->E <= 32) ? 4 : (c->E <= 64 ? 2 : 1);
-  if (vec == 4) rc = launch_dwr<T, 4>(c, x, idx, d_logits, partials, chunks, s);
-  else if (vec == 2) rc = launch_dwr<T, 2>(c, x, idx, d_logits, partials, chunks, s);
-  else rc = launch_dwr<T, 1>(c, x, idx, d_logits, partials, chunks, s);
-  if (rc != MOE_OK) return rc;
-  route_bwd_reduce_kernel<false><<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, chunks, accumulate);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  route_bwd_reduce_kernel<<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E, gm.partial_rows, accumulate);
   return launch_status();
 }
 
