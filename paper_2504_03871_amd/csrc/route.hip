@@ -316,14 +316,13 @@ __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
 }
 
 // ---------------------------------------------------------------- backward
-// Three small kernels.
+// Four small kernels.
 //  1. WrT[e][i] = Wr[i][e], so that the input-gradient kernel reads contiguous weights.
 //  2. One wave per token: dsel_j = w_j (dw_j - sum_i w_i dw_i); writes the token's d_logits row and
 //     adds sum_j dsel_j WrT[e_j][:] to dx[t][:].
-//  3. dWr = x^T d_logits in its sparse form (k non-zeros per token): a block owns a tile of columns
-//     and a chunk of tokens, every wave keeps a private [E][columns] accumulator in LDS for a quarter
-//     of the chunk, the waves are summed in a fixed order and the per-chunk partials are reduced by a
-//     last kernel in chunk order, so the result is bit-reproducible.
+//  3. dWr = x^T d_logits, dense: token slices accumulate [16 experts] x [columns] blocks in registers, one row
+//     of partial sums per slice, and a last kernel adds the rows in a fixed order, so the result is
+//     bit-reproducible.
 __global__ void wr_transpose_kernel(const float* __restrict__ Wr, float* __restrict__ WrT, int d, int E) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < d * E) WrT[(size_t)(i % E) * d + i / E] = Wr[i];
