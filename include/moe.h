@@ -176,6 +176,19 @@ MOE_API int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const voi
                        void* saved, void* y_perm, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * moe_expert_ffn_fwd for a layer whose activations are checkpointed (Section 6.1): the same two GEMMs, but of
+ * the saved planes only the hidden activation H is written, to `hidden` ([T*k][d_ff] in the storage type), because
+ * the second GEMM reads it; the pre-activations (A, or G and U) are not stored, which removes one (GELU) or two
+ * (SwiGLU) of the first GEMM's output planes from its HBM writes.  H and y_perm are bit-identical to
+ * moe_expert_ffn_fwd's.  Before the backward the caller refills a full `saved` buffer with
+ * moe_expert_ffn_recompute.  Other arguments as in moe_expert_ffn_fwd.
+ */
+MOE_API int moe_expert_ffn_fwd_light(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b,
+                             const void* W2, const int32_t* offsets, const int32_t* kept,
+                             const int32_t* slice_lo, const int32_t* slice_hi,
+                             void* hidden, void* y_perm, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Activation checkpointing (the paper trains with it, Section 6.1): the first half of
  * moe_expert_ffn_fwd again.  Fills every plane of `saved` from x_perm and the first-layer weights with
  * the same kernel the forward call uses, so the planes are bit-identical to the forward's, and does

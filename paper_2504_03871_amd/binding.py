@@ -18,7 +18,7 @@ ACT_GELU, ACT_SWIGLU = 0, 1
 MAX_E, MAX_K = 256, 8
 
 SYMBOLS = ("moe_error_string", "moe_last_hip_error", "moe_workspace_bytes", "moe_saved_bytes", "moe_route",
-           "moe_dispatch", "moe_dispatch_static", "moe_expert_ffn_fwd", "moe_expert_ffn_recompute", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
+           "moe_dispatch", "moe_dispatch_static", "moe_expert_ffn_fwd", "moe_expert_ffn_fwd_light", "moe_expert_ffn_recompute", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
            "moe_route_bwd", "moe_asymea_plan", "moe_asymea_shares", "moe_bench_stream", "moe_bench_clock_probe", "moe_bench_mfma_loop", "moe_gemm_block_tile")
 
 PROF = {"gemm1_fwd": 0, "gemm2_fwd": 1, "dh_bwd": 2, "dw2_bwd": 3, "dw1_bwd": 4, "dx_bwd": 5, "gather": 6,
@@ -67,6 +67,7 @@ def lib():
             "moe_dispatch": [cfgp] + [p] * 11 + [sz, p],
             "moe_dispatch_static": [cfgp] + [p] * 11,
             "moe_expert_ffn_fwd": [cfgp] + [p] * 11 + [sz, p],
+            "moe_expert_ffn_fwd_light": [cfgp] + [p] * 11 + [sz, p],
             "moe_expert_ffn_recompute": [cfgp] + [p] * 9 + [sz, p],
             "moe_combine": [cfgp] + [p] * 9 + [i32, p],
             "moe_combine_bwd": [cfgp] + [p] * 12,
@@ -163,6 +164,15 @@ def moe_expert_ffn_fwd(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_
                                                           _ptr(slice_hi), _ptr(saved), _ptr(y_perm), _ptr(ws),
                                                           _nbytes(ws) if ws_bytes is None else ws_bytes,
                                                           _stream() if stream is None else stream))
+
+
+def moe_expert_ffn_fwd_light(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, hidden, y_perm, ws,
+                             stream=None, ws_bytes=None):
+    """moe_expert_ffn_fwd that keeps only the hidden activation (for activation-checkpointed layers)."""
+    _check("moe_expert_ffn_fwd_light", lib().moe_expert_ffn_fwd_light(
+        ctypes.byref(cfg), _ptr(x_perm), _ptr(W1), _ptr(W1b), _ptr(W2), _ptr(offsets), _ptr(kept), _ptr(slice_lo),
+        _ptr(slice_hi), _ptr(hidden), _ptr(y_perm), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+        _stream() if stream is None else stream))
 
 
 def moe_expert_ffn_recompute(cfg, x_perm, W1, W1b, offsets, kept, slice_lo, slice_hi, saved, ws, stream=None,

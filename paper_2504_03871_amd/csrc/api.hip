@@ -303,10 +303,11 @@ int moe_dispatch_static(const moe_cfg* cfg, const void* x, const int32_t* topk_i
 }
 
 namespace {
-// GEMM1 with its activation epilogue into `saved`, then (y_perm != NULL) GEMM2.
+// GEMM1 with its activation epilogue into `saved` (or, saved == NULL, its hidden activation alone into
+// `hidden`), then (y_perm != NULL) GEMM2.
 int ffn_fwd_impl(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b, const void* W2,
                  const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo, const int32_t* slice_hi,
-                 void* saved, void* y_perm, void* ws, hipStream_t s) {
+                 void* saved, void* hidden, void* y_perm, void* ws, hipStream_t s) {
   const bool swiglu = cfg->act == MOE_ACT_SWIGLU;
   const WsLayout w = ws_layout(cfg);
   const int A = cfg->T * cfg->k, d = cfg->d_model, f = cfg->d_ff;
@@ -322,13 +323,18 @@ int ffn_fwd_impl(const moe_cfg* cfg, const void* x_perm, const void* W1, const v
   // hidden = act(x_perm W1)
   g.A = x_perm; g.B = W1; g.B2 = W1b; g.N = f; g.K = d;
   g.C = sv; g.C2 = sv + plane; g.C3 = sv + 2 * plane;
+  char* hid = swiglu ? sv + 2 * plane : sv + plane;
+  if (saved == nullptr) {   // keep nothing but the hidden activation
+    hid = static_cast<char*>(hidden);
+    g.C = nullptr; g.C2 = swiglu ? nullptr : hid; g.C3 = swiglu ? hid : nullptr;
+  }
   {
     ProfScope ps(cfg, MOE_PROF_GEMM1_FWD, s);
     CHECK(launch_gemm(cfg, MODE_NN, swiglu ? EPI_SWIGLU_FWD : EPI_GELU_FWD, swiglu, false, g, max_tiles, s));
   }
   if (y_perm == nullptr) return MOE_OK;
   // y = hidden W2
-  g.A = swiglu ? sv + 2 * plane : sv + plane; g.B = W2; g.B2 = nullptr; g.N = d; g.K = f;
+  g.A = hid; g.B = W2; g.B2 = nullptr; g.N = d; g.K = f;
   g.C = y_perm; g.C2 = g.C3 = nullptr;
   if (is_half(cfg) && split_k_applies(cfg->E, f))   // smallest row tiles: split-K (gemm.h)
     g.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ffn_split);
@@ -350,7 +356,26 @@ int moe_expert_ffn_fwd(const moe_cfg* cfg, const void* x_perm, const void* W1, c
   ALIGNED(slice_hi); ALIGNED(saved); ALIGNED(y_perm); ALIGNED(ws);
   CHECK(check_ws(cfg, ws, ws_bytes));
   if (cfg->T == 0) return MOE_OK;
-  return ffn_fwd_impl(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, saved, y_perm, ws, (hipStream_t)stream);
+  return ffn_fwd_impl(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, saved, nullptr, y_perm, ws,
+                      (hipStream_t)stream);
+}
+
+int moe_expert_ffn_fwd_light(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b, const void* W2,
+                             const int32_t* offsets, const int32_t* kept, const int32_t* slice_lo,
+                             const int32_t* slice_hi, void* hidden, void* y_perm, void* ws, size_t ws_bytes,
+                             void* stream) {
+  CHECK(check_cfg(cfg));
+  CHECK(check_slices(slice_lo, slice_hi));
+  REQUIRE(x_perm); REQUIRE(W1); REQUIRE(W2); REQUIRE(offsets); REQUIRE(kept); REQUIRE(hidden); REQUIRE(y_perm); REQUIRE(ws);
+  const bool swiglu = cfg->act == MOE_ACT_SWIGLU;
+  if (swiglu) REQUIRE(W1b);
+  if (!swiglu && W1b != nullptr) return MOE_ERR_BAD_DTYPE;
+  ALIGNED(x_perm); ALIGNED(W1); ALIGNED(W1b); ALIGNED(W2); ALIGNED(offsets); ALIGNED(kept); ALIGNED(slice_lo);
+  ALIGNED(slice_hi); ALIGNED(hidden); ALIGNED(y_perm); ALIGNED(ws);
+  CHECK(check_ws(cfg, ws, ws_bytes));
+  if (cfg->T == 0) return MOE_OK;
+  return ffn_fwd_impl(cfg, x_perm, W1, W1b, W2, offsets, kept, slice_lo, slice_hi, nullptr, hidden, y_perm, ws,
+                      (hipStream_t)stream);
 }
 
 int moe_expert_ffn_recompute(const moe_cfg* cfg, const void* x_perm, const void* W1, const void* W1b,
@@ -366,7 +391,7 @@ int moe_expert_ffn_recompute(const moe_cfg* cfg, const void* x_perm, const void*
   ALIGNED(saved); ALIGNED(ws);
   CHECK(check_ws(cfg, ws, ws_bytes));
   if (cfg->T == 0) return MOE_OK;
-  return ffn_fwd_impl(cfg, x_perm, W1, W1b, nullptr, offsets, kept, slice_lo, slice_hi, saved, nullptr, ws,
+  return ffn_fwd_impl(cfg, x_perm, W1, W1b, nullptr, offsets, kept, slice_lo, slice_hi, saved, nullptr, nullptr, ws,
                       (hipStream_t)stream);
 }
 

@@ -146,8 +146,8 @@ enum GemmMode {
 
 enum Epilogue {
   EPI_STORE = 0,       // C = acc
-  EPI_GELU_FWD = 1,    // C = acc (pre-activation), C2 = gelu(acc)
-  EPI_SWIGLU_FWD = 2,  // dual accumulators g,u: C = g, C2 = u, C3 = silu(g)*u
+  EPI_GELU_FWD = 1,    // C = acc (pre-activation; skipped when C is NULL), C2 = gelu(acc)
+  EPI_SWIGLU_FWD = 2,  // dual accumulators g,u: C = g, C2 = u (both skipped when C is NULL), C3 = silu(g)*u
   EPI_GELU_BWD = 3,    // C = acc * gelu'(S1)
   EPI_SWIGLU_BWD = 4,  // C = dG = acc * S2 * silu'(S1), C2 = dU = acc * silu(S1)   (S1 = G, S2 = U)
   EPI_DW = 5           // fp32 C_e = acc (+ C_e)
@@ -197,12 +197,14 @@ template <typename T, int EPI>
 __device__ __forceinline__ void epilogue(const GemmArgs& g, size_t idx, float acc, float acc2) {
   if constexpr (EPI == EPI_STORE) {
     reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc);
-  } else if constexpr (EPI == EPI_GELU_FWD) {
-    reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc);
+  } else if constexpr (EPI == EPI_GELU_FWD) {   // C == NULL: the caller keeps only the hidden activation
+    if (g.C != nullptr) reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc);
     reinterpret_cast<T*>(g.C2)[idx] = from_f32<T>(gelu_f(acc));
   } else if constexpr (EPI == EPI_SWIGLU_FWD) {
-    reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc);
-    reinterpret_cast<T*>(g.C2)[idx] = from_f32<T>(acc2);
+    if (g.C != nullptr) {
+      reinterpret_cast<T*>(g.C)[idx] = from_f32<T>(acc);
+      reinterpret_cast<T*>(g.C2)[idx] = from_f32<T>(acc2);
+    }
     reinterpret_cast<T*>(g.C3)[idx] = from_f32<T>(acc * sigmoid_f(acc) * acc2);
   } else if constexpr (EPI == EPI_GELU_BWD) {
     const float a = to_f32(reinterpret_cast<const T*>(g.S1)[idx]);

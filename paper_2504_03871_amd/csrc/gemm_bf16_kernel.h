@@ -183,7 +183,7 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
   } else if constexpr (EPI == EPI_GELU_FWD) {
     // h = a Phi(v), v = the pre-activation as stored: GELU of the saved tensor; Phi looked up (bf16) or evaluated (fp16)
     const uint32_t p0 = H::pack2(a[0], a[1]), p1 = H::pack2(a[2], a[3]);
-    *reinterpret_cast<u32x2*>(reinterpret_cast<ST*>(g.C) + idx) = u32x2{p0, p1};
+    if (g.C != nullptr) *reinterpret_cast<u32x2*>(reinterpret_cast<ST*>(g.C) + idx) = u32x2{p0, p1};   // NULL: only H is kept
     if constexpr (H::GELU_TABLE) {
       st(g.C2, idx, a[0] * gelu_tab_lookup(tab, p0 & 0xffffu), a[1] * gelu_tab_lookup(tab, p0 >> 16),
          a[2] * gelu_tab_lookup(tab, p1 & 0xffffu), a[3] * gelu_tab_lookup(tab, p1 >> 16));
@@ -191,8 +191,10 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
       st(g.C2, idx, a[0] * phi_f(H::lo(p0)), a[1] * phi_f(H::hi(p0)), a[2] * phi_f(H::lo(p1)), a[3] * phi_f(H::hi(p1)));
     }
   } else if constexpr (EPI == EPI_SWIGLU_FWD) {
-    st(g.C, idx, a[0], a[1], a[2], a[3]);
-    st(g.C2, idx, a2[0], a2[1], a2[2], a2[3]);
+    if (g.C != nullptr) {   // NULL: only H is kept
+      st(g.C, idx, a[0], a[1], a[2], a[3]);
+      st(g.C2, idx, a2[0], a2[1], a2[2], a2[3]);
+    }
     float h[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) h[i] = a[i] * sigmoid_fast(a[i]) * a2[i];

@@ -89,6 +89,12 @@ class MoELayer:
         B.moe_expert_ffn_fwd(self.cfg, self.x_perm, self.W1, self.W1b, self.W2, self.offsets, self.kept,
                              self.slice_lo, self.slice_hi, self.saved, self.y_perm, self.ws)
 
+    def ffn_fwd_light(self):
+        """Forward of a checkpointed layer: only the hidden activation is kept (in its plane of `saved`)."""
+        planes = 3 if self.cfg.act == B.ACT_SWIGLU else 2
+        B.moe_expert_ffn_fwd_light(self.cfg, self.x_perm, self.W1, self.W1b, self.W2, self.offsets, self.kept,
+                                   self.slice_lo, self.slice_hi, self.saved_plane(planes - 1), self.y_perm, self.ws)
+
     def ffn_recompute(self):
         """Activation checkpointing: refill the saved planes from x_perm (first half of ffn_fwd)."""
         B.moe_expert_ffn_recompute(self.cfg, self.x_perm, self.W1, self.W1b, self.offsets, self.kept,
@@ -162,8 +168,11 @@ class MoELayer:
     def step_checkpointed(self):
         """Forward, then the backward of a checkpointed layer: gate, dispatch and the saved activations
         are computed again from the layer input before the gradients (y_perm is kept: the combine
-        backward needs the expert outputs)."""
-        self.forward()
+        backward needs the expert outputs).  The forward keeps only the hidden activation."""
+        self.route()
+        self.dispatch()
+        self.ffn_fwd_light()
+        self.combine()
         self.route()
         self.dispatch()
         self.ffn_recompute()

@@ -78,6 +78,9 @@ def test_pointer_validation_happens_before_any_launch():
         B.moe_expert_ffn_fwd(cfg, P, P, P, P, P, P, None, None, P, P, P, stream=s)   # W1b given for GELU
     assert ei.value.code == -3
     with pytest.raises(B.MoeError) as ei:
+        B.moe_expert_ffn_fwd_light(cfg, P, P, None, P, P, P, None, None, None, P, P, stream=s)   # no hidden buffer
+    assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:
         B.moe_expert_ffn_recompute(cfg, P, P, None, P, P, None, None, None, P, stream=s)   # no saved buffer
     assert ei.value.code == -1
     with pytest.raises(B.MoeError) as ei:
@@ -117,6 +120,7 @@ def test_too_small_workspace_is_rejected_before_any_launch():
         lambda n: B.moe_route(cfg, P, P, None, None, P, P, P, ws=P, stream=s, ws_bytes=n),
         lambda n: B.moe_dispatch(cfg, P, P, None, None, P, P, P, P, P, P, P, stream=s, ws_bytes=n),
         lambda n: B.moe_expert_ffn_fwd(cfg, P, P, None, P, P, P, None, None, P, P, P, stream=s, ws_bytes=n),
+        lambda n: B.moe_expert_ffn_fwd_light(cfg, P, P, None, P, P, P, None, None, P, P, P, stream=s, ws_bytes=n),
         lambda n: B.moe_expert_ffn_recompute(cfg, P, P, None, P, P, None, None, P, P, stream=s, ws_bytes=n),
         lambda n: B.moe_expert_ffn_bwd(cfg, P, P, P, P, None, P, P, P, None, None, P, P, None, P, 0, P, stream=s, ws_bytes=n),
         lambda n: B.moe_route_bwd(cfg, P, P, P, P, P, P, P, P, P, stream=s, ws_bytes=n),

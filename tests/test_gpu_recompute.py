@@ -69,3 +69,44 @@ def test_recomputed_activations_and_gradients_are_bit_identical(name):
     for n, key in (("dx", "dx"), ("dW1", "dW1"), ("dW2", "dW2"), ("dWr", "dWr")) + \
             ((("dW1b", "dW1b"),) if w.act == S.ACT_SWIGLU else ()):
         U.assert_close("checkpointed " + n, U.host(getattr(L, n)), ref[key], U.TOL[w.dtype])
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_light_forward_keeps_only_the_hidden_activation(name):
+    """moe_expert_ffn_fwd_light: H and y_perm bit-identical to the saving forward's, the other planes untouched;
+    the checkpointed step built on it gives the gradients of the plain step, bit for bit."""
+    import torch
+    w = CASES[name]
+    print(f"\n[case {name}] {w}", flush=True)
+    inp = S.make_inputs(w)
+    L = U.make_layer(w, inp)
+    if w.partial:
+        L.route()
+        L.dispatch(gather=False)
+        torch.cuda.synchronize()
+        L.set_slices(*S.partial_slices(w, U.host(L.kept)))
+    bits = lambda t: t.view(torch.int16 if t.element_size() == 2 else torch.int32)
+    U.fill_sentinels(L)
+    L.step()
+    torch.cuda.synchronize()
+    nplanes = 3 if w.act == S.ACT_SWIGLU else 2
+    grads = ["dx", "dW1", "dW2", "dWr"] + (["dW1b"] if w.act == S.ACT_SWIGLU else [])
+    keep = {n: getattr(L, n).clone() for n in grads + ["out", "y_perm"]}
+    hidden = L.saved_plane(nplanes - 1).clone()
+
+    U.fill_sentinels(L)
+    sentinel = L.saved_plane(0).clone()
+    L.route()
+    L.dispatch()
+    L.ffn_fwd_light()
+    torch.cuda.synchronize()
+    assert torch.equal(bits(L.saved_plane(nplanes - 1)), bits(hidden)), "hidden activation differs"
+    assert torch.equal(bits(L.y_perm), bits(keep["y_perm"])), "expert outputs differ"
+    for i in range(nplanes - 1):
+        assert torch.equal(bits(L.saved_plane(i)), bits(sentinel)), "a pre-activation plane was written"
+
+    U.fill_sentinels(L)
+    L.step_checkpointed()
+    torch.cuda.synchronize()
+    for n in grads + ["out"]:
+        assert torch.equal(bits(getattr(L, n)), bits(keep[n])), n
