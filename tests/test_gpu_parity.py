@@ -261,3 +261,28 @@ def test_dispatch_many_blocks_and_ids_out_of_range():
         if bad:
             flat = idx.reshape(-1)
             assert (row_of.cpu().numpy()[(flat < 0) | (flat >= E)] == -1).all()
+
+
+def test_random_workloads():
+    """Thirty seeded random small workloads (all three storage types, both activations, 1 to 130 experts, ragged
+    token counts, capacity, skew, partial shares, the split-K widths) through the same checks as the named cases."""
+    import random
+    rnd = random.Random(20250403871)
+    for it in range(30):
+        dt = rnd.choice([S.DT_BF16, S.DT_BF16, S.DT_F16, S.DT_F32])
+        act = rnd.choice([S.ACT_GELU, S.ACT_SWIGLU])
+        E = rnd.choice([1, 2, 3, 4, 5, 8, 12, 16, 17, 32, 33, 64, 70, 130])
+        k = rnd.randint(1, min(E, 8))
+        mult = 64 if dt != S.DT_F32 else 4
+        d = mult * rnd.randint(1, 6 if dt != S.DT_F32 else 40)
+        f = mult * rnd.randint(1, 9 if dt != S.DT_F32 else 60)
+        if dt != S.DT_F32 and rnd.random() < 0.15:
+            f = 2048 + 512 * rnd.randint(0, 2)                       # wide enough for split-K of the smallest tiles
+        T = rnd.choice([1, 7, 33, 100, 257, 300, 511, 600, 1025, 1500])
+        if dt == S.DT_F32:
+            T = min(T, 300)
+        base = W["cfg3"] if act == S.ACT_SWIGLU else W["cfg1"]
+        w = base.scaled(T=T, d=d, f=f, E=E, k=k, capacity_factor=rnd.choice([0.0, 0.0, 0.7, 1.1]),
+                        partial=rnd.random() < 0.4, zipf_s=rnd.choice([0.0, 0.8, 1.3]), dtype=dt)
+        print(f"\n[random {it}] {w}", flush=True)
+        run_case(w)
