@@ -10,7 +10,8 @@ HBM-bound kernels cold and warm), the CPU oracle timed on the host cores as a re
 the step time and all-GEMM fraction of the other benchmark configurations under `other_workloads`.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--also cfg1,cfg2,cfg4|none]
-                  [--no-cpu-baseline] [--checkpoint] [--overlap-gate-bwd]
+                  [--no-cpu-baseline] [--full-oracle] [--checkpoint] [--f16] [--overlap-gate-bwd]
+                  [--clock-probe] [--mfma-loop] [--copy-probe]
 """
 from __future__ import annotations
 
@@ -421,6 +422,9 @@ def main():
     ap.add_argument("--clock-probe", action="store_true",
                     help="sample the shader clock with a one-wave kernel on a second stream while steps run "
                          "(evidence for the clock the chip sustains under the GEMMs; not part of the timed region)")
+    ap.add_argument("--full-oracle", action="store_true",
+                    help="time the CPU oracle on the whole batch instead of a bounded token sample "
+                         "(cfg1: under a minute; cfg3: about an hour of host time)")
     ap.add_argument("--mfma-loop", action="store_true",
                     help="also time a kernel of nothing but MFMAs for both bf16 instruction shapes "
                          "(device.mfma_loop: the matrix-core rate the chip's power management allows)")
@@ -465,13 +469,16 @@ def main():
         per = 18 if w.act == S.ACT_SWIGLU else 12
         target_flops = 1.2e13
         Ts = int(min(w.T, max(256, target_flops // (per * w.k * w.d * w.f))))
+        if args.full_oracle:
+            Ts = w.T
         tc = time.perf_counter()
         O.moe_layer(inp["x"][:Ts], inp["Wr"], inp["bias"], inp["W1"], inp.get("W1b"), inp["W2"], inp["d_out"][:Ts],
                     w.k, w.act, capacity=w.capacity)
         dt = time.perf_counter() - tc
         cpu = {"value": round(Ts / dt, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"first {Ts} of {w.T} tokens of {w.name} through all {w.E} experts, full layer fwd+bwd, "
-                         f"numpy fp64, {dt:.1f} s; tokens/s = sample tokens / that time (extrapolated to the batch)"}
+               "sample": (f"all {w.T} tokens of {w.name}, full layer fwd+bwd, numpy fp64, {dt:.1f} s" if Ts == w.T else
+                          f"first {Ts} of {w.T} tokens of {w.name} through all {w.E} experts, full layer fwd+bwd, "
+                          f"numpy fp64, {dt:.1f} s; tokens/s = sample tokens / that time (extrapolated to the batch)")}
     del inp
     r.pop("inp")
 
