@@ -201,115 +201,103 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
 }
 
 // ---------------------------------------------------------------- forward on the matrix cores (bf16 x)
-// logits = x Wr as a [T x d] x [d x E] product on v_mfma_f32_32x32x16_bf16.  x is bf16 already; the fp32
+// logits = x Wr as a [T x d] x [d x E] product on v_mfma_f32_16x16x32_bf16.  x is bf16 already; the fp32
 // gate weight is split into two bf16 terms, w = hi + lo with hi = bf16(w), lo = bf16(w - hi), and both
 // products are accumulated in fp32, which keeps the weight to about 16 mantissa bits (relative error
 // 2^-17 per product, far below the bf16 resolution of x itself).
 //
-// A block of four waves owns 32 tokens; the waves split K in blocks of 64 (wave w: blocks w, w+4, ...),
-// each multiplies its share for all experts (NTL tiles of 32), and the four partial tiles are added in
-// wave order through LDS (deterministic).  Operands come straight from memory, no LDS staging:
-//  * A: lane (row r = l%32, half h = l/32) reads the 64 contiguous bytes x[t0+r][kb*64 + h*32 .. +31],
-//    i.e. a full 128-byte line per token row, and uses 8 of those 32 elements in each of four MFMA steps;
+// A block of NW waves owns TT tiles of 16 tokens (64 tokens with eight waves, 32 with four); the waves split K in
+// blocks of 128 (wave w: blocks w, w+NW, ...), each multiplies its share for all experts (NET tiles of 16) with
+// the 16 x 16 x 32 MFMA, and the partial tiles are added in wave order through LDS (deterministic).  Operands
+// come straight from memory, no LDS staging:
+//  * A: lane (row r = l%16 of a token tile, quarter c = l/16) reads the 64 contiguous bytes
+//    x[t0+r][kb*128 + c*32 .. +31], so the four lanes of a row cover two whole 128-byte lines, and uses 8 of
+//    those 32 elements in each of four MFMA steps;
 //  * B: wr_frag_kernel writes the two bf16 terms once per call in exactly the register layout of those
-//    steps: unit ((((nt*nkb + kb)*4 + s)*2 + term)*64 + lane) holds, for lane (expert c = l%32 of tile nt,
-//    half h), the eight values Wr[kb*64 + h*32 + s*8 + i][nt*32 + c], i = 0..7 (zero past d or E); a wave
-//    reads a unit group as one contiguous kilobyte.
+//    steps: unit ((((nt*nkb + kb)*4 + s)*2 + term)*64 + lane) holds, for lane (expert e = l%16 of tile nt,
+//    quarter c), the eight values Wr[kb*128 + c*32 + s*8 + i][nt*16 + e], i = 0..7 (zero past d or E); a wave
+//    reads a unit as one contiguous kilobyte, once for all its token tiles.
 // The K order inside a step differs from memory order, which a dot product does not mind as long as
-// both operands agree.  MFMA register layout: see gemm_bf16_kernel.h.
+// both operands agree.  MFMA register layout: see gemm_bf16_kernel.h.  (An earlier version on 32 x 32 x 16
+// tiles with 32 tokens per block read twice as many weight bytes from L2 as x bytes from memory.)
 typedef bf16 rt_bf16x8 __attribute__((ext_vector_type(8)));
-typedef float rt_f32x16 __attribute__((ext_vector_type(16)));
-constexpr int RM_TOK = 32;
+typedef float rt_f32x4 __attribute__((ext_vector_type(4)));
 
-__global__ void wr_frag_kernel(const float* __restrict__ Wr, rt_bf16x8* __restrict__ wfrag, int d, int E, int nkb, int ntl) {
+__global__ void wr_frag_kernel(const float* __restrict__ Wr, rt_bf16x8* __restrict__ wfrag, int d, int E, int nkb, int net) {
   const int u = blockIdx.x * blockDim.x + threadIdx.x;
-  if (u >= ntl * nkb * 4 * 2 * 64) return;
+  if (u >= net * nkb * 4 * 2 * 64) return;
   const int lane = u & 63, term = (u >> 6) & 1, s = (u >> 7) & 3, kb = (u >> 9) % nkb, nt = (u >> 9) / nkb;
-  const int c = nt * 32 + (lane & 31), k0 = kb * 64 + (lane >> 5) * 32 + s * 8;
+  const int e = nt * 16 + (lane & 15), k0 = kb * 128 + (lane >> 4) * 32 + s * 8;
   rt_bf16x8 v;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const float w = (c < E && k0 + i < d) ? Wr[(size_t)(k0 + i) * E + c] : 0.f;
+    const float w = (e < E && k0 + i < d) ? Wr[(size_t)(k0 + i) * E + e] : 0.f;
     const bf16 hi = (bf16)w;
     v[i] = term == 0 ? hi : (bf16)(w - (float)hi);
   }
   wfrag[u] = v;
 }
 
-// NW waves per block split K (more waves in flight per compute unit when the token count alone gives too few
-// blocks to cover the memory latency).
-template <int NTL, int NW>
+template <int NET, int TT, int NW>
 __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
     const bf16* __restrict__ x, const rt_bf16x8* __restrict__ wfrag, const float* __restrict__ bias,
     float* __restrict__ logits_out, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d, int E, int k) {
-  extern __shared__ float part[];   // [NW waves][32 tokens][LD]; the sum ends up in part[0]
-  constexpr int LD = NTL * 32;
+  extern __shared__ float part[];   // [NW waves][TOK tokens][LD]; the sum ends up in part[0]
+  constexpr int TOK = TT * 16, LD = NET * 16;
+  static_assert(TOK == NW * 8, "the selection runs eight lanes per token over the whole block");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int tok0 = blockIdx.x * RM_TOK, nkb = d / 64;
-  const int r = lane & 31, h = lane >> 5;
-  const bf16* xrow = x + (size_t)min(tok0 + r, Tn - 1) * d + h * 32;   // rows past the batch repeat the last token
-  rt_f32x16 acc[NTL];
+  const int tok0 = blockIdx.x * TOK, nkb = (d + 127) / 128;
+  const int r = lane & 15, c = lane >> 4;
+  const bf16* xrow[TT];
 #pragma unroll
-  for (int nt = 0; nt < NTL; ++nt)
+  for (int tt = 0; tt < TT; ++tt) xrow[tt] = x + (size_t)min(tok0 + tt * 16 + r, Tn - 1) * d + c * 32;   // rows past the batch repeat the last token
+  rt_f32x4 acc[TT][NET];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[nt][v] = 0.f;
-  // x (and, with one expert tile, the weight units too) of the next K block are loaded while this one
-  // multiplies: a block lives for a handful of K blocks per wave, so exposed load latency is what it costs
-  constexpr bool PFB = (NTL == 1);
-  rt_bf16x8 a[4], an[4], b[PFB ? 8 : 1], bn[PFB ? 8 : 1];
-  {
-    const int kb0 = min(wave, nkb - 1);
+  for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      a[s] = *reinterpret_cast<const rt_bf16x8*>(xrow + (size_t)kb0 * 64 + s * 8);
-      an[s] = a[s];
-    }
-    if constexpr (PFB) {
-#pragma unroll
-      for (int q = 0; q < 8; ++q) { b[q] = wfrag[((size_t)kb0 * 8 + q) * 64 + lane]; bn[q] = b[q]; }
-    }
-  }
+    for (int nt = 0; nt < NET; ++nt) acc[tt][nt] = rt_f32x4{0.f, 0.f, 0.f, 0.f};
+  const rt_bf16x8 zero = {};
   for (int kb = wave; kb < nkb; kb += NW) {
-    if (kb + NW < nkb) {
+    const bool inb = kb * 128 + c * 32 < d;   // d is a multiple of 64: a lane's 32 elements lie inside the row or past it
+    rt_bf16x8 a[TT][4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) an[s] = *reinterpret_cast<const rt_bf16x8*>(xrow + (size_t)(kb + NW) * 64 + s * 8);
-      if constexpr (PFB) {
+    for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-        for (int q = 0; q < 8; ++q) bn[q] = wfrag[((size_t)(kb + NW) * 8 + q) * 64 + lane];
-      }
-    }
+      for (int s = 0; s < 4; ++s)
+        a[tt][s] = inb ? *reinterpret_cast<const rt_bf16x8*>(xrow[tt] + (size_t)kb * 128 + s * 8) : zero;
 #pragma unroll
-    for (int nt = 0; nt < NTL; ++nt) {
+    for (int nt = 0; nt < NET; ++nt) {
       const rt_bf16x8* wf = wfrag + ((size_t)(nt * nkb + kb) * 8) * 64 + lane;
+      rt_bf16x8 b[8];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], PFB ? b[s * 2] : wf[(s * 2) * 64], acc[nt], 0, 0, 0);
-        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], PFB ? b[s * 2 + 1] : wf[(s * 2 + 1) * 64], acc[nt], 0, 0, 0);
-      }
-    }
+      for (int q = 0; q < 8; ++q) b[q] = wf[q * 64];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) a[s] = an[s];
-    if constexpr (PFB) {
+      for (int s = 0; s < 4; ++s)
 #pragma unroll
-      for (int q = 0; q < 8; ++q) b[q] = bn[q];
+        for (int tt = 0; tt < TT; ++tt) {
+          acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s], b[s * 2], acc[tt][nt], 0, 0, 0);
+          acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s], b[s * 2 + 1], acc[tt][nt], 0, 0, 0);
+        }
     }
   }
-  // partial tiles to LDS: accumulator register v of lane l is token (v/4)*8 + (l/32)*4 + v%4, expert l%32
-  float* mine = part + (size_t)wave * RM_TOK * LD;
+  // partial tiles to LDS: accumulator register v of lane l is token (l/16)*4 + v, expert l%16 of its tile
+  float* mine = part + (size_t)wave * TOK * LD;
 #pragma unroll
-  for (int nt = 0; nt < NTL; ++nt)
+  for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) mine[((v >> 2) * 8 + h * 4 + (v & 3)) * LD + nt * 32 + r] = acc[nt][v];
+    for (int nt = 0; nt < NET; ++nt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) mine[(tt * 16 + c * 4 + v) * LD + nt * 16 + r] = acc[tt][nt][v];
   __syncthreads();
-  for (int i = tid; i < RM_TOK * LD; i += NW * 64) {
+  for (int i = tid; i < TOK * LD; i += NW * 64) {
     const int e = i % LD;
     float sum = part[i];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) sum += part[w * RM_TOK * LD + i];   // wave order: deterministic
+    for (int w = 1; w < NW; ++w) sum += part[w * TOK * LD + i];   // wave order: deterministic
     part[i] = sum + ((bias != nullptr && e < E) ? bias[e] : 0.f);
   }
   __syncthreads();
-  const int ntok = min(RM_TOK, Tn - tok0);
+  const int ntok = min(TOK, Tn - tok0);
   for (int i = tid; i < ntok * E; i += NW * 64) logits_out[(size_t)tok0 * E + i] = part[(i / E) * LD + i % E];
   const int tl = tid >> 3;   // eight lanes per token
   route_select(part, LD, tl, tid & 7, 8, tl < ntok, tok0 + tl, E, k, topk_idx, topk_w);
@@ -468,26 +456,27 @@ __global__ __launch_bounds__(256) void route_bwd_reduce_kernel(const float* __re
 }
 
 // ---------------------------------------------------------------- launchers
+static int route_expert_tiles(int E) { return E <= 16 ? 1 : (E <= 32 ? 2 : (E <= 64 ? 4 : (E <= 128 ? 8 : 16))); }
 size_t route_wfrag_bytes(int d, int E) {
-  const int ntl = E <= 32 ? 1 : (E <= 64 ? 2 : (E <= 128 ? 4 : 8));
-  return (size_t)ntl * ((d + 63) / 64) * 8 * 64 * 16;
+  return (size_t)route_expert_tiles(E) * ((d + 127) / 128) * 8 * 64 * 16;
 }
 
-template <int NTL, int NW>
+template <int NET, int TT, int NW>
 static int launch_route_mfma(const moe_cfg* c, const void* x, const float* Wr, const float* bias, float* logits_out,
                              int32_t* idx, float* w, void* wfrag, hipStream_t s) {
-  const int nkb = c->d_model / 64, units = NTL * nkb * 8 * 64;
-  wr_frag_kernel<<<(units + 255) / 256, 256, 0, s>>>(Wr, (rt_bf16x8*)wfrag, c->d_model, c->E, nkb, NTL);
+  constexpr int TOK = TT * 16;
+  const int nkb = (c->d_model + 127) / 128, units = NET * nkb * 8 * 64;
+  wr_frag_kernel<<<(units + 255) / 256, 256, 0, s>>>(Wr, (rt_bf16x8*)wfrag, c->d_model, c->E, nkb, NET);
   int rc = launch_status();
   if (rc != MOE_OK) return rc;
-  const size_t lds = (size_t)NW * RM_TOK * NTL * 32 * 4;
-  auto kern = route_mfma_kernel<NTL, NW>;
+  const size_t lds = (size_t)NW * TOK * NET * 16 * 4;
+  auto kern = route_mfma_kernel<NET, TT, NW>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return set_hip_error(e);
   }
-  kern<<<(c->T + RM_TOK - 1) / RM_TOK, NW * 64, lds, s>>>((const bf16*)x, (const rt_bf16x8*)wfrag, bias, logits_out, idx, w,
-                                                     c->T, c->d_model, c->E, c->k);
+  kern<<<(c->T + TOK - 1) / TOK, NW * 64, lds, s>>>((const bf16*)x, (const rt_bf16x8*)wfrag, bias, logits_out, idx, w,
+                                                 c->T, c->d_model, c->E, c->k);
   return launch_status();
 }
 
@@ -495,14 +484,17 @@ static int launch_route_mfma(const moe_cfg* c, const void* x, const float* Wr, c
 int launch_route(const moe_cfg* c, const void* x, const float* Wr, const float* bias, const float* logits_in,
                  float* logits_out, int32_t* idx, float* w, void* wfrag, hipStream_t s) {
   if (c->dtype == MOE_DTYPE_BF16 && logits_in == nullptr) {
-    // long rows and few expert tiles: eight waves per block (a block per 32 tokens leaves only T / 32 blocks)
+    // long rows and few expert tiles: eight waves and 64 tokens per block; else four waves and 32 tokens
     const bool wide = c->d_model >= 2048;
-    if (c->E <= 32) return wide ? launch_route_mfma<1, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
-                                : launch_route_mfma<1, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-    if (c->E <= 64) return wide ? launch_route_mfma<2, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
-                                : launch_route_mfma<2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-    if (c->E <= 128) return launch_route_mfma<4, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-    return launch_route_mfma<8, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    switch (route_expert_tiles(c->E)) {
+      case 1: return wide ? launch_route_mfma<1, 4, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
+                          : launch_route_mfma<1, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+      case 2: return wide ? launch_route_mfma<2, 4, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
+                          : launch_route_mfma<2, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+      case 4: return launch_route_mfma<4, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+      case 8: return launch_route_mfma<8, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+      default: return launch_route_mfma<16, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    }
   }
   const RouteGeom gm = route_geom(c->E);
   const int grid = (c->T + gm.tok - 1) / gm.tok;
