@@ -176,11 +176,33 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // exact-erf GELU pieces, SiLU pieces (fp32)
 __device__ __forceinline__ float gelu_f(float a) { return 0.5f * a * erfcf(-a * 0.70710678118654752440f); }
-__device__ __forceinline__ float phi_f(float a) { return 0.5f * erfcf(-a * 0.70710678118654752440f); }
 __device__ __forceinline__ float gelu_grad_f(float a) {
   return 0.5f * erfcf(-a * 0.70710678118654752440f) + a * 0.39894228040143267794f * __expf(-0.5f * a * a);
 }
 __device__ __forceinline__ float sigmoid_f(float g) { return 1.0f / (1.0f + __expf(-g)); }
+// Phi(v) and the normal density at v for the fp16 GELU epilogues, which have no table: erfc by the rational
+// approximation 7.1.26 of Abramowitz and Stegun (t = 1 / (1 + p x), erfc(x) = t (a1 + ... + a5 t^4) exp(-x^2),
+// absolute error 1.5e-7), one exponential and one reciprocal instead of a library erfc.  Over every finite fp16
+// number Phi is within 2.8e-7 and gelu' within 3e-7 of the exact values, against an fp16 resolution of 4.9e-4.
+__device__ __forceinline__ void gelu_pieces_fast(float v, float& phi, float& pdf) {
+  const float x = fabsf(v) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  const float poly = t * fmaf(t, fmaf(t, fmaf(t, fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f), -0.284496736f), 0.254829592f);
+  const float ex = __builtin_amdgcn_exp2f(-(x * x) * 1.44269504088896340736f);   // exp(-v^2 / 2)
+  const float half = 0.5f * poly * ex;
+  phi = v >= 0.f ? 1.0f - half : half;
+  pdf = 0.39894228040143267794f * ex;
+}
+__device__ __forceinline__ float phi_fast(float v) {
+  float phi, pdf;
+  gelu_pieces_fast(v, phi, pdf);
+  return phi;
+}
+__device__ __forceinline__ float gelu_grad_fast(float v) {
+  float phi, pdf;
+  gelu_pieces_fast(v, phi, pdf);
+  return fmaf(v, pdf, phi);
+}
 #endif  // __HIPCC__
 
 }  // namespace moe

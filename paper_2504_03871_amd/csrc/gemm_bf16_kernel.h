@@ -188,7 +188,7 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
       st(g.C2, idx, a[0] * gelu_tab_lookup(tab, p0 & 0xffffu), a[1] * gelu_tab_lookup(tab, p0 >> 16),
          a[2] * gelu_tab_lookup(tab, p1 & 0xffffu), a[3] * gelu_tab_lookup(tab, p1 >> 16));
     } else {
-      st(g.C2, idx, a[0] * phi_f(H::lo(p0)), a[1] * phi_f(H::hi(p0)), a[2] * phi_f(H::lo(p1)), a[3] * phi_f(H::hi(p1)));
+      st(g.C2, idx, a[0] * phi_fast(H::lo(p0)), a[1] * phi_fast(H::hi(p0)), a[2] * phi_fast(H::lo(p1)), a[3] * phi_fast(H::hi(p1)));
     }
   } else if constexpr (EPI == EPI_SWIGLU_FWD) {
     if (g.C != nullptr) {   // NULL: only H is kept
@@ -206,8 +206,8 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
       o0 = a[0] * gelu_tab_lookup(tab, sv1.x & 0xffffu); o1 = a[1] * gelu_tab_lookup(tab, sv1.x >> 16);
       o2 = a[2] * gelu_tab_lookup(tab, sv1.y & 0xffffu); o3 = a[3] * gelu_tab_lookup(tab, sv1.y >> 16);
     } else {
-      o0 = a[0] * gelu_grad_f(H::lo(sv1.x)); o1 = a[1] * gelu_grad_f(H::hi(sv1.x));
-      o2 = a[2] * gelu_grad_f(H::lo(sv1.y)); o3 = a[3] * gelu_grad_f(H::hi(sv1.y));
+      o0 = a[0] * gelu_grad_fast(H::lo(sv1.x)); o1 = a[1] * gelu_grad_fast(H::hi(sv1.x));
+      o2 = a[2] * gelu_grad_fast(H::lo(sv1.y)); o3 = a[3] * gelu_grad_fast(H::hi(sv1.y));
     }
     st(g.C, idx, o0, o1, o2, o3);
   } else if constexpr (EPI == EPI_SWIGLU_BWD) {
