@@ -145,29 +145,65 @@ __global__ __launch_bounds__(CB_THREADS) void combine_bwd_kernel(
     }
 }
 
+// Column units in flight per lane: enough to cover a whole row where the row is long (k <= 2: eight units = 8 KB of
+// 16-bit elements; more experts per token: four), half that for short rows, where the extra units would only be
+// predicated off.
+template <typename TY, int KM, int CU>
+static void launch_combine_one(const moe_cfg* c, const void* y_perm, const float* w, const int32_t* idx, const int32_t* row_of,
+                               const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, void* out,
+                               int accumulate, hipStream_t s) {
+  const int grid = (c->T + CB_THREADS / WAVE - 1) / (CB_THREADS / WAVE);
+  combine_kernel<TY, KM, CU><<<grid, CB_THREADS, 0, s>>>((const TY*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (TY*)out,
+                                                         c->T, c->d_model, c->k, accumulate);
+}
+template <typename TY, int KM, int CU>
+static void launch_combine_bwd_one(const moe_cfg* c, const void* d_out, const void* y_perm, const float* w, const int32_t* idx,
+                                   const int32_t* row_of, const int32_t* offsets, const int32_t* kept, const int32_t* lo,
+                                   const int32_t* hi, void* dy_perm, float* dw, hipStream_t s) {
+  const int grid = (c->T + CB_THREADS / WAVE - 1) / (CB_THREADS / WAVE);
+  combine_bwd_kernel<TY, KM, CU><<<grid, CB_THREADS, 0, s>>>((const TY*)d_out, (const TY*)y_perm, w, idx, row_of, offsets, kept,
+                                                             lo, hi, (TY*)dy_perm, dw, c->T, c->d_model, c->k);
+}
+// true when a row spans more than `units` column units of a wave (16 bytes per lane each)
+template <typename TY>
+static bool long_row(const moe_cfg* c, int units) { return c->d_model > units * WAVE * Vec16<TY>::N; }
+
+template <typename TY>
+static void launch_combine_typed(const moe_cfg* c, const void* y_perm, const float* w, const int32_t* idx, const int32_t* row_of,
+                                 const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, void* out,
+                                 int accumulate, hipStream_t s) {
+#define MOE_ARGS c, y_perm, w, idx, row_of, offsets, kept, lo, hi, out, accumulate, s
+  if (c->k <= 2) { if (long_row<TY>(c, 4)) launch_combine_one<TY, 2, 8>(MOE_ARGS); else launch_combine_one<TY, 2, 4>(MOE_ARGS); }
+  else if (c->k <= 4) { if (long_row<TY>(c, 2)) launch_combine_one<TY, 4, 4>(MOE_ARGS); else launch_combine_one<TY, 4, 2>(MOE_ARGS); }
+  else { if (long_row<TY>(c, 2)) launch_combine_one<TY, 8, 4>(MOE_ARGS); else launch_combine_one<TY, 8, 2>(MOE_ARGS); }
+#undef MOE_ARGS
+}
+template <typename TY>
+static void launch_combine_bwd_typed(const moe_cfg* c, const void* d_out, const void* y_perm, const float* w, const int32_t* idx,
+                                     const int32_t* row_of, const int32_t* offsets, const int32_t* kept, const int32_t* lo,
+                                     const int32_t* hi, void* dy_perm, float* dw, hipStream_t s) {
+#define MOE_ARGS c, d_out, y_perm, w, idx, row_of, offsets, kept, lo, hi, dy_perm, dw, s
+  if (c->k <= 2) { if (long_row<TY>(c, 4)) launch_combine_bwd_one<TY, 2, 8>(MOE_ARGS); else launch_combine_bwd_one<TY, 2, 4>(MOE_ARGS); }
+  else if (c->k <= 4) { if (long_row<TY>(c, 2)) launch_combine_bwd_one<TY, 4, 4>(MOE_ARGS); else launch_combine_bwd_one<TY, 4, 2>(MOE_ARGS); }
+  else { if (long_row<TY>(c, 2)) launch_combine_bwd_one<TY, 8, 4>(MOE_ARGS); else launch_combine_bwd_one<TY, 8, 2>(MOE_ARGS); }
+#undef MOE_ARGS
+}
+
 int launch_combine(const moe_cfg* c, const void* y_perm, const float* w, const int32_t* idx, const int32_t* row_of,
                    const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, void* out,
                    int accumulate, hipStream_t s) {
-  const int grid = (c->T + CB_THREADS / WAVE - 1) / (CB_THREADS / WAVE);
-#define MOE_COMBINE(TY, KM, CU) \
-  combine_kernel<TY, KM, CU><<<grid, CB_THREADS, 0, s>>>((const TY*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (TY*)out, c->T, c->d_model, c->k, accumulate)
-  if (c->dtype == MOE_DTYPE_BF16) { if (c->k <= 2) MOE_COMBINE(bf16, 2, 4); else if (c->k <= 4) MOE_COMBINE(bf16, 4, 2); else MOE_COMBINE(bf16, 8, 1); }
-  else if (c->dtype == MOE_DTYPE_F16) { if (c->k <= 2) MOE_COMBINE(f16, 2, 4); else if (c->k <= 4) MOE_COMBINE(f16, 4, 2); else MOE_COMBINE(f16, 8, 1); }
-  else { if (c->k <= 2) MOE_COMBINE(float, 2, 4); else if (c->k <= 4) MOE_COMBINE(float, 4, 2); else MOE_COMBINE(float, 8, 1); }
-#undef MOE_COMBINE
+  if (c->dtype == MOE_DTYPE_BF16) launch_combine_typed<bf16>(c, y_perm, w, idx, row_of, offsets, kept, lo, hi, out, accumulate, s);
+  else if (c->dtype == MOE_DTYPE_F16) launch_combine_typed<f16>(c, y_perm, w, idx, row_of, offsets, kept, lo, hi, out, accumulate, s);
+  else launch_combine_typed<float>(c, y_perm, w, idx, row_of, offsets, kept, lo, hi, out, accumulate, s);
   return launch_status();
 }
 
 int launch_combine_bwd(const moe_cfg* c, const void* d_out, const void* y_perm, const float* w, const int32_t* idx,
                        const int32_t* row_of, const int32_t* offsets, const int32_t* kept, const int32_t* lo,
                        const int32_t* hi, void* dy_perm, float* dw, hipStream_t s) {
-  const int grid = (c->T + CB_THREADS / WAVE - 1) / (CB_THREADS / WAVE);
-#define MOE_COMBINE_BWD(TY, KM, CU) \
-  combine_bwd_kernel<TY, KM, CU><<<grid, CB_THREADS, 0, s>>>((const TY*)d_out, (const TY*)y_perm, w, idx, row_of, offsets, kept, lo, hi, (TY*)dy_perm, dw, c->T, c->d_model, c->k)
-  if (c->dtype == MOE_DTYPE_BF16) { if (c->k <= 2) MOE_COMBINE_BWD(bf16, 2, 4); else if (c->k <= 4) MOE_COMBINE_BWD(bf16, 4, 2); else MOE_COMBINE_BWD(bf16, 8, 1); }
-  else if (c->dtype == MOE_DTYPE_F16) { if (c->k <= 2) MOE_COMBINE_BWD(f16, 2, 4); else if (c->k <= 4) MOE_COMBINE_BWD(f16, 4, 2); else MOE_COMBINE_BWD(f16, 8, 1); }
-  else { if (c->k <= 2) MOE_COMBINE_BWD(float, 2, 4); else if (c->k <= 4) MOE_COMBINE_BWD(float, 4, 2); else MOE_COMBINE_BWD(float, 8, 1); }
-#undef MOE_COMBINE_BWD
+  if (c->dtype == MOE_DTYPE_BF16) launch_combine_bwd_typed<bf16>(c, d_out, y_perm, w, idx, row_of, offsets, kept, lo, hi, dy_perm, dw, s);
+  else if (c->dtype == MOE_DTYPE_F16) launch_combine_bwd_typed<f16>(c, d_out, y_perm, w, idx, row_of, offsets, kept, lo, hi, dy_perm, dw, s);
+  else launch_combine_bwd_typed<float>(c, d_out, y_perm, w, idx, row_of, offsets, kept, lo, hi, dy_perm, dw, s);
   return launch_status();
 }
 

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
 // of its live slots, so the read traffic is the T*d elements the algorithm needs however large k is.  Every
 // in-share row belongs to exactly one slot, so all of them are written and no other row is touched.
 // The stores are non-temporal (x_perm is far larger than the caches and is read next by another kernel).
-constexpr int GU = 4;
+constexpr int GU = 8;   // 16-byte column pieces per lane in flight: a row of 4096 16-bit elements in one pass
 template <typename T, int KMAX>
 __global__ __launch_bounds__(256) void dispatch_gather_kernel(
     const T* __restrict__ x, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ row_of,
