@@ -347,26 +347,34 @@ __global__ __launch_bounds__(256) void route_bwd_dx_kernel(
     d_logits[(size_t)t * E + e] = v;
   }
   if (dx == nullptr) return;
-  for (int c = lane * VN; c < d; c += WAVE * VN) {
-    Vec16<T> v;
-    v.load(dx + (size_t)t * d + c);
-    float acc[VN];
-    v.unpack(acc);
+  constexpr int U = 4;   // 16-byte pieces of the dx row per lane in flight (dx is touched once here: streaming access)
+  for (int c0 = lane * VN; c0 < d; c0 += WAVE * VN * U) {
+    Vec16<T> v[U];
 #pragma unroll
-    for (int j = 0; j < MOE_MAX_K; ++j)
-      if (j < k) {
-        const float* wr = WrT + (size_t)max(ej[j], 0) * d + c;
+    for (int u = 0; u < U; ++u)
+      if (c0 + u * WAVE * VN < d) v[u].load_nt(dx + (size_t)t * d + c0 + u * WAVE * VN);
 #pragma unroll
-        for (int i = 0; i < VN; i += 4) {
-          const float4 w4 = *reinterpret_cast<const float4*>(wr + i);
-          acc[i] = fmaf(ds[j], w4.x, acc[i]);
-          acc[i + 1] = fmaf(ds[j], w4.y, acc[i + 1]);
-          acc[i + 2] = fmaf(ds[j], w4.z, acc[i + 2]);
-          acc[i + 3] = fmaf(ds[j], w4.w, acc[i + 3]);
+    for (int u = 0; u < U; ++u) {
+      const int c = c0 + u * WAVE * VN;
+      if (c >= d) break;
+      float acc[VN];
+      v[u].unpack(acc);
+#pragma unroll
+      for (int j = 0; j < MOE_MAX_K; ++j)
+        if (j < k) {
+          const float* wr = WrT + (size_t)max(ej[j], 0) * d + c;
+#pragma unroll
+          for (int i = 0; i < VN; i += 4) {
+            const float4 w4 = *reinterpret_cast<const float4*>(wr + i);
+            acc[i] = fmaf(ds[j], w4.x, acc[i]);
+            acc[i + 1] = fmaf(ds[j], w4.y, acc[i + 1]);
+            acc[i + 2] = fmaf(ds[j], w4.z, acc[i + 2]);
+            acc[i + 3] = fmaf(ds[j], w4.w, acc[i + 3]);
+          }
         }
-      }
-    v.pack(acc);
-    v.store(dx + (size_t)t * d + c);
+      v[u].pack(acc);
+      v[u].store_nt(dx + (size_t)t * d + c);
+    }
   }
 }
 
@@ -381,7 +389,7 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_dense_kernel(
     RouteBwdGeom gm) {
   extern __shared__ float4 s_dl4[];   // [slices_per_block][tps][EB] floats
   float* s_dl = reinterpret_cast<float*>(s_dl4);
-  constexpr int VN = Vec16<T>::N, U = 4;
+  constexpr int VN = Vec16<T>::N, U = 8;   // tokens whose x pieces a thread keeps in flight
   const int c = threadIdx.x & (gm.cg_pow2 - 1), slice = threadIdx.x / gm.cg_pow2;
   const int col = (blockIdx.x * gm.cg_pow2 + c) * VN;
   const int row = blockIdx.y * gm.slices_per_block + slice;   // row of partial sums = token slice
@@ -406,7 +414,7 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_dense_kernel(
   for (int tb = 0; tb < nt; tb += U) {
     Vec16<T> xv[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) xv[u].load(x + (size_t)(t0 + min(tb + u, nt - 1)) * d + col);
+    for (int u = 0; u < U; ++u) xv[u].load_nt(x + (size_t)(t0 + min(tb + u, nt - 1)) * d + col);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float xf[VN];
