@@ -55,23 +55,45 @@ def host(t):
     return a.astype(np.float64) if a.dtype == np.float32 else a
 
 
-def rel_err(got, ref):
-    """(relative L2 error, max abs error / max abs ref) over the finite entries of ref."""
+def rel_err(got, ref, scale=None):
+    """(relative L2 error, max abs error / max abs ref) over the finite entries of ref.
+
+    `scale` (same shape as ref, or None) is a second yardstick for outputs that are sums with cancellation:
+    the size each entry would have without it.  The denominators are then the larger of the reference's own
+    norm and the scale's, so that a reference whose few entries all happen to cancel is not the measure.
+    """
     m = np.isfinite(ref)
     g, r = got[m], ref[m]
     den = np.linalg.norm(r)
     mx = np.abs(r).max() if r.size else 0.0
+    if scale is not None:
+        den = max(den, np.linalg.norm(scale[m]))
+        mx = max(mx, np.abs(scale[m]).max() if r.size else 0.0)
     l2 = np.linalg.norm(g - r) / den if den > 0 else np.linalg.norm(g - r)
     ma = np.abs(g - r).max() / mx if mx > 0 else (np.abs(g - r).max() if r.size else 0.0)
     return l2, ma
 
 
-def assert_close(name, got, ref, tol):
+def assert_close(name, got, ref, tol, scale=None):
     assert got.shape == ref.shape, f"{name}: shape {got.shape} vs {ref.shape}"
     assert np.isfinite(got[np.isfinite(ref)]).all(), f"{name}: non-finite values"
-    l2, ma = rel_err(got, ref)
+    l2, ma = rel_err(got, ref, scale)
     assert l2 <= tol and ma <= tol, f"{name}: rel L2 {l2:.3e}, max-abs/max {ma:.3e} > {tol:g}"
     return l2, ma
+
+
+def dot_scale(d_out, y_perm, idx, row_of, offsets, lo, hi):
+    """[T, k]: sqrt(sum_i (d_out[t, i] * y_perm[row, i])^2) of every in-share slot, 0 elsewhere: the size that the
+    rounding errors of the d products of d_topk_w[t, j] = <d_out[t], y_perm[row]> add up to when they are
+    independent (each product is good to the storage type's unit roundoff), whatever the sum cancels to."""
+    T, k = np.asarray(idx).shape
+    ok = O.in_share(idx, row_of, offsets, lo, hi).reshape(T, k)
+    rows = np.asarray(row_of).reshape(T, k)
+    sc = np.zeros((T, k))
+    for j in range(k):
+        t = np.nonzero(ok[:, j])[0]
+        sc[t, j] = np.sqrt(((np.asarray(d_out, dtype=np.float64)[t] * y_perm[rows[t, j]]) ** 2).sum(axis=1))
+    return sc
 
 
 def run_oracle(w: S.Workload, inp: dict, gpu_logits=None, lo=None, hi=None, slice_fn=None):

@@ -52,6 +52,8 @@ CASES = {
     "f16_many_experts": W["cfg1"].scaled(T=700, d=128, f=128, E=200, k=8, dtype=S.DT_F16),
     "f16_one_token": W["cfg1"].scaled(T=1, d=64, f=128, E=4, k=2, dtype=S.DT_F16),
     "f16_split_k_mixed": W["cfg1"].scaled(T=620, d=128, f=2560, E=4, k=2, dtype=S.DT_F16),
+    # one token, two slots, both d_topk_w values a fifth of their uncancelled size
+    "f16_one_token_cancelling": W["cfg1"].scaled(T=1, d=128, f=2560, E=64, k=2, dtype=S.DT_F16, zipf_s=0.8),
 }
 
 
@@ -117,19 +119,31 @@ def run_case(w: S.Workload):
         rep["dy_perm"] = U.assert_close("dy_perm", U.host(L.dy_perm), ref["dy_perm"], tol)
         rep["dx_perm"] = U.assert_close("dx_perm", U.host(L.dx_perm), ref["dx_perm"], tol)
     rep["out"] = U.assert_close("out", U.host(L.out), ref["out"], tol)
-    rep["d_topk_w"] = U.assert_close("d_topk_w", U.host(L.d_topk_w), ref["dw"], tol)
+    # d_topk_w is a dot product over d_model that may cancel; with few slots every reference value can be such a
+    # cancelled sum, so the uncancelled size of the sum is the second yardstick (see gpu_util.dot_scale)
+    dw_scale = U.dot_scale(inp["d_out"], ref["fw"]["Y"], ref["idx"], ref["row_of"], ref["offsets"], ref["lo"], ref["hi"])
+    rep["d_topk_w"] = U.assert_close("d_topk_w", U.host(L.d_topk_w), ref["dw"], tol, scale=dw_scale)
     dead = ~U.O.in_share(ref["idx"], ref["row_of"], ref["offsets"], ref["lo"], ref["hi"])
     assert (U.host(L.d_topk_w).reshape(-1)[dead] == 0).all(), "d_topk_w of dropped / foreign slots must be 0"
     rep["dW1"] = U.assert_close("dW1", U.host(L.dW1), ref["dW1"], tol)
     rep["dW2"] = U.assert_close("dW2", U.host(L.dW2), ref["dW2"], tol)
     if w.act == S.ACT_SWIGLU:
         rep["dW1b"] = U.assert_close("dW1b", U.host(L.dW1b), ref["dW1b"], tol)
-    rep["d_logits"] = U.assert_close("d_logits", U.host(L.d_logits), ref["dlogits"], tol)
+    # gate backward, stage by stage: the oracle's softmax and linear backward applied to the GPU's own d_topk_w
+    dl_s, dWr_s, dxg_s = U.O.route_bwd(inp["x"], inp["Wr"], ref["idx"], ref["w"], U.host(L.d_topk_w))
+    rep["d_logits (stage)"] = U.assert_close("d_logits (stage)", U.host(L.d_logits), dl_s, tol)
+    rep["dWr (stage)"] = U.assert_close("dWr (stage)", U.host(L.dWr), dWr_s, tol)
+    rep["dx (stage)"] = U.assert_close("dx (stage)", U.host(L.dx), ref["dx_experts"] + dxg_s, tol)
     unsel = np.ones((w.T, w.E), bool)
     np.put_along_axis(unsel, ref["idx"].astype(np.int64), False, axis=1)
     assert (U.host(L.d_logits)[unsel] == 0).all()
-    rep["dWr"] = U.assert_close("dWr", U.host(L.dWr), ref["dWr"], tol)
-    rep["dx"] = U.assert_close("dx", U.host(L.dx), ref["dx"], tol)
+    # and end to end against the oracle's own chain.  d_logits is w_j (dw_j - sum_i w_i dw_i): with a handful of
+    # slots the difference can cancel what is left of already cancelled dot products, and then no fixed
+    # tolerance relative to the reference holds, so this needs enough slots for the largest value to be typical
+    if w.T * w.k >= 64:
+        rep["d_logits"] = U.assert_close("d_logits", U.host(L.d_logits), ref["dlogits"], tol)
+        rep["dWr"] = U.assert_close("dWr", U.host(L.dWr), ref["dWr"], tol)
+        rep["dx"] = U.assert_close("dx", U.host(L.dx), ref["dx"], tol)
     return L, ref, rep
 
 

@@ -266,3 +266,31 @@ def test_dw_is_gradient_of_weights():
     rows = row_of[live]
     tok = np.nonzero(live)[0] // k
     np.testing.assert_allclose(dy[rows], w.reshape(-1)[live][:, None] * dout[tok], rtol=1e-15)
+
+
+def test_dot_scale_is_the_size_of_storage_rounding_in_d_topk_w():
+    """The parity tests measure d_topk_w = <d_out, y_perm row> also against gpu_util.dot_scale.  Rounding y to
+    fp16 (unit roundoff 2^-11, relative error uniform, variance u^2/3 at most) must move the dot product by about
+    u/sqrt(3) times that scale, whatever the dot product itself cancels to."""
+    from tests import gpu_util as U
+    rng = np.random.default_rng(5)
+    T, k, d = 400, 2, 128
+    y = rng.standard_normal((T * k, d))
+    d_out = rng.standard_normal((T, d))
+    idx = np.zeros((T, k), dtype=np.int32)
+    idx[:, 1] = 1
+    # two experts: expert 0 holds the rows of slot 0, expert 1 those of slot 1
+    order = np.argsort(idx.reshape(-1), kind="stable")
+    row_of = np.empty(T * k, dtype=np.int64)
+    row_of[order] = np.arange(T * k)
+    offsets = np.array([0, T], dtype=np.int64)
+    lo, hi = np.zeros(2, dtype=np.int64), np.array([T, T // 2], dtype=np.int64)            # half of expert 1 is foreign
+    sc = U.dot_scale(d_out, y, idx, row_of, offsets, lo, hi)
+    _, dw = O.combine_bwd(d_out, y, np.ones((T, k)), idx, row_of, offsets, lo, hi)
+    _, dw16 = O.combine_bwd(d_out, y.astype(np.float16).astype(np.float64), np.ones((T, k)), idx, row_of, offsets, lo, hi)
+    ok = O.in_share(idx, row_of, offsets, lo, hi).reshape(T, k)
+    assert (sc[~ok] == 0).all() and (sc[ok] > 0).all()
+    z = (dw16 - dw)[ok] / (2.0 ** -11 / np.sqrt(3) * sc[ok])
+    assert 0.4 < z.std() < 1.0 and np.abs(z).max() < 5          # binade structure makes the variance a bit smaller
+    # the scale is what the reference's own magnitude is when nothing cancels in particular
+    assert 0.8 < np.sqrt((dw[ok] ** 2).mean()) / np.sqrt((sc[ok] ** 2).mean()) < 1.2
