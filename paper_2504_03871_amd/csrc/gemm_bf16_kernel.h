@@ -532,7 +532,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
   }
 
   {
-    // per-wave slab [32][WTN*32 + 8] fp32 (the ring is free: the loop ended with a block barrier)
+    // per-wave slab [32][WTN*32 + 4] fp32 (the stages are free: the loop ended with a block barrier)
     constexpr int C = WTN * 32, P = C + 4, LPR = C / 4, RPP = 64 / LPR, PASSES = 32 / RPP;
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * P);
     const int rr = lane / LPR, c4 = lane % LPR;
