@@ -174,6 +174,22 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, WAVE);
+  return v;
+}
+// inclusive prefix sum over the lanes of a wave
+__device__ __forceinline__ int wave_scan_i(int v) {
+  const int lane = threadIdx.x & (WAVE - 1);
+#pragma unroll
+  for (int d = 1; d < WAVE; d <<= 1) {
+    const int up = __shfl_up(v, d, WAVE);
+    if (lane >= d) v += up;
+  }
+  return v;
+}
+
 // exact-erf GELU pieces, SiLU pieces (fp32)
 __device__ __forceinline__ float gelu_f(float a) { return 0.5f * a * erfcf(-a * 0.70710678118654752440f); }
 __device__ __forceinline__ float gelu_grad_f(float a) {

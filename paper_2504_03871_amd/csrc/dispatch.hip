@@ -15,6 +15,7 @@ constexpr int DP_THREADS = 256;
 constexpr int DP_WAVES = DP_THREADS / WAVE;
 constexpr int DP_ROUNDS = DISPATCH_CHUNK / DP_THREADS;   // 4
 constexpr int DP_SUB = DP_ROUNDS * DP_WAVES;             // 16 sub-chunks of 64 assignments, ascending
+static_assert(MOE_MAX_E == 4 * WAVE, "the rank kernel scans the experts four per lane of one wave");
 
 __global__ __launch_bounds__(DP_THREADS) void dispatch_hist_kernel(const int32_t* __restrict__ topk_idx, int A, int E,
                                                                   int32_t* __restrict__ blk_cnt) {
@@ -62,36 +63,7 @@ __global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
   __shared__ int s_sub[DP_SUB][MOE_MAX_E];       // per sub-chunk counts, then exclusive offsets
   const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
 
-  // scan over blocks (few blocks: each block redoes it, nblk*E is tiny) and over experts
-  for (int e = tid; e < MOE_MAX_E; e += DP_THREADS) {
-    int before = 0, total = 0;
-    if (e < E) {
-      if constexpr (SCANNED) {
-        if (nblk > 0) { before = blk_cnt[(size_t)blockIdx.x * E + e]; total = blk_cnt[(size_t)nblk * E + e]; }
-      } else {
-        for (int b = 0; b < nblk; ++b) {
-          const int c = blk_cnt[(size_t)b * E + e];
-          before += (b < (int)blockIdx.x) ? c : 0;
-          total += c;
-        }
-      }
-    }
-    const int m = (capacity > 0) ? min(total, capacity) : total;
-    s_before[e] = before;
-    s_kept[e] = m;
-    if (blockIdx.x == 0 && e < E) { counts[e] = total; kept[e] = m; }
-    for (int sc = 0; sc < DP_SUB; ++sc) s_sub[sc][e] = 0;
-  }
-  __syncthreads();
-  if (tid == 0) {   // E <= 256: a serial scan costs less than a barrier-heavy parallel one
-    int run = 0;
-    for (int e = 0; e < E; ++e) { s_off[e] = run; run += s_kept[e]; }
-    s_off[E] = run;
-  }
-  __syncthreads();
-  if (blockIdx.x == 0)
-    for (int e = tid; e <= E; e += DP_THREADS) offsets[e] = s_off[e];
-
+  // this block's assignments: loaded first, so that their latency runs beside the scan over blocks
   const int base = blockIdx.x * DISPATCH_CHUNK;
   int my_e[DP_ROUNDS], my_rank[DP_ROUNDS];
 #pragma unroll
@@ -99,20 +71,105 @@ __global__ __launch_bounds__(DP_THREADS) void dispatch_rank_kernel(
     const int a = base + r * DP_THREADS + tid;
     int e = (a < A) ? topk_idx[a] : -1;
     if (e < 0 || e >= E) e = -1;        // past the end, or an id outside [0, E): dropped, never an index
-    const bool valid = e >= 0;
     my_e[r] = e;
-    // rank among the lanes of this wave with the same expert; one pass per distinct expert present
-    unsigned long long todo = __ballot(valid);
-    int rank = 0;
-    while (todo) {
-      const int leader = __ffsll((long long)todo) - 1;
-      const int e0 = __shfl(e, leader, WAVE);
-      const unsigned long long same = __ballot(valid && e == e0);
-      if (valid && e == e0) {
-        rank = __popcll(same & ((1ull << lane) - 1ull));
-        if (rank == 0) s_sub[r * DP_WAVES + wave][e0] = __popcll(same);   // one writer per (sub-chunk, expert)
+  }
+
+  // scan over blocks: s_before = assignments of e in earlier blocks, s_kept = all of them for now
+  for (int e = tid; e < MOE_MAX_E; e += DP_THREADS) { s_before[e] = 0; s_kept[e] = 0; }
+  for (int sc = 0; sc < DP_SUB; ++sc)
+    for (int e = tid; e < E; e += DP_THREADS) s_sub[sc][e] = 0;
+  __syncthreads();
+  if constexpr (SCANNED) {
+    for (int e = tid; e < E; e += DP_THREADS)
+      if (nblk > 0) { s_before[e] = blk_cnt[(size_t)blockIdx.x * E + e]; s_kept[e] = blk_cnt[(size_t)nblk * E + e]; }
+  } else {
+    // few blocks: every block adds up all nblk x E counts itself: all threads load, eight counts each in
+    // flight; a thread walks the flat index i = b * E + e in steps of the block size, keeps sums in
+    // registers while its expert stays the same (always, when E divides the block size) and adds them to
+    // LDS when it changes (integer sums: the order of the additions does not matter)
+    const int n = nblk * E;
+    const int db = DP_THREADS / E, de = DP_THREADS % E;
+    int b = tid / E, e = tid % E;
+    int cur = e, tot = 0, bef = 0;
+    for (int i0 = tid; i0 < n; i0 += DP_THREADS * 8) {
+      int c[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * DP_THREADS;
+        c[u] = i < n ? blk_cnt[i] : 0;
       }
-      todo &= ~same;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (e != cur) {
+          if (tot != 0) atomicAdd(&s_kept[cur], tot);
+          if (bef != 0) atomicAdd(&s_before[cur], bef);
+          cur = e; tot = 0; bef = 0;
+        }
+        tot += c[u];
+        bef += (b < (int)blockIdx.x) ? c[u] : 0;
+        b += db;
+        e += de;
+        if (e >= E) { e -= E; ++b; }
+      }
+    }
+    if (tot != 0) atomicAdd(&s_kept[cur], tot);
+    if (bef != 0) atomicAdd(&s_before[cur], bef);
+  }
+  __syncthreads();
+  // kept counts and their exclusive scan over the experts: the first wave, four experts per lane
+  if (wave == 0) {
+    int m[4], sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = lane * 4 + i;
+      const int total = s_kept[e];
+      m[i] = (capacity > 0) ? min(total, capacity) : total;
+      if (blockIdx.x == 0 && e < E) { counts[e] = total; kept[e] = m[i]; }
+      sum += m[i];
+    }
+    const int incl = wave_scan_i(sum);
+    int run = incl - sum;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = lane * 4 + i;
+      s_kept[e] = m[i];
+      s_off[e] = run;
+      run += m[i];
+    }
+    if (lane == WAVE - 1) s_off[MOE_MAX_E] = run;
+  }
+  __syncthreads();
+  // experts past E hold zero counts, so s_off[E] == s_off[MOE_MAX_E] == all kept rows
+  if (blockIdx.x == 0)
+    for (int e = tid; e <= E; e += DP_THREADS) offsets[e] = s_off[e];
+
+#pragma unroll
+  for (int r = 0; r < DP_ROUNDS; ++r) {
+    const int e = my_e[r];
+    const bool valid = e >= 0;
+    // rank among the lanes of this wave with the same expert, and the number of such lanes
+    int rank = 0;
+    if (E <= 16) {   // few experts: one pass of ballots per distinct expert present
+      unsigned long long todo = __ballot(valid);
+      while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int e0 = __shfl(e, leader, WAVE);
+        const unsigned long long same = __ballot(valid && e == e0);
+        if (valid && e == e0) {
+          rank = __popcll(same & ((1ull << lane) - 1ull));
+          if (rank == 0) s_sub[r * DP_WAVES + wave][e0] = __popcll(same);   // one writer per (sub-chunk, expert)
+        }
+        todo &= ~same;
+      }
+    } else {         // many experts, up to 64 distinct ones in the wave: compare with every lane in turn
+      int cnt = 0;
+#pragma unroll
+      for (int l = 0; l < WAVE; ++l) {
+        const bool same = __builtin_amdgcn_readlane(e, l) == e;
+        cnt += same;
+        rank += same && l < lane;
+      }
+      if (valid && rank == 0) s_sub[r * DP_WAVES + wave][e] = cnt;
     }
     my_rank[r] = rank;
   }

@@ -10,13 +10,17 @@ namespace moe {
 // partly filled tiles by descending row count.  Blocks are dispatched in tile order, so the short
 // tiles fill the chip's last round instead of each costing a full round.
 // header[0] = number of tiles, header[1] = tiles walked XCD by XCD, header[2] = trailing tiles that may be split along K (gemm.h).
-__global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept,
-                                                       const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
-                                                       int E, int tile_rows, int32_t* __restrict__ header,
-                                                       RowTile* __restrict__ tiles, int32_t* __restrict__ order,
-                                                       float* __restrict__ gelu_tab, int table) {
-  __shared__ int s_full[MOE_MAX_E], s_rem[MOE_MAX_E], s_start[MOE_MAX_E + 1], s_len[MOE_MAX_E];
-  __shared__ int s_nfull, s_npart, s_major;
+constexpr int TM_THREADS = 4 * MOE_MAX_E;   // four threads per expert
+__global__ __launch_bounds__(TM_THREADS) void tile_map_kernel(const int32_t* __restrict__ offsets, const int32_t* __restrict__ kept,
+                                                              const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
+                                                              int E, int tile_rows, int32_t* __restrict__ header,
+                                                              RowTile* __restrict__ tiles, int32_t* __restrict__ order,
+                                                              float* __restrict__ gelu_tab, int table) {
+  // sort keys: (value << 32) | (MOE_MAX_E - 1 - id), so that "ahead of me" (larger value, ties by lower id) is
+  // one 64-bit comparison; entries from E on hold value 0 and ids above every real one: never ahead
+  __shared__ __align__(16) unsigned long long s_klen[MOE_MAX_E], s_krem[MOE_MAX_E];
+  __shared__ int s_full[MOE_MAX_E], s_rem[MOE_MAX_E], s_start[MOE_MAX_E], s_base[MOE_MAX_E];
+  __shared__ int s_nfull, s_major;
   if (blockIdx.x > 0) {   // blocks past the first fill the table: Phi(v) or gelu'(v) for the bf16 numbers (layout: gemm.h)
     for (int i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < GELU_TAB_FLOATS; i += (gridDim.x - 1) * blockDim.x) {
       float v = 0.f;
@@ -32,49 +36,74 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
     }
     return;
   }
-  const int e = threadIdx.x;
-  int l = 0, h = 0;
-  if (e < E) share_of(lo, hi, kept[e], e, l, h);
-  s_full[e] = (h - l) / tile_rows;
-  s_rem[e] = (h - l) % tile_rows;
-  s_len[e] = h - l;
-  __syncthreads();
-  if (e < E) {   // experts by descending share length, ties by id
-    int rank = 0;
-    for (int o = 0; o < E; ++o) rank += (s_len[o] > s_len[e]) || (s_len[o] == s_len[e] && o < e);
-    order[rank] = e;
-  }
-  if (threadIdx.x == 0) {
-    int run = 0, parts = 0;
-    int small = 0;
-    for (int i = 0; i < E; ++i) {
-      s_start[i] = run;
-      run += s_full[i];
-      parts += (s_rem[i] > 0);
-      small += (s_rem[i] > 0 && s_rem[i] <= SPLIT_ROWS);
+  const int tid = threadIdx.x;
+  if (tid < MOE_MAX_E) {
+    int l = 0, h = 0, base = 0;
+    if (tid < E) {
+      share_of(lo, hi, kept[tid], tid, l, h);
+      base = offsets[tid] + l;
     }
-    s_nfull = run;
-    s_npart = parts;
+    const int rem = (h - l) % tile_rows;
+    s_full[tid] = (h - l) / tile_rows;
+    s_rem[tid] = rem;
+    s_base[tid] = base;
+    s_klen[tid] = ((unsigned long long)(h - l) << 32) | (unsigned)(MOE_MAX_E - 1 - tid);
+    s_krem[tid] = ((unsigned long long)rem << 32) | (unsigned)(MOE_MAX_E - 1 - tid);
+  }
+  __syncthreads();
+  // Expert e = tid / 4; its four threads each compare it with a quarter of the experts and add up.
+  const int e = tid >> 2, part = tid & 3;
+  const int per = 2 * ((E + 7) / 8);     // entries per quarter, even (16-byte LDS reads)
+  auto rank_desc = [&](const unsigned long long* key) {   // number of entries ahead of key[e]
+    const unsigned long long mine = key[e];
+    int rank = 0;
+#pragma unroll 4
+    for (int o = part * per; o < min((part + 1) * per, MOE_MAX_E); o += 2) {
+      const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(key + o);
+      rank += (v.x > mine) + (v.y > mine);
+    }
+    rank += __shfl_xor(rank, 1, WAVE);
+    rank += __shfl_xor(rank, 2, WAVE);
+    return rank;
+  };
+  const int rank_len = rank_desc(s_klen), rank_rem = rank_desc(s_krem);
+  if (part == 0 && e < E) order[rank_len] = e;   // experts by descending share length, ties by id
+  if (tid < WAVE) {   // the first wave scans the experts, four per lane (MOE_MAX_E = 4 x 64)
+    int full[4], some[4], sum_full = 0, sum_part = 0, sum_small = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      full[i] = s_full[tid * 4 + i];
+      const int rem = s_rem[tid * 4 + i];
+      some[i] = rem > 0;
+      sum_full += full[i];
+      sum_part += some[i];
+      sum_small += (rem > 0 && rem <= SPLIT_ROWS);
+    }
+    const int run = wave_sum_i(sum_full), parts = wave_sum_i(sum_part), small = wave_sum_i(sum_small);
     // Many experts of few row tiles each: an expert's weight panels are used by two or three tiles only,
     // so these must run together (same XCD, same time) or the panels are fetched once per tile.  The
     // list is then expert-major (each expert's full tiles, then its partly filled one) and the whole of
     // it is walked as the full region is.
-    s_major = E > SPLIT_MAX_E && run < 3 * E;
-    if (s_major) {
-      int pos = 0;
-      for (int i = 0; i < E; ++i) {
-        s_start[i] = pos;
-        pos += s_full[i] + (s_rem[i] > 0);
-      }
+    const bool major = E > SPLIT_MAX_E && run < 3 * E;
+    const int mine = major ? sum_full + sum_part : sum_full;
+    int pos = wave_scan_i(mine) - mine;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s_start[tid * 4 + i] = pos;
+      pos += full[i] + (major ? some[i] : 0);
     }
-    header[0] = run + parts;
-    header[1] = s_major ? run + parts : run;
-    header[2] = s_major ? 0 : small;   // the last entries: the partly filled tiles are sorted by descending size
+    if (tid == 0) {
+      s_nfull = run;
+      s_major = major;
+      header[0] = run + parts;
+      header[1] = major ? run + parts : run;
+      header[2] = major ? 0 : small;   // the last entries: the partly filled tiles are sorted by descending size
+    }
   }
   __syncthreads();
   if (e < E) {
-    const int base = offsets[e] + l;
-    for (int i = 0; i < s_full[e]; ++i) {
+    const int base = s_base[e], nfull = s_full[e];
+    for (int i = part; i < nfull; i += 4) {   // the expert's four threads share its full tiles
       RowTile t;
       t.e = e;
       t.row0 = base + i * tile_rows;
@@ -82,23 +111,21 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
       t.pad = 0;
       tiles[s_start[e] + i] = t;
     }
-    if (s_rem[e] > 0) {
-      int rank = 0;   // position among the partial tiles: more rows first, ties by expert id
-      for (int o = 0; o < E; ++o) rank += (s_rem[o] > s_rem[e]) || (s_rem[o] == s_rem[e] && o < e);
+    if (part == 0 && s_rem[e] > 0) {   // position among the partial tiles: more rows first, ties by expert id
       RowTile t;
       t.e = e;
-      t.row0 = base + s_full[e] * tile_rows;
+      t.row0 = base + nfull * tile_rows;
       t.nrows = s_rem[e];
       t.pad = 0;
-      tiles[s_major ? s_start[e] + s_full[e] : s_nfull + rank] = t;
+      tiles[s_major ? s_start[e] + nfull : s_nfull + rank_rem] = t;
     }
   }
 }
 
 int launch_tile_map(const int32_t* offsets, const int32_t* kept, const int32_t* lo, const int32_t* hi, int E,
                     int tile_rows, TileMap map, int table, hipStream_t s) {
-  const int grid = table == GELU_TAB_NONE ? 1 : 1 + GELU_TAB_FLOATS / 256;   // one thread per table entry
-  tile_map_kernel<<<grid, 256, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles, map.order,
+  const int grid = table == GELU_TAB_NONE ? 1 : 1 + (GELU_TAB_FLOATS + TM_THREADS - 1) / TM_THREADS;   // one thread per table entry
+  tile_map_kernel<<<grid, TM_THREADS, 0, s>>>(offsets, kept, lo, hi, E, tile_rows, map.header, map.tiles, map.order,
                                     map.gelu_tab, table);
   return launch_status();
 }
