@@ -257,27 +257,82 @@ __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
 #pragma unroll
     for (int nt = 0; nt < NET; ++nt) acc[tt][nt] = rt_f32x4{0.f, 0.f, 0.f, 0.f};
   const rt_bf16x8 zero = {};
-  for (int kb = wave; kb < nkb; kb += NW) {
+  auto load_a = [&](rt_bf16x8 (*dst)[4], int kb) {
     const bool inb = kb * 128 + c * 32 < d;   // d is a multiple of 64: a lane's 32 elements lie inside the row or past it
-    rt_bf16x8 a[TT][4];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
       for (int s = 0; s < 4; ++s)
-        a[tt][s] = inb ? *reinterpret_cast<const rt_bf16x8*>(xrow[tt] + (size_t)kb * 128 + s * 8) : zero;
+        dst[tt][s] = inb ? *reinterpret_cast<const rt_bf16x8*>(xrow[tt] + (size_t)kb * 128 + s * 8) : zero;
+  };
+  auto load_b = [&](rt_bf16x8* dst, int kb, int nt) {
+    const rt_bf16x8* wf = wfrag + ((size_t)(nt * nkb + kb) * 8) * 64 + lane;
 #pragma unroll
-    for (int nt = 0; nt < NET; ++nt) {
-      const rt_bf16x8* wf = wfrag + ((size_t)(nt * nkb + kb) * 8) * 64 + lane;
-      rt_bf16x8 b[8];
+    for (int q = 0; q < 8; ++q) dst[q] = wf[q * 64];
+  };
+  auto mfmas = [&](rt_bf16x8 (*a)[4], const rt_bf16x8* b, int nt) {
 #pragma unroll
-      for (int q = 0; q < 8; ++q) b[q] = wf[q * 64];
+    for (int s = 0; s < 4; ++s)
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
+      for (int tt = 0; tt < TT; ++tt) {
+        acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s], b[s * 2], acc[tt][nt], 0, 0, 0);
+        acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s], b[s * 2 + 1], acc[tt][nt], 0, 0, 0);
+      }
+  };
+  if constexpr (NET >= 4) {
+    // Many expert tiles: a block streams the whole gate weight (1-2 MB) through its four waves, and a wave
+    // that waits for each 8 KB unit before asking for the next one spends its time in L2 round trips.  The
+    // units run through a ring of PF register buffers, PF - 1 of them in flight ahead of the one the
+    // MFMAs use, across the K blocks; the token rows of the next K block are loaded one block ahead.
+    constexpr int PF = 4;
+    static_assert(NET % PF == 0, "unit nt of any K block sits in buffer nt % PF");
+    // The blocks of an XCD would all ask its L2 for the same unit at the same time (one or two channels
+    // serving 32 compute units); every block therefore starts its walk over the K blocks at another one.
+    rt_bf16x8 a[TT][4], an[TT][4], b[PF][8];
+    const int n_it = wave < nkb ? (nkb - wave + NW - 1) / NW : 0;   // K blocks wave, wave + NW, ... of this wave
+    const int rot = n_it > 0 ? (int)(blockIdx.x % n_it) : 0;
+    auto kb_of = [&](int it) {
+      int j = it + rot;
+      if (j >= n_it) j -= n_it;
+      return wave + NW * j;
+    };
+    if (n_it > 0) {
+      load_a(a, kb_of(0));
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-          acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s], b[s * 2], acc[tt][nt], 0, 0, 0);
-          acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s], b[s * 2 + 1], acc[tt][nt], 0, 0, 0);
-        }
+      for (int p = 0; p < PF - 1; ++p) load_b(b[p], kb_of(0), p);
+    }
+    for (int it = 0; it < n_it; ++it) {
+      const int kb = kb_of(it);
+      const bool more = it + 1 < n_it;
+      const int kbn = more ? kb_of(it + 1) : kb;
+      if (more) load_a(an, kbn);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int nt = 0; nt < NET; ++nt) {
+        constexpr int AHEAD = PF - 1;
+        if (nt + AHEAD < NET) load_b(b[(nt + AHEAD) % PF], kb, nt + AHEAD);
+        else if (more) load_b(b[(nt + AHEAD) % PF], kbn, nt + AHEAD - NET);
+        __builtin_amdgcn_sched_barrier(0);   // the loads stay here, ahead of the MFMAs: left alone, the scheduler sinks each to its use
+        mfmas(a, b[nt % PF], nt);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (more) {
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) a[tt][s] = an[tt][s];
+      }
+    }
+  } else {
+    for (int kb = wave; kb < nkb; kb += NW) {
+      rt_bf16x8 a[TT][4];
+      load_a(a, kb);
+#pragma unroll
+      for (int nt = 0; nt < NET; ++nt) {
+        rt_bf16x8 b[8];
+        load_b(b, kb, nt);
+        mfmas(a, b, nt);
+      }
     }
   }
   // partial tiles to LDS: accumulator register v of lane l is token (l/16)*4 + v, expert l%16 of its tile
