@@ -35,7 +35,10 @@ WsLayout ws_layout(const moe_cfg* c) {
   w.tile_map = off;
   off += align_up(tile_map_bytes(max_row_tiles((int)A, c->E, TILE_ROWS_MIN), c->E), 256);
   w.route_partials = off;
-  off += align_up((size_t)route_bwd_geom(c->T, c->d_model, (int)elt_size(c), c->E).partial_rows * c->d_model * c->E * 4, 256);
+  const size_t partial_rows = route_bwd_uses_mfma(c->dtype == MOE_DTYPE_BF16, c->E)
+                                  ? (size_t)route_bwd_mfma_geom(c->T, c->d_model, c->E).rows
+                                  : (size_t)route_bwd_geom(c->T, c->d_model, (int)elt_size(c), c->E).partial_rows;
+  off += align_up(partial_rows * c->d_model * c->E * 4, 256);
   w.route_wrt = off;   // shared with the forward's gate weight in MFMA operand layout (never live together)
   off += align_up(std::max((size_t)c->d_model * c->E * 4, route_wfrag_bytes(c->d_model, c->E)), 256);
   w.ffn_split = off;

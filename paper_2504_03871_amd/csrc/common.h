@@ -66,6 +66,26 @@ inline RouteBwdGeom route_bwd_geom(int T, int d, int elt_bytes, int E) {
   gm.partial_rows = gm.row_blocks * gm.slices_per_block;
   return gm;
 }
+// Gate weight gradient on the matrix cores (bf16 inputs, more than 16 experts): a block owns 128 columns of
+// x, up to 128 experts and a slice of tokens, a multiple of 32 long, chosen so that the grid is about two
+// blocks per compute unit; every slice writes one row of E x d partial sums.
+constexpr int ROUTE_BWD_MFMA_COLS = 128, ROUTE_BWD_MFMA_KSTEP = 32, ROUTE_BWD_MFMA_EXPERTS = 128;
+struct RouteBwdMfmaGeom { int col_blocks, expert_blocks, slice_tokens, rows; };
+inline bool route_bwd_uses_mfma(int dtype_is_bf16, int E) { return dtype_is_bf16 && E > 16; }
+inline RouteBwdMfmaGeom route_bwd_mfma_geom(int T, int d, int E) {
+  RouteBwdMfmaGeom gm;
+  gm.col_blocks = (d + ROUTE_BWD_MFMA_COLS - 1) / ROUTE_BWD_MFMA_COLS;
+  gm.expert_blocks = (E + ROUTE_BWD_MFMA_EXPERTS - 1) / ROUTE_BWD_MFMA_EXPERTS;
+  int slices = 512 / (gm.col_blocks * gm.expert_blocks);
+  if (slices < 1) slices = 1;
+  int len = (T + slices - 1) / slices;
+  len = (len + ROUTE_BWD_MFMA_KSTEP - 1) / ROUTE_BWD_MFMA_KSTEP * ROUTE_BWD_MFMA_KSTEP;
+  if (len < 4 * ROUTE_BWD_MFMA_KSTEP) len = 4 * ROUTE_BWD_MFMA_KSTEP;
+  gm.slice_tokens = len;
+  gm.rows = (T + len - 1) / len;
+  if (gm.rows < 1) gm.rows = 1;
+  return gm;
+}
 constexpr int TILE_ROWS_MIN = 64;      // smallest row-tile height any grouped GEMM uses (sizes the tile map)
 
 // ---------------------------------------------------------------- device side

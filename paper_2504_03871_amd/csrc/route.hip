@@ -4,6 +4,7 @@
 // stored fp32 logits and the softmax over the selected ones.
 // Backward: softmax-over-selected backward, dWr = x^T dlogits, dx += dlogits Wr^T.
 #include "common.h"
+#include <type_traits>
 
 namespace moe {
 
@@ -286,16 +287,9 @@ __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
     // MFMAs use, across the K blocks; the token rows of the next K block are loaded one block ahead.
     constexpr int PF = 4;
     static_assert(NET % PF == 0, "unit nt of any K block sits in buffer nt % PF");
-    // The blocks of an XCD would all ask its L2 for the same unit at the same time (one or two channels
-    // serving 32 compute units); every block therefore starts its walk over the K blocks at another one.
     rt_bf16x8 a[TT][4], an[TT][4], b[PF][8];
     const int n_it = wave < nkb ? (nkb - wave + NW - 1) / NW : 0;   // K blocks wave, wave + NW, ... of this wave
-    const int rot = n_it > 0 ? (int)(blockIdx.x % n_it) : 0;
-    auto kb_of = [&](int it) {
-      int j = it + rot;
-      if (j >= n_it) j -= n_it;
-      return wave + NW * j;
-    };
+    auto kb_of = [&](int it) { return wave + NW * it; };
     if (n_it > 0) {
       load_a(a, kb_of(0));
 #pragma unroll
@@ -496,6 +490,129 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_dense_kernel(
     }
 }
 
+// Gate weight gradient on the matrix cores (bf16 x, more than 16 experts, where the kernel above is bound by its
+// fp32 multiply-adds: E of them per token and column for k non-zeros).  dWr^T[e][c] = sum_t d_logits[t][e] x[t][c]
+// is an MFMA with experts as M, columns as N and tokens as K.  Both operands have K (tokens) as the slow index in
+// memory, so the tiles of a K step of 32 tokens lie in LDS as [token][column] and [token][expert] and the
+// fragments come from transposing LDS reads.  d_logits is fp32 and enters as two bf16 terms (hi + lo, about 16
+// mantissa bits), like the gate weight in the forward kernel.  LDS rows are 256 bytes or longer; their 64-byte
+// granules are XOR-swizzled with token % 4 and the 32-byte halves with (token / 8) % 2, which spreads the four
+// token rows of one transposing read, and two reads eight rows apart, over the banks.
+// A block: 128 columns, a slice of tokens, up to 128 experts (NET tiles of 16; more experts: gridDim.z blocks,
+// which keeps the accumulators at 64 registers and several blocks on a compute unit); a wave: 32 of the
+// columns.  Global loads of the next K step are in flight while the MFMAs of this one run.
+typedef short rt_s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int rt_ks_mask(int krow) { return ((krow & 3) << 6) | (((krow >> 3) & 1) << 5); }
+// the eight K values of a lane (column l % 16 of a 16-column tile, K rows 8 (l / 16) .. + 7): two transposing
+// reads of four K rows each; lane s of a 16-lane block passes the address of (K row s / 4, columns 4 (s % 4) .. + 3)
+__device__ __forceinline__ rt_bf16x8 rt_read_tr(const char* p, int row_bytes) {
+  typedef __attribute__((address_space(3))) rt_s16x4 lds_v;
+  union { struct { rt_s16x4 a, b; } q; rt_bf16x8 v; } u;
+  u.q.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v*)(p));
+  u.q.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v*)(p + 4 * row_bytes));
+  return u.v;
+}
+template <int NET>
+__global__ __launch_bounds__(256) void route_bwd_dwr_mfma_kernel(
+    const bf16* __restrict__ x, const float* __restrict__ d_logits, float* __restrict__ partials, int Tn, int d, int E,
+    int slice_tokens) {
+  constexpr int CB = ROUTE_BWD_MFMA_COLS, KS = ROUTE_BWD_MFMA_KSTEP, EP = NET * 16;
+  constexpr int XB = CB * 2;                      // bytes per token row of the x tile
+  constexpr int PB = (EP < 128 ? 128 : EP) * 2;   // bytes per token row of a d_logits plane
+  constexpr int NP = KS * EP / 2 / 256;           // pairs of adjacent experts per thread and K step
+  static_assert(CB == 128 && KS == 32 && NP >= 1, "256 threads: 16 column groups x 16 token rows, twice");
+  extern __shared__ __align__(16) char dwr_smem[];
+  char* xs = dwr_smem;
+  char* ph = dwr_smem + KS * XB;
+  char* pl = ph + KS * PB;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c0 = blockIdx.x * CB, t_begin = blockIdx.y * slice_tokens, t_end = min(Tn, t_begin + slice_tokens);
+  const int e_base = blockIdx.z * EP;
+  const int nsteps = (t_end - t_begin + KS - 1) / KS;
+
+  uint4 xr[2];
+  float dr[NP][2];
+  auto fetch = [&](int step) {   // global -> registers; tokens past the slice or the batch: x of the last token, d_logits 0
+    const int t0 = t_begin + step * KS;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int t = min(t0 + (tid >> 4) + h * 16, Tn - 1), col = c0 + (tid & 15) * 8;
+      xr[h] = col < d ? *reinterpret_cast<const uint4*>(x + (size_t)t * d + col) : uint4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int i = tid + 256 * j, t = t0 + i / (EP / 2), e = e_base + (i % (EP / 2)) * 2;
+      const float* row = d_logits + (size_t)min(t, Tn - 1) * E;
+      dr[j][0] = (t < t_end && e < E) ? row[e] : 0.f;
+      dr[j][1] = (t < t_end && e + 1 < E) ? row[e + 1] : 0.f;
+    }
+  };
+  auto stash = [&]() {           // registers -> LDS, d_logits split into its two bf16 terms
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int r = (tid >> 4) + h * 16;
+      *reinterpret_cast<uint4*>(xs + r * XB + (((tid & 15) * 16) ^ rt_ks_mask(r))) = xr[h];
+    }
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int i = tid + 256 * j, r = i / (EP / 2), e = (i % (EP / 2)) * 2;
+      const uint32_t h0 = f32_to_bf16_bits(dr[j][0]), h1 = f32_to_bf16_bits(dr[j][1]);
+      const uint32_t l0 = f32_to_bf16_bits(dr[j][0] - bf16_bits_to_f32(h0)), l1 = f32_to_bf16_bits(dr[j][1] - bf16_bits_to_f32(h1));
+      const int off = r * PB + ((e * 2) ^ rt_ks_mask(r));
+      *reinterpret_cast<uint32_t*>(ph + off) = h0 | (h1 << 16);
+      *reinterpret_cast<uint32_t*>(pl + off) = l0 | (l1 << 16);
+    }
+  };
+
+  rt_f32x4 acc[NET][2];
+#pragma unroll
+  for (int nt = 0; nt < NET; ++nt)
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) acc[nt][ct] = rt_f32x4{0.f, 0.f, 0.f, 0.f};
+  const int s16 = lane & 15, kgrp = lane >> 4;
+  const int krow = kgrp * 8 + (s16 >> 2), mask = rt_ks_mask(krow), sub = 8 * (s16 & 3);   // this lane's piece of a transposing read
+  fetch(0);
+  for (int step = 0; step < nsteps; ++step) {
+    stash();
+    __syncthreads();
+    if (step + 1 < nsteps) fetch(step + 1);
+    rt_bf16x8 bx[2];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) bx[ct] = rt_read_tr(xs + krow * XB + (((wave * 32 + ct * 16) * 2) ^ mask) + sub, XB);
+#pragma unroll
+    for (int nt = 0; nt < NET; ++nt) {
+      const int off = krow * PB + ((nt * 32) ^ mask) + sub;
+      const rt_bf16x8 hi = rt_read_tr(ph + off, PB), lo = rt_read_tr(pl + off, PB);
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) acc[nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, bx[ct], acc[nt][ct], 0, 0, 0);
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) acc[nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, bx[ct], acc[nt][ct], 0, 0, 0);
+    }
+    __syncthreads();   // every wave is done with the tiles before the next K step overwrites them
+  }
+  // accumulator register v of lane l: expert 4 (l / 16) + v of the tile, column l % 16
+  float* out = partials + (size_t)blockIdx.y * E * d;
+#pragma unroll
+  for (int nt = 0; nt < NET; ++nt)
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int e = e_base + nt * 16 + kgrp * 4 + v, col = c0 + wave * 32 + ct * 16 + s16;
+        if (e < E && col < d) out[(size_t)e * d + col] = acc[nt][ct][v];
+      }
+}
+template <int NET>
+static int launch_dwr_mfma(const moe_cfg* c, const void* x, const float* d_logits, float* partials, hipStream_t s) {
+  const RouteBwdMfmaGeom gm = route_bwd_mfma_geom(c->T, c->d_model, c->E);
+  constexpr int EP = NET * 16, PB = (EP < 128 ? 128 : EP) * 2;
+  static_assert(EP <= ROUTE_BWD_MFMA_EXPERTS, "a block along gridDim.z covers ROUTE_BWD_MFMA_EXPERTS experts");
+  const size_t lds = (size_t)ROUTE_BWD_MFMA_KSTEP * (ROUTE_BWD_MFMA_COLS * 2 + 2 * PB);
+  route_bwd_dwr_mfma_kernel<NET><<<dim3(gm.col_blocks, gm.rows, gm.expert_blocks), 256, lds, s>>>((const bf16*)x, d_logits, partials, c->T,
+                                                                              c->d_model, c->E, gm.slice_tokens);
+  return launch_status();
+}
+
 // dWr = sum over the rows of partial sums, in a fixed order (deterministic).  A block owns 64 adjacent
 // elements of a row of partial sums; its four waves take the rows r = w, w+4, ... (each a coalesced
 // 256-byte read), and the four wave sums are added in wave order.  The rows are laid out [E][d], dWr itself [d][E].
@@ -586,6 +703,19 @@ static int route_bwd_typed(const moe_cfg* c, const void* x, const float* Wr, con
   route_bwd_dx_kernel<T><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (T*)dx, c->T, c->d_model, c->E, c->k);
   if ((rc = launch_status()) != MOE_OK) return rc;
   if (dWr == nullptr) return MOE_OK;
+  if constexpr (std::is_same<T, bf16>::value) {
+    if (route_bwd_uses_mfma(1, c->E)) {
+      switch (route_expert_tiles(c->E)) {
+        case 2: rc = launch_dwr_mfma<2>(c, x, d_logits, partials, s); break;
+        case 4: rc = launch_dwr_mfma<4>(c, x, d_logits, partials, s); break;
+        default: rc = launch_dwr_mfma<8>(c, x, d_logits, partials, s); break;   // 128 experts per block
+      }
+      if (rc != MOE_OK) return rc;
+      route_bwd_reduce_kernel<<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E,
+                                                          route_bwd_mfma_geom(c->T, c->d_model, c->E).rows, accumulate);
+      return launch_status();
+    }
+  }
   const RouteBwdGeom gm = route_bwd_geom(c->T, c->d_model, (int)sizeof(T), c->E);
   const int eb = c->E <= 4 ? 4 : (c->E <= 8 ? 8 : 16);
   const dim3 dgrid(gm.col_blocks, gm.row_blocks, (c->E + eb - 1) / eb);

@@ -39,6 +39,8 @@ CASES = {
     # two and four expert tiles in the matrix-core gate kernel, a token count that is not a multiple of 32
     "e48_k4": W["cfg1"].scaled(T=333, d=192, f=128, E=48, k=4),
     "e100_k6": W["cfg1"].scaled(T=77, d=128, f=64, E=100, k=6),
+    # the matrix-core gate weight gradient: a last column block of 64, a last K step of 11 tokens, three expert tiles
+    "e40_d320": W["cfg1"].scaled(T=203, d=320, f=128, E=40, k=3),
     # d_ff long enough for split-K of the smallest row tiles: only such tiles / a full tile plus a small rest
     "split_k_tiny": W["cfg1"].scaled(T=40, d=128, f=2048, E=4, k=2),
     "split_k_mixed": W["cfg1"].scaled(T=620, d=128, f=2560, E=4, k=2),
