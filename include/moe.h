@@ -127,9 +127,10 @@ MOE_API int moe_saved_bytes(const moe_cfg* cfg, size_t* bytes);
  * descending value, equal values by ascending expert id; slot 0 is the best.
  * topk_w[t][j] = exp(l_j - l_0) / sum_i exp(l_i - l_0) over the k selected logits.
  * bias[E] may be NULL.  logits_out may be NULL only when logits_in is given.
- * bf16: the product runs on the matrix cores with the fp32 gate weight split into two bf16 terms
- * (about 16 mantissa bits); ws (moe_workspace_bytes, device) holds the re-laid-out weight and is
- * required unless logits_in is given.  fp32 and fp16: plain fp32 FMAs on the stored values, ws may be NULL.
+ * bf16 and fp16: the product runs on the matrix cores with the fp32 gate weight split into two bf16 terms
+ * (about 16 mantissa bits; fp16 activations enter exactly, as two bf16 terms each); ws (moe_workspace_bytes,
+ * device) holds the re-laid-out weight and is required unless logits_in is given.  fp32: plain fp32 FMAs on
+ * the stored values, ws may be NULL.
  */
 MOE_API int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* bias,
               const float* logits_in, float* logits_out, int32_t* topk_idx, float* topk_w,

@@ -35,7 +35,7 @@ WsLayout ws_layout(const moe_cfg* c) {
   w.tile_map = off;
   off += align_up(tile_map_bytes(max_row_tiles((int)A, c->E, TILE_ROWS_MIN), c->E), 256);
   w.route_partials = off;
-  const size_t partial_rows = route_bwd_uses_mfma(c->dtype == MOE_DTYPE_BF16, c->E)
+  const size_t partial_rows = route_bwd_uses_mfma(c->dtype != MOE_DTYPE_F32, c->E)
                                   ? (size_t)route_bwd_mfma_geom(c->T, c->d_model, c->E).rows
                                   : (size_t)route_bwd_geom(c->T, c->d_model, (int)elt_size(c), c->E).partial_rows;
   off += align_up(partial_rows * c->d_model * c->E * 4, 256);
@@ -257,7 +257,7 @@ int moe_route(const moe_cfg* cfg, const void* x, const float* Wr, const float* b
               float* logits_out, int32_t* topk_idx, float* topk_w, void* ws, size_t ws_bytes, void* stream) {
   CHECK(check_cfg(cfg));
   if (logits_in == nullptr) { REQUIRE(x); REQUIRE(Wr); REQUIRE(logits_out); }
-  if (logits_in == nullptr && cfg->dtype == MOE_DTYPE_BF16) REQUIRE(ws);   // the matrix-core gate (bf16 only)
+  if (logits_in == nullptr && cfg->dtype != MOE_DTYPE_F32) REQUIRE(ws);   // the matrix-core gate (16-bit storage)
   REQUIRE(topk_idx);
   REQUIRE(topk_w);
   ALIGNED(x); ALIGNED(Wr); ALIGNED(bias); ALIGNED(logits_in); ALIGNED(logits_out); ALIGNED(topk_idx); ALIGNED(topk_w);

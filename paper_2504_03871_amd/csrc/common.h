@@ -66,12 +66,12 @@ inline RouteBwdGeom route_bwd_geom(int T, int d, int elt_bytes, int E) {
   gm.partial_rows = gm.row_blocks * gm.slices_per_block;
   return gm;
 }
-// Gate weight gradient on the matrix cores (bf16 inputs, more than 16 experts): a block owns 128 columns of
+// Gate weight gradient on the matrix cores (bf16 or fp16 inputs, more than 16 experts): a block owns 128 columns of
 // x, up to 128 experts and a slice of tokens, a multiple of 32 long, chosen so that the grid is about two
 // blocks per compute unit; every slice writes one row of E x d partial sums.
 constexpr int ROUTE_BWD_MFMA_COLS = 128, ROUTE_BWD_MFMA_KSTEP = 32, ROUTE_BWD_MFMA_EXPERTS = 128;
 struct RouteBwdMfmaGeom { int col_blocks, expert_blocks, slice_tokens, rows; };
-inline bool route_bwd_uses_mfma(int dtype_is_bf16, int E) { return dtype_is_bf16 && E > 16; }
+inline bool route_bwd_uses_mfma(int storage_is_16bit, int E) { return storage_is_16bit && E > 16; }
 inline RouteBwdMfmaGeom route_bwd_mfma_geom(int T, int d, int E) {
   RouteBwdMfmaGeom gm;
   gm.col_blocks = (d + ROUTE_BWD_MFMA_COLS - 1) / ROUTE_BWD_MFMA_COLS;

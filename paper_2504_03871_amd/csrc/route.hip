@@ -239,9 +239,38 @@ __global__ void wr_frag_kernel(const float* __restrict__ Wr, rt_bf16x8* __restri
   wfrag[u] = v;
 }
 
-template <int NET, int TT, int NW>
+// Sixteen bytes of x as bf16 MFMA operands.  bf16 storage: as they are.  fp16 storage: every value (11
+// significant bits) is the exact sum of two bf16 numbers, its first 8 significant bits and the rest (at most 3
+// bits; bf16's exponent range covers fp16's subnormals), so the product with the two-term weight takes four
+// MFMAs instead of two and no fp16 range question (subnormal low-order terms) comes up.
+template <typename T> struct XTerms;
+template <> struct XTerms<bf16> {
+  static constexpr int N = 1;
+  static __device__ __forceinline__ void split(const uint4& raw, rt_bf16x8* out) { out[0] = __builtin_bit_cast(rt_bf16x8, raw); }
+};
+template <> struct XTerms<f16> {
+  static constexpr int N = 2;
+  static __device__ __forceinline__ void split(const uint4& raw, rt_bf16x8* out) {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    uint4 h, l;
+    uint32_t* hp = &h.x;
+    uint32_t* lp = &l.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float f0 = f16_bits_to_f32(w[i] & 0xffffu), f1 = f16_bits_to_f32(w[i] >> 16);
+      const uint32_t h0 = __float_as_uint(f0) & 0xffff0000u, h1 = __float_as_uint(f1) & 0xffff0000u;
+      const float r0 = f0 - __uint_as_float(h0), r1 = f1 - __uint_as_float(h1);   // exact
+      hp[i] = (h0 >> 16) | h1;
+      lp[i] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xffff0000u);
+    }
+    out[0] = __builtin_bit_cast(rt_bf16x8, h);
+    out[1] = __builtin_bit_cast(rt_bf16x8, l);
+  }
+};
+
+template <typename T, int NET, int TT, int NW>
 __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
-    const bf16* __restrict__ x, const rt_bf16x8* __restrict__ wfrag, const float* __restrict__ bias,
+    const T* __restrict__ x, const rt_bf16x8* __restrict__ wfrag, const float* __restrict__ bias,
     float* __restrict__ logits_out, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d, int E, int k) {
   extern __shared__ float part[];   // [NW waves][TOK tokens][LD]; the sum ends up in part[0]
   constexpr int TOK = TT * 16, LD = NET * 16;
@@ -249,7 +278,8 @@ __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tok0 = blockIdx.x * TOK, nkb = (d + 127) / 128;
   const int r = lane & 15, c = lane >> 4;
-  const bf16* xrow[TT];
+  constexpr int XT = XTerms<T>::N;
+  const T* xrow[TT];
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) xrow[tt] = x + (size_t)min(tok0 + tt * 16 + r, Tn - 1) * d + c * 32;   // rows past the batch repeat the last token
   rt_f32x4 acc[TT][NET];
@@ -257,28 +287,35 @@ __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
   for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
     for (int nt = 0; nt < NET; ++nt) acc[tt][nt] = rt_f32x4{0.f, 0.f, 0.f, 0.f};
-  const rt_bf16x8 zero = {};
-  auto load_a = [&](rt_bf16x8 (*dst)[4], int kb) {
+  auto load_a = [&](uint4 (*dst)[4], int kb) {   // raw 16-byte pieces; split into operands once they have arrived
     const bool inb = kb * 128 + c * 32 < d;   // d is a multiple of 64: a lane's 32 elements lie inside the row or past it
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
       for (int s = 0; s < 4; ++s)
-        dst[tt][s] = inb ? *reinterpret_cast<const rt_bf16x8*>(xrow[tt] + (size_t)kb * 128 + s * 8) : zero;
+        dst[tt][s] = inb ? *reinterpret_cast<const uint4*>(xrow[tt] + (size_t)kb * 128 + s * 8) : uint4{0u, 0u, 0u, 0u};
+  };
+  auto split_a = [&](rt_bf16x8 (*dst)[4][XT], uint4 (*raw)[4]) {
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) XTerms<T>::split(raw[tt][s], dst[tt][s]);
   };
   auto load_b = [&](rt_bf16x8* dst, int kb, int nt) {
     const rt_bf16x8* wf = wfrag + ((size_t)(nt * nkb + kb) * 8) * 64 + lane;
 #pragma unroll
     for (int q = 0; q < 8; ++q) dst[q] = wf[q * 64];
   };
-  auto mfmas = [&](rt_bf16x8 (*a)[4], const rt_bf16x8* b, int nt) {
+  auto mfmas = [&](rt_bf16x8 (*a)[4][XT], const rt_bf16x8* b, int nt) {
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-      for (int tt = 0; tt < TT; ++tt) {
-        acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s], b[s * 2], acc[tt][nt], 0, 0, 0);
-        acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s], b[s * 2 + 1], acc[tt][nt], 0, 0, 0);
-      }
+      for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s][xt], b[s * 2], acc[tt][nt], 0, 0, 0);
+          acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt][s][xt], b[s * 2 + 1], acc[tt][nt], 0, 0, 0);
+        }
   };
   if constexpr (NET >= 4) {
     // Many expert tiles: a block streams the whole gate weight (1-2 MB) through its four waves, and a wave
@@ -287,19 +324,21 @@ __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
     // MFMAs use, across the K blocks; the token rows of the next K block are loaded one block ahead.
     constexpr int PF = 4;
     static_assert(NET % PF == 0, "unit nt of any K block sits in buffer nt % PF");
-    rt_bf16x8 a[TT][4], an[TT][4], b[PF][8];
+    uint4 raw[TT][4];
+    rt_bf16x8 a[TT][4][XT], b[PF][8];
     const int n_it = wave < nkb ? (nkb - wave + NW - 1) / NW : 0;   // K blocks wave, wave + NW, ... of this wave
     auto kb_of = [&](int it) { return wave + NW * it; };
     if (n_it > 0) {
-      load_a(a, kb_of(0));
+      load_a(raw, kb_of(0));
 #pragma unroll
       for (int p = 0; p < PF - 1; ++p) load_b(b[p], kb_of(0), p);
+      split_a(a, raw);
     }
     for (int it = 0; it < n_it; ++it) {
       const int kb = kb_of(it);
       const bool more = it + 1 < n_it;
       const int kbn = more ? kb_of(it + 1) : kb;
-      if (more) load_a(an, kbn);
+      if (more) load_a(raw, kbn);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int nt = 0; nt < NET; ++nt) {
@@ -310,17 +349,14 @@ __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
         mfmas(a, b[nt % PF], nt);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (more) {
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-          for (int s = 0; s < 4; ++s) a[tt][s] = an[tt][s];
-      }
+      if (more) split_a(a, raw);
     }
   } else {
     for (int kb = wave; kb < nkb; kb += NW) {
-      rt_bf16x8 a[TT][4];
-      load_a(a, kb);
+      uint4 raw[TT][4];
+      rt_bf16x8 a[TT][4][XT];
+      load_a(raw, kb);
+      split_a(a, raw);
 #pragma unroll
       for (int nt = 0; nt < NET; ++nt) {
         rt_bf16x8 b[8];
@@ -512,18 +548,19 @@ __device__ __forceinline__ rt_bf16x8 rt_read_tr(const char* p, int row_bytes) {
   u.q.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v*)(p + 4 * row_bytes));
   return u.v;
 }
-template <int NET>
+template <typename T, int NET>
 __global__ __launch_bounds__(256) void route_bwd_dwr_mfma_kernel(
-    const bf16* __restrict__ x, const float* __restrict__ d_logits, float* __restrict__ partials, int Tn, int d, int E,
+    const T* __restrict__ x, const float* __restrict__ d_logits, float* __restrict__ partials, int Tn, int d, int E,
     int slice_tokens) {
   constexpr int CB = ROUTE_BWD_MFMA_COLS, KS = ROUTE_BWD_MFMA_KSTEP, EP = NET * 16;
   constexpr int XB = CB * 2;                      // bytes per token row of the x tile
   constexpr int PB = (EP < 128 ? 128 : EP) * 2;   // bytes per token row of a d_logits plane
   constexpr int NP = KS * EP / 2 / 256;           // pairs of adjacent experts per thread and K step
   static_assert(CB == 128 && KS == 32 && NP >= 1, "256 threads: 16 column groups x 16 token rows, twice");
+  constexpr int XT = XTerms<T>::N;                // x tiles: one (bf16) or two (the bf16 terms of fp16 values)
   extern __shared__ __align__(16) char dwr_smem[];
   char* xs = dwr_smem;
-  char* ph = dwr_smem + KS * XB;
+  char* ph = dwr_smem + XT * KS * XB;
   char* pl = ph + KS * PB;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c0 = blockIdx.x * CB, t_begin = blockIdx.y * slice_tokens, t_end = min(Tn, t_begin + slice_tokens);
@@ -551,7 +588,11 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_mfma_kernel(
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int r = (tid >> 4) + h * 16;
-      *reinterpret_cast<uint4*>(xs + r * XB + (((tid & 15) * 16) ^ rt_ks_mask(r))) = xr[h];
+      rt_bf16x8 terms[XT];
+      XTerms<T>::split(xr[h], terms);
+#pragma unroll
+      for (int xt = 0; xt < XT; ++xt)
+        *reinterpret_cast<rt_bf16x8*>(xs + xt * KS * XB + r * XB + (((tid & 15) * 16) ^ rt_ks_mask(r))) = terms[xt];
     }
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
@@ -576,17 +617,23 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_mfma_kernel(
     stash();
     __syncthreads();
     if (step + 1 < nsteps) fetch(step + 1);
-    rt_bf16x8 bx[2];
+    rt_bf16x8 bx[XT][2];
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct) bx[ct] = rt_read_tr(xs + krow * XB + (((wave * 32 + ct * 16) * 2) ^ mask) + sub, XB);
+    for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+        bx[xt][ct] = rt_read_tr(xs + xt * KS * XB + krow * XB + (((wave * 32 + ct * 16) * 2) ^ mask) + sub, XB);
 #pragma unroll
     for (int nt = 0; nt < NET; ++nt) {
       const int off = krow * PB + ((nt * 32) ^ mask) + sub;
       const rt_bf16x8 hi = rt_read_tr(ph + off, PB), lo = rt_read_tr(pl + off, PB);
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) acc[nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, bx[ct], acc[nt][ct], 0, 0, 0);
+      for (int xt = 0; xt < XT; ++xt) {
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) acc[nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, bx[ct], acc[nt][ct], 0, 0, 0);
+        for (int ct = 0; ct < 2; ++ct) acc[nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, bx[xt][ct], acc[nt][ct], 0, 0, 0);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) acc[nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, bx[xt][ct], acc[nt][ct], 0, 0, 0);
+      }
     }
     __syncthreads();   // every wave is done with the tiles before the next K step overwrites them
   }
@@ -602,13 +649,13 @@ __global__ __launch_bounds__(256) void route_bwd_dwr_mfma_kernel(
         if (e < E && col < d) out[(size_t)e * d + col] = acc[nt][ct][v];
       }
 }
-template <int NET>
+template <typename T, int NET>
 static int launch_dwr_mfma(const moe_cfg* c, const void* x, const float* d_logits, float* partials, hipStream_t s) {
   const RouteBwdMfmaGeom gm = route_bwd_mfma_geom(c->T, c->d_model, c->E);
   constexpr int EP = NET * 16, PB = (EP < 128 ? 128 : EP) * 2;
   static_assert(EP <= ROUTE_BWD_MFMA_EXPERTS, "a block along gridDim.z covers ROUTE_BWD_MFMA_EXPERTS experts");
-  const size_t lds = (size_t)ROUTE_BWD_MFMA_KSTEP * (ROUTE_BWD_MFMA_COLS * 2 + 2 * PB);
-  route_bwd_dwr_mfma_kernel<NET><<<dim3(gm.col_blocks, gm.rows, gm.expert_blocks), 256, lds, s>>>((const bf16*)x, d_logits, partials, c->T,
+  const size_t lds = (size_t)ROUTE_BWD_MFMA_KSTEP * (XTerms<T>::N * ROUTE_BWD_MFMA_COLS * 2 + 2 * PB);
+  route_bwd_dwr_mfma_kernel<T, NET><<<dim3(gm.col_blocks, gm.rows, gm.expert_blocks), 256, lds, s>>>((const T*)x, d_logits, partials, c->T,
                                                                               c->d_model, c->E, gm.slice_tokens);
   return launch_status();
 }
@@ -641,7 +688,7 @@ size_t route_wfrag_bytes(int d, int E) {
   return (size_t)route_expert_tiles(E) * ((d + 127) / 128) * 8 * 64 * 16;
 }
 
-template <int NET, int TT, int NW>
+template <typename T, int NET, int TT, int NW>
 static int launch_route_mfma(const moe_cfg* c, const void* x, const float* Wr, const float* bias, float* logits_out,
                              int32_t* idx, float* w, void* wfrag, hipStream_t s) {
   constexpr int TOK = TT * 16;
@@ -650,32 +697,38 @@ static int launch_route_mfma(const moe_cfg* c, const void* x, const float* Wr, c
   int rc = launch_status();
   if (rc != MOE_OK) return rc;
   const size_t lds = (size_t)NW * TOK * NET * 16 * 4;
-  auto kern = route_mfma_kernel<NET, TT, NW>;
+  auto kern = route_mfma_kernel<T, NET, TT, NW>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return set_hip_error(e);
   }
-  kern<<<(c->T + TOK - 1) / TOK, NW * 64, lds, s>>>((const bf16*)x, (const rt_bf16x8*)wfrag, bias, logits_out, idx, w,
+  kern<<<(c->T + TOK - 1) / TOK, NW * 64, lds, s>>>((const T*)x, (const rt_bf16x8*)wfrag, bias, logits_out, idx, w,
                                                  c->T, c->d_model, c->E, c->k);
   return launch_status();
 }
 
 // wfrag: workspace for the gate weight in MFMA operand layout (route_wfrag_bytes), used for bf16 x
+template <typename T>
+static int route_mfma_typed(const moe_cfg* c, const void* x, const float* Wr, const float* bias, float* logits_out,
+                            int32_t* idx, float* w, void* wfrag, hipStream_t s) {
+  // long rows and few expert tiles: eight waves and 64 tokens per block; else four waves and 32 tokens
+  const bool wide = c->d_model >= 2048;
+  switch (route_expert_tiles(c->E)) {
+    case 1: return wide ? launch_route_mfma<T, 1, 4, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
+                        : launch_route_mfma<T, 1, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    case 2: return wide ? launch_route_mfma<T, 2, 4, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
+                        : launch_route_mfma<T, 2, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    case 4: return launch_route_mfma<T, 4, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    case 8: return launch_route_mfma<T, 8, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+    default: return launch_route_mfma<T, 16, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
+  }
+}
+
 int launch_route(const moe_cfg* c, const void* x, const float* Wr, const float* bias, const float* logits_in,
                  float* logits_out, int32_t* idx, float* w, void* wfrag, hipStream_t s) {
-  if (c->dtype == MOE_DTYPE_BF16 && logits_in == nullptr) {
-    // long rows and few expert tiles: eight waves and 64 tokens per block; else four waves and 32 tokens
-    const bool wide = c->d_model >= 2048;
-    switch (route_expert_tiles(c->E)) {
-      case 1: return wide ? launch_route_mfma<1, 4, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
-                          : launch_route_mfma<1, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-      case 2: return wide ? launch_route_mfma<2, 4, 8>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
-                          : launch_route_mfma<2, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-      case 4: return launch_route_mfma<4, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-      case 8: return launch_route_mfma<8, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-      default: return launch_route_mfma<16, 2, 4>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
-    }
-  }
+  if ((c->dtype == MOE_DTYPE_BF16 || c->dtype == MOE_DTYPE_F16) && logits_in == nullptr)
+    return c->dtype == MOE_DTYPE_BF16 ? route_mfma_typed<bf16>(c, x, Wr, bias, logits_out, idx, w, wfrag, s)
+                                      : route_mfma_typed<f16>(c, x, Wr, bias, logits_out, idx, w, wfrag, s);
   const RouteGeom gm = route_geom(c->E);
   const int grid = (c->T + gm.tok - 1) / gm.tok;
   const size_t es = elt_size(c);
@@ -703,12 +756,12 @@ static int route_bwd_typed(const moe_cfg* c, const void* x, const float* Wr, con
   route_bwd_dx_kernel<T><<<grid, 256, 0, s>>>(WrT, idx, w, dw, d_logits, (T*)dx, c->T, c->d_model, c->E, c->k);
   if ((rc = launch_status()) != MOE_OK) return rc;
   if (dWr == nullptr) return MOE_OK;
-  if constexpr (std::is_same<T, bf16>::value) {
+  if constexpr (!std::is_same<T, float>::value) {
     if (route_bwd_uses_mfma(1, c->E)) {
       switch (route_expert_tiles(c->E)) {
-        case 2: rc = launch_dwr_mfma<2>(c, x, d_logits, partials, s); break;
-        case 4: rc = launch_dwr_mfma<4>(c, x, d_logits, partials, s); break;
-        default: rc = launch_dwr_mfma<8>(c, x, d_logits, partials, s); break;   // 128 experts per block
+        case 2: rc = launch_dwr_mfma<T, 2>(c, x, d_logits, partials, s); break;
+        case 4: rc = launch_dwr_mfma<T, 4>(c, x, d_logits, partials, s); break;
+        default: rc = launch_dwr_mfma<T, 8>(c, x, d_logits, partials, s); break;   // 128 experts per block
       }
       if (rc != MOE_OK) return rc;
       route_bwd_reduce_kernel<<<(n + 63) / 64, 256, 0, s>>>(partials, dWr, c->d_model, c->E,

@@ -68,6 +68,9 @@ def test_pointer_validation_happens_before_any_launch():
     with pytest.raises(B.MoeError) as ei:
         B.moe_route(cfg, P, P, None, None, P, P, P, ws=None, stream=s)      # bf16 gate needs the workspace
     assert ei.value.code == -1
+    with pytest.raises(B.MoeError) as ei:                                       # and so does the fp16 gate
+        B.moe_route(B.make_cfg(8, 64, 128, 4, 2, dtype=B.DTYPE_F16), P, P, None, None, P, P, P, ws=None, stream=s)
+    assert ei.value.code == -1
     with pytest.raises(B.MoeError) as ei:
         B.moe_dispatch(cfg, P, P, P, None, P, P, P, P, P, P, P, stream=s)      # only one slice bound
     assert ei.value.code == -4

@@ -92,10 +92,10 @@ def run_case(w: S.Workload):
     if len(diff) and w.k < w.E:
         # A flip needs two logits closer than the error of the GPU's two dot products.  With
         # S = max_e sum_i |x_i Wr_ie|: fp32 accumulation of d terms in some order leaves about
-        # sqrt(d) * 2^-24 * S (random-walk estimate; the factor 8 is the margin); the bf16 gate also
-        # keeps the weight as two bf16 terms, i.e. to 2^-17 relative, which adds 2^-17 * S per logit.
+        # sqrt(d) * 2^-24 * S (random-walk estimate; the factor 8 is the margin); the bf16 and fp16 gates also
+        # keep the weight as two bf16 terms, i.e. to 2^-17 relative, which adds 2^-17 * S per logit.
         acc = 8 * 2.0 ** -24 * np.sqrt(w.d)
-        rep_w = 2 * 2.0 ** -17 if w.dtype == S.DT_BF16 else 0.0    # fp32 and fp16 inputs: plain fp32 FMAs on the fp32 weight
+        rep_w = 2 * 2.0 ** -17 if w.dtype != S.DT_F32 else 0.0    # fp32 inputs: plain fp32 FMAs on the fp32 weight
         mag = np.abs(inp["x"][diff].astype(np.float64)) @ np.abs(inp["Wr"].astype(np.float64))
         srt = np.sort(ref["logits"][diff], axis=1)[:, ::-1]
         gaps = np.abs(np.diff(srt[:, :w.k + 1], axis=1)).min(axis=1)
