@@ -102,22 +102,43 @@ __global__ __launch_bounds__(TM_THREADS) void tile_map_kernel(const int32_t* __r
   }
   __syncthreads();
   if (e < E) {
-    const int base = s_base[e], nfull = s_full[e];
-    for (int i = part; i < nfull; i += 4) {   // the expert's four threads share its full tiles
-      RowTile t;
-      t.e = e;
-      t.row0 = base + i * tile_rows;
-      t.nrows = tile_rows;
-      t.pad = 0;
-      tiles[s_start[e] + i] = t;
-    }
-    if (part == 0 && s_rem[e] > 0) {   // position among the partial tiles: more rows first, ties by expert id
-      RowTile t;
-      t.e = e;
-      t.row0 = base + nfull * tile_rows;
-      t.nrows = s_rem[e];
-      t.pad = 0;
-      tiles[s_major ? s_start[e] + nfull : s_nfull + rank_rem] = t;
+    const int base = s_base[e], nfull = s_full[e], rem = s_rem[e];
+    if (s_major) {
+      // Expert-major list: an expert's rows are cut into its ceil(len / tile_rows) tiles evenly (in steps of 64
+      // rows, two MFMA row bands) instead of full tiles plus a remainder.  A remainder of a few rows costs a
+      // block the whole weight panel for next to no arithmetic; two tiles of 140 rows cost less than one of
+      // 256 and one of 24, and every output row is computed the same way wherever its tile starts.
+      const int len = nfull * tile_rows + rem, ntile = nfull + (rem > 0);
+      int per = tile_rows;
+      if (ntile > 1) {
+        per = min(tile_rows, ((len + ntile - 1) / ntile + 63) & ~63);
+        if ((ntile - 1) * per >= len) per = tile_rows;   // many tiles: the rounding would leave the last one empty
+      }
+      for (int i = part; i < ntile; i += 4) {   // the expert's four threads share its tiles
+        RowTile t;
+        t.e = e;
+        t.row0 = base + i * per;
+        t.nrows = min(per, len - i * per);
+        t.pad = 0;
+        tiles[s_start[e] + i] = t;
+      }
+    } else {
+      for (int i = part; i < nfull; i += 4) {
+        RowTile t;
+        t.e = e;
+        t.row0 = base + i * tile_rows;
+        t.nrows = tile_rows;
+        t.pad = 0;
+        tiles[s_start[e] + i] = t;
+      }
+      if (part == 0 && rem > 0) {   // position among the partial tiles: more rows first, ties by expert id
+        RowTile t;
+        t.e = e;
+        t.row0 = base + nfull * tile_rows;
+        t.nrows = rem;
+        t.pad = 0;
+        tiles[s_nfull + rank_rem] = t;
+      }
     }
   }
 }
