@@ -8,7 +8,7 @@
 
 namespace moe {
 
-// Forward kernel.  A block of 256 threads owns TOK tokens.  Thread (token, k part, expert group) keeps
+// Forward kernel for fp32 inputs and for routing from given logits.  A block of 256 threads owns TOK tokens.  Thread (token, k part, expert group) keeps
 // the dot products of its token with four experts over its share of every d chunk, so x Wr needs no
 // cross-lane reduction beyond adding the k parts (adjacent lanes) at the end.  x chunks [TOK][DC] and
 // Wr chunks [DC][E4] are staged through LDS (coalesced global loads, prefetched into registers one
@@ -201,8 +201,9 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
   route_select(s_logit, E, tl, tid & (G - 1), G, tl < ntok, tok0 + tl, E, k, topk_idx, topk_w);
 }
 
-// ---------------------------------------------------------------- forward on the matrix cores (bf16 x)
-// logits = x Wr as a [T x d] x [d x E] product on v_mfma_f32_16x16x32_bf16.  x is bf16 already; the fp32
+// ---------------------------------------------------------------- forward on the matrix cores (bf16 or fp16 x)
+// logits = x Wr as a [T x d] x [d x E] product on v_mfma_f32_16x16x32_bf16.  x is bf16 already (fp16: the exact
+// sum of two bf16 terms, XTerms below); the fp32
 // gate weight is split into two bf16 terms, w = hi + lo with hi = bf16(w), lo = bf16(w - hi), and both
 // products are accumulated in fp32, which keeps the weight to about 16 mantissa bits (relative error
 // 2^-17 per product, far below the bf16 resolution of x itself).
