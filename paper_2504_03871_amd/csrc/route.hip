@@ -260,7 +260,9 @@ template <> struct XTerms<f16> {
     for (int i = 0; i < 4; ++i) {
       const float f0 = f16_bits_to_f32(w[i] & 0xffffu), f1 = f16_bits_to_f32(w[i] >> 16);
       const uint32_t h0 = __float_as_uint(f0) & 0xffff0000u, h1 = __float_as_uint(f1) & 0xffff0000u;
-      const float r0 = f0 - __uint_as_float(h0), r1 = f1 - __uint_as_float(h1);   // exact
+      // exact; an infinity (or NaN) stays in the first term alone instead of making inf - inf
+      const float r0 = (h0 & 0x7f800000u) == 0x7f800000u ? 0.f : f0 - __uint_as_float(h0);
+      const float r1 = (h1 & 0x7f800000u) == 0x7f800000u ? 0.f : f1 - __uint_as_float(h1);
       hp[i] = (h0 >> 16) | h1;
       lp[i] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xffff0000u);
     }
