@@ -176,3 +176,9 @@ def sampled_check(w: S.Workload, rows_per_expert=64, cols_per_expert=16, n_token
 @pytest.mark.parametrize("name", ["cfg2", "cfg4", "cfg4z", "cfg3", "cfg5", "cfg6"])
 def test_sampled_full_size(name):
     sampled_check(S.WORKLOADS[name])
+
+
+@pytest.mark.timeout(900)
+def test_sampled_full_size_fp16_many_experts():
+    """cfg6 in fp16 storage: the matrix-core gate kernels with fp16 activations split into bf16 pairs, 256 experts."""
+    sampled_check(S.WORKLOADS["cfg6"].scaled(dtype=S.DT_F16))
