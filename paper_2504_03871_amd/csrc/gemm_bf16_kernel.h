@@ -172,7 +172,12 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
                                           const u32x2& sv1, const u32x2& sv2, const float* tab) {
   typedef Half16<ST> H;
   auto st = [](void* base, size_t i, float v0, float v1, float v2, float v3) {
-    *reinterpret_cast<u32x2*>(reinterpret_cast<ST*>(base) + i) = u32x2{H::pack2(v0, v1), H::pack2(v2, v3)};
+    // outputs are written once and read by a later launch: streaming stores keep them from displacing operand
+    // panels in the L2 (measured: dH -1.3 %, the GELU workloads -0.4 to -1.5 % per step; the SwiGLU forward with
+    // its three stores per element is 1 % faster with plain ones)
+    const u32x2 v = u32x2{H::pack2(v0, v1), H::pack2(v2, v3)};
+    u32x2* p = reinterpret_cast<u32x2*>(reinterpret_cast<ST*>(base) + i);
+    if constexpr (EPI == EPI_SWIGLU_FWD) *p = v; else __builtin_nontemporal_store(v, p);
   };
   auto ld = [](const u32x2& r, float* f) {   // four saved 16-bit values, loaded by the caller ahead of time
     f[0] = H::lo(r.x); f[1] = H::hi(r.x);
@@ -183,7 +188,7 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& g, size_t idx, const f
   } else if constexpr (EPI == EPI_GELU_FWD) {
     // h = a Phi(v), v = the pre-activation as stored: GELU of the saved tensor; Phi looked up (bf16) or evaluated (fp16)
     const uint32_t p0 = H::pack2(a[0], a[1]), p1 = H::pack2(a[2], a[3]);
-    if (g.C != nullptr) *reinterpret_cast<u32x2*>(reinterpret_cast<ST*>(g.C) + idx) = u32x2{p0, p1};   // NULL: only H is kept
+    if (g.C != nullptr) __builtin_nontemporal_store(u32x2{p0, p1}, reinterpret_cast<u32x2*>(reinterpret_cast<ST*>(g.C) + idx));   // NULL: only H is kept
     if constexpr (H::GELU_TABLE) {
       st(g.C2, idx, a[0] * gelu_tab_lookup(tab, p0 & 0xffffu), a[1] * gelu_tab_lookup(tab, p0 >> 16),
          a[2] * gelu_tab_lookup(tab, p1 & 0xffffu), a[3] * gelu_tab_lookup(tab, p1 >> 16));
