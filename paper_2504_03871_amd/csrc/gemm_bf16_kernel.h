@@ -553,8 +553,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
         const int m = (band * WGM + wm) * 32 + p * RPP + rr, n = wn * C + c4 * 4;
         const bool ok = m < mvalid && n < nvalid;
         const size_t idx = (size_t)(row0 + (ok ? m : 0)) * g.N + n0 + (ok ? n : 0);
-        d1[p] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S1) + idx);
-        if constexpr (NEED_S2) d2[p] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S2) + idx);
+        d1[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S1) + idx));
+        if constexpr (NEED_S2) d2[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16*>(g.S2) + idx));
       }
     };
     if constexpr (NEED_S1) load_saved(0, s1[0], s2[0]);
@@ -593,7 +593,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs& g, const int vb, 
             *reinterpret_cast<f32x4*>(g.split_ws + (((size_t)split_tile * SPLIT_K + ksplit) * SPLIT_ROWS + m) * g.N + n0 + n) = va[p];
           } else if constexpr (MODE == MODE_TN) {   // fp32 weight gradient of expert e, 16 bytes per lane
             f32x4* c = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + ((size_t)e * g.M + m0 + m) * g.N + n0 + n);
-            *c = g.accumulate ? *c + va[p] : va[p];
+            if (g.accumulate) *c = *c + va[p]; else __builtin_nontemporal_store(va[p], c);
           } else {
             epilogue4<ST, EPI>(g, (size_t)(row0 + m) * g.N + n0 + n, va[p], vb[DUAL ? p : 0],
                            s1[NEED_S1 ? i & 1 : 0][NEED_S1 ? p : 0], s2[NEED_S2 ? i & 1 : 0][NEED_S2 ? p : 0], tab_lds);
