@@ -302,3 +302,24 @@ def test_random_workloads():
                         partial=rnd.random() < 0.4, zipf_s=rnd.choice([0.0, 0.8, 1.3]), dtype=dt)
         print(f"\n[random {it}] {w}", flush=True)
         run_case(w)
+
+
+def test_random_wide_row_workloads():
+    """Twelve more seeded random workloads with long token rows (1024 to 4096 elements, one of them not a multiple
+    of 128) and 16-bit storage: the eight-wave gate kernels, the long-row forms of gather and combine, the last column
+    block of the matrix-core gate weight gradient."""
+    import random
+    rnd = random.Random(3871)
+    for it in range(12):
+        dt = rnd.choice([S.DT_BF16, S.DT_F16])
+        act = rnd.choice([S.ACT_GELU, S.ACT_SWIGLU])
+        E = rnd.choice([2, 8, 16, 17, 40, 64, 130, 200])
+        k = rnd.randint(1, min(E, 8))
+        d = rnd.choice([1024, 2048, 2112, 4096])
+        f = 64 * rnd.randint(1, 3)
+        T = rnd.choice([1, 33, 257, 600, 1025])
+        base = W["cfg3"] if act == S.ACT_SWIGLU else W["cfg1"]
+        w = base.scaled(T=T, d=d, f=f, E=E, k=k, capacity_factor=rnd.choice([0.0, 0.0, 0.8]),
+                        partial=rnd.random() < 0.4, zipf_s=rnd.choice([0.0, 1.0]), dtype=dt)
+        print(f"\n[random wide {it}] {w}", flush=True)
+        run_case(w)
