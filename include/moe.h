@@ -251,6 +251,8 @@ MOE_API int moe_expert_ffn_bwd(const moe_cfg* cfg, const void* dy_perm, const vo
  * weight gradient (d_logits is always written): the two parts are independent, so a caller can run the
  * weight-gradient part on a second stream next to the expert backward, with a workspace and a d_logits
  * buffer of its own, and add to dx once the gradient through the experts has been written.
+ * Sums are fp32 in a fixed order.  bf16 / fp16 storage with more than 16 experts: dWr runs on the matrix cores
+ * with d_logits entering as two bf16 terms (about 16 mantissa bits) and x exactly; otherwise plain fp32 FMAs.
  */
 MOE_API int moe_route_bwd(const moe_cfg* cfg, const void* x, const float* Wr, const int32_t* topk_idx,
                   const float* topk_w, const float* d_topk_w,
