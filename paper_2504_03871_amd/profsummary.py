@@ -101,6 +101,7 @@ def main():
     ap.add_argument("--clock-log", help="output of bench.py --clock-probe: writes <workload>_shader_clock.md")
     ap.add_argument("--mfma-log", help="output of bench.py --mfma-loop: writes mfma_loop_rates.md")
     ap.add_argument("--out", default="profiles")
+    ap.add_argument("--f16", action="store_true", help="the runs were made with bench.py --f16: files are named <workload>_f16_...")
     a = ap.parse_args()
     w = a.workload
     title = a.title or w
@@ -109,7 +110,10 @@ def main():
         line = [x for x in open(a.bench_json) if x.startswith("{")][-1]
         bench = json.loads(line)
         title = bench["config"]["workload"]
-    bench_cmd = f"python3 bench.py --workload {w} --also none --no-cpu-baseline"
+    bench_cmd = f"python3 bench.py --workload {w} --also none --no-cpu-baseline" + (" --f16" if a.f16 else "")
+    tag = w + ("_f16" if a.f16 else "")   # file name stem
+    if a.f16:
+        title += " (fp16 storage)"
 
     if a.mfma_log:
         j = json.loads([x for x in open(a.mfma_log) if x.startswith("{")][-1])
@@ -154,7 +158,7 @@ def main():
                "The clock depends on the instruction mix.  With the 32 x 32 x 16 MFMA the same probe read a median of 1656 MHz",
                "under the same workload; a loop of nothing but MFMAs (matrix cores busy 99 % of cycles by the SQ counters in",
                "both cases) runs at 1880 TFLOP/s with 32 x 32 x 16 and at 2140 TFLOP/s with 16 x 16 x 32."]
-        open(os.path.join(a.out, f"{w}_shader_clock.md"), "w").write("\n".join(out) + "\n")
+        open(os.path.join(a.out, f"{tag}_shader_clock.md"), "w").write("\n".join(out) + "\n")
 
     if a.trace:
         rows = list(csv.DictReader(open(find_csv(a.trace, "kernel_stats.csv"))))
@@ -177,9 +181,9 @@ def main():
             out += ["", f"bench.py line of the same run: {bench['ms_per_step']} ms/step, {bench['value']:.0f} tokens/s; dominant kernel "
                     f"{rf['kernel']}: {rf['us_per_launch']} us per launch by HIP events in the timed region (median "
                     f"{rf['us_per_launch_median']}, min {rf['us_per_launch_min']}), {rf['achieved']} TFLOP/s "
-                    f"({rf['frac']*100:.1f} % of the {rf['peak']:.0f} TFLOP/s bf16 peak); all GEMM launches of a step: "
+                    f"({rf['frac']*100:.1f} % of the {rf['peak']:.0f} TFLOP/s bf16 / fp16 peak); all GEMM launches of a step: "
                     f"{rf['all_gemms']['us_per_step']} us, {rf['all_gemms']['TFLOPs']} TFLOP/s ({rf['all_gemms']['frac']*100:.1f} %)."]
-        open(os.path.join(a.out, f"{w}_kernel_trace_stats.md"), "w").write("\n".join(out) + "\n")
+        open(os.path.join(a.out, f"{tag}_kernel_trace_stats.md"), "w").write("\n".join(out) + "\n")
 
     if a.fetch and a.write:
         pf = per_kernel(find_csv(a.fetch, "counter_collection.csv"))
@@ -221,7 +225,7 @@ def main():
                 lines.append(f"| {role} | {rd/1024:.1f} | {wr/1024:.1f} | {tot} | {desc} |")
         lines += ["", "Reads above the algorithmic figure are operand panels fetched again by tiles whose L2 (4 MB per XCD) no longer",
                   "holds them; the counter sits between the L2s and the memory-side cache, so part of it never reaches HBM."]
-        open(os.path.join(a.out, f"{w}_gemm_hbm_traffic.md"), "w").write("\n".join(lines) + "\n")
+        open(os.path.join(a.out, f"{tag}_gemm_hbm_traffic.md"), "w").write("\n".join(lines) + "\n")
         tpath = os.path.join(a.out, "hbm_traffic.json")
         cur = json.load(open(tpath)) if os.path.exists(tpath) else {}
         cur[w] = tj
@@ -251,7 +255,7 @@ def main():
             name = "dW (all weight gradients)" if role0.startswith("dw") else role0
             lines.append(f"| {name} `{short(k)}` | {acc['SQ_VALU_MFMA_BUSY_CYCLES']/n/b/4:.2f} | {acc['SQ_WAIT_ANY']/max(acc['SQ_WAVE_CYCLES'],1):.2f} | "
                          f"{acc['SQ_LDS_BANK_CONFLICT']/n/b:.3f} | {acc['SQ_VMEM_TA_ADDR_FIFO_FULL']/n/b:.3f} | {acc['SQ_INSTS_VALU_MFMA_MOPS_BF16']/n:.0f} |")
-        open(os.path.join(a.out, f"{w}_gemm_mfma_busy.md"), "w").write("\n".join(lines) + "\n")
+        open(os.path.join(a.out, f"{tag}_gemm_mfma_busy.md"), "w").write("\n".join(lines) + "\n")
 
 
 if __name__ == "__main__":
