@@ -355,16 +355,27 @@ __global__ __launch_bounds__(NW * 64) void route_mfma_kernel(
       if (more) split_a(a, raw);
     }
   } else {
+    // one or two expert tiles: a 16-byte piece of x is split into its operands right before its MFMAs (fp16:
+    // keeps the registers of the second term out of the loop's budget; with two tiles it is split twice)
     for (int kb = wave; kb < nkb; kb += NW) {
       uint4 raw[TT][4];
-      rt_bf16x8 a[TT][4][XT];
       load_a(raw, kb);
-      split_a(a, raw);
 #pragma unroll
       for (int nt = 0; nt < NET; ++nt) {
         rt_bf16x8 b[8];
         load_b(b, kb, nt);
-        mfmas(a, b, nt);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) {
+            rt_bf16x8 t[XT];
+            XTerms<T>::split(raw[tt][s], t);
+#pragma unroll
+            for (int xt = 0; xt < XT; ++xt) {
+              acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t[xt], b[s * 2], acc[tt][nt], 0, 0, 0);
+              acc[tt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t[xt], b[s * 2 + 1], acc[tt][nt], 0, 0, 0);
+            }
+          }
       }
     }
   }
